@@ -1,0 +1,178 @@
+/*
+ * ftar.h - C ABI of the MI355X (gfx950) GPU data path of the Fault Tolerant
+ * All Reduce (FTAR): the masked multi-replica gradient reduction.
+ *
+ * Division of labour (paper section 4.2, "CPU-GPU interaction"): the CPU is the
+ * control plane - it decides who is in the group (the paper's reconfig
+ * function; here `live_mask`) and the chunk schedule (here `ftar_plan`); the
+ * GPU is the data plane - it runs the per-chunk reduce and copy (here the
+ * kernels behind the *_step and reduce_* calls).  No call in this header ever
+ * takes a membership decision on the device.
+ *
+ * One GPU, simulated replicas: replica r's gradient is the device buffer
+ * bufs[r].  The union of all ranks' send/receive buffers of the paper's ring
+ * collapses to one fp32 buffer `acc` holding, for every portion, the partial
+ * sum that is in flight.
+ *
+ * Conventions for every call
+ *   - `bufs` is a HOST array of n_replicas DEVICE pointers indexed by replica
+ *     id.  Entries of dead replicas are never dereferenced and may be NULL.
+ *     The library copies what it needs before returning; the caller may free
+ *     the host array at once.  All device memory is caller-owned; no call
+ *     allocates or frees device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Compute calls only enqueue work on it and return; they never
+ *     synchronise.  Calls on one stream are ordered by the stream.
+ *   - Device pointers must be aligned to their element size.  When every
+ *     pointer (and every portion or bucket boundary) is 16-byte aligned the
+ *     128-bit vector kernels run, otherwise an element-wise kernel of the same
+ *     arithmetic runs.
+ *   - Errors are return codes; nothing aborts or throws across this boundary.
+ *     On any error no work has been enqueued and no state has changed.
+ *     Following the paper's split (section 4.2, "Timeout and error handling"):
+ *     caller errors and device errors are not retryable; the retryable class
+ *     is reserved for a membership change while work is queued.
+ *   - Arithmetic: inputs are widened exactly to fp32; sums are fp32 additions
+ *     in a fixed order; the mean is ONE multiplication by
+ *     scale = 1.0f/(float)n_live (one correctly rounded fp32 division, done on
+ *     the host); bf16 outputs are rounded once, to nearest even.  No fused
+ *     multiply-add, no flush of denormals.
+ */
+#ifndef FTAR_H_
+#define FTAR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FTAR_MAX_REPLICAS 64
+
+typedef struct ftar_plan_s ftar_plan_t; /* opaque, host memory owned by the library */
+
+typedef enum { FTAR_F32 = 0, FTAR_BF16 = 1 } ftar_dtype_t;
+
+typedef enum {
+  FTAR_OK = 0,
+  /* caller errors */
+  FTAR_ERR_INVALID_ARG = 1, /* null pointer, n_replicas outside [1,64], count == 0,
+                               chunk_elems == 0, unknown dtype, misaligned pointer */
+  FTAR_ERR_NO_LIVE = 2,     /* live_mask has no bit set below n_replicas */
+  FTAR_ERR_BAD_MASK = 3,    /* live_mask has a bit set at or above n_replicas */
+  FTAR_ERR_BAD_STEP = 4,    /* step outside [0, n_live-2] */
+  /* retryable: re-plan over the new group and restart the schedule */
+  FTAR_ERR_STALE_PLAN = 16, /* reserved */
+  /* fatal: the HIP runtime reported a failure */
+  FTAR_ERR_DEVICE = 32
+} ftar_status_t;
+
+/* ---------------------------------------------------------------------------
+ * ftar_plan - the CPU side of the ring schedule.
+ * Paper: section 4.2 - reconfig decides the group ("CPU-GPU interaction"); the
+ * ring has a ReduceScatter and an AllGather phase of N-1 steps each and replica
+ * i starts by sending its i-th portion to its right neighbour ("Ring
+ * algorithm"); data moves in fixed-size chunks.
+ *
+ * n_replicas   number of replica slots, 1..64
+ * live_mask    bit r set = replica r takes part; N = popcount
+ * count        elements per replica buffer (> 0)
+ * chunk_elems  chunk size in elements (> 0); portion boundaries fall on chunk
+ *              boundaries: portion k = [min(count, floor(k*n_chunks/N)*chunk_elems),
+ *              ...next), n_chunks = ceil(count/chunk_elems)
+ * Ring position p is the p-th live replica in ascending index order; the right
+ * neighbour of p is (p+1) mod N.
+ * Returns a plan (default dtype FTAR_BF16) or NULL; ftar_last_error() tells why.
+ * The plan is immutable apart from ftar_plan_set_dtype, holds no device
+ * memory, and the same arguments always give the same plan.
+ * A membership change is handled by destroying the plan, making a new one and
+ * restarting from ReduceScatter step 0; this is sound as long as the last
+ * ReduceScatter step of the old plan has not been enqueued, because until then
+ * no replica buffer has been written.
+ */
+ftar_plan_t* ftar_plan(int n_replicas, uint64_t live_mask, size_t count, size_t chunk_elems);
+void ftar_plan_destroy(ftar_plan_t* plan);
+
+/* Element type of the replica buffers for the step calls (input and output type are the same). */
+ftar_status_t ftar_plan_set_dtype(ftar_plan_t* plan, ftar_dtype_t dtype);
+
+int ftar_plan_n_live(const ftar_plan_t* plan);     /* N; 0 if plan is NULL */
+int ftar_plan_n_steps(const ftar_plan_t* plan);    /* N-1, the steps of each phase */
+size_t ftar_plan_acc_bytes(const ftar_plan_t* plan); /* count * 4: size of `acc` */
+float ftar_plan_scale(const ftar_plan_t* plan);    /* 1.0f/(float)N */
+/* Portion k in [0,N): element range [*begin,*end) and the replica that holds its
+ * finished value after the ReduceScatter phase (the replica at ring position k-1). */
+ftar_status_t ftar_plan_segment(const ftar_plan_t* plan, int k, size_t* begin, size_t* end,
+                                int* owner_replica);
+
+/* ---------------------------------------------------------------------------
+ * ftar_reduce_step - one ReduceScatter step, for all N portions at once (each
+ * portion stands for the work of a different rank at that step).
+ * Paper: section 4.2, "Ring algorithm" (reduce on arrival, forward) and
+ * "Optimizations" (intermediate results go to the send buffer only; the last
+ * step's result goes to the local data buffer, fused into the same kernel).
+ * With x_p = fp32 image of the buffer of the replica at ring position p, for i in portion k:
+ *   step 0 (N >= 3)      acc[i] = x_k[i] + x_{k+1}[i]
+ *   step s, 1..N-3       acc[i] = acc[i] + x_{k+s+1}[i]
+ *   step N-2 (N >= 3)    o = k+N-1:  buf_o[i] = cvt(scale * (acc[i] + x_o[i]))   (in place)
+ *   N == 2, step 0       o = k+1:    buf_o[i] = cvt(scale * (x_k[i] + x_o[i]))   (acc unused)
+ * (position indices mod N).  N == 1 has no steps.
+ * acc: device, ftar_plan_acc_bytes() bytes, 16-byte aligned; contents are
+ * defined only between step 0 and step N-2 of one plan.  May be NULL when N == 2.
+ */
+ftar_status_t ftar_reduce_step(const ftar_plan_t* plan, int step, void* const* bufs, float* acc,
+                               void* stream);
+
+/* ---------------------------------------------------------------------------
+ * ftar_allgather_step - one AllGather step, for all N portions at once.
+ * Paper: section 4.2, "Ring algorithm" (each GPU forwards its finished portion
+ * to its right neighbour, receivers forward what they received) and
+ * "Optimizations" (received data is stored to the local data buffer).
+ *   step t, 0..N-2: for i in portion k: buf_{k+t}[i] = buf_{k+t-1}[i]   (bit copy; positions mod N)
+ */
+ftar_status_t ftar_allgather_step(const ftar_plan_t* plan, int step, void* const* bufs,
+                                  void* stream);
+
+/* ---------------------------------------------------------------------------
+ * ftar_reduce_masked - the whole reduction in one pass: what the all-reduce
+ * over the live group must deliver (paper section 4.1: the sum of the
+ * participants' gradients; the mean by this library's convention).
+ *   out[i] = cvt(scale * (((x_a[i] + x_b[i]) + x_c[i]) + ...)),  a < b < c ... the live replicas
+ * The sum starts from the first live value, so a single live replica is the
+ * bitwise identity.  out: device, count elements of `dtype`; it may be equal to
+ * bufs[r] of a live replica (same-thread read then write) but must not
+ * partially overlap any input.
+ */
+ftar_status_t ftar_reduce_masked(const void* const* bufs, int n_replicas, uint64_t live_mask,
+                                 size_t count, ftar_dtype_t dtype, void* out, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * ftar_reduce_masked_bucketed - ftar_reduce_masked with a live mask of its own
+ * for every bucket of bucket_elems consecutive elements (the last bucket may be
+ * short), in one launch per 256 buckets.  Models replicas that leave and rejoin
+ * between the iterations of one all-reduce (paper section 4.2: FTAR may run for
+ * several iterations, each exchanging a portion of the gradients; membership is
+ * decided by the CPU before each).  Same arithmetic as calling
+ * ftar_reduce_masked once per bucket with masks[b]; scale is per bucket.
+ * masks: HOST array of ceil(count/bucket_elems) masks, each valid for n_replicas.
+ */
+ftar_status_t ftar_reduce_masked_bucketed(const void* const* bufs, int n_replicas,
+                                          const uint64_t* masks, size_t n_buckets,
+                                          size_t bucket_elems, size_t count, ftar_dtype_t dtype,
+                                          void* out, void* stream);
+
+/* --------------------------------------------------------------------------- */
+ftar_status_t ftar_last_error(void);          /* status of this thread's last failing call */
+int ftar_status_is_retryable(ftar_status_t s);
+const char* ftar_status_str(ftar_status_t s); /* static string */
+
+/* Launch shape, for measurement only (results never depend on it).
+ * blocks_per_cu: workgroups launched per compute unit (0 = default);
+ * flags: bit 0 = plain instead of non-temporal loads and stores. */
+void ftar_set_tuning(int blocks_per_cu, int flags);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FTAR_H_ */

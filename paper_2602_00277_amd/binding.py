@@ -1,0 +1,271 @@
+"""Thin Python binding over the C ABI in include/ftar.h (same names, argument
+marshalling only; every step of the path runs in the HIP kernels of libftar.so).
+
+Buffers are torch tensors living on the GPU (torch is used for device memory and
+streams only); each wrapper passes their data pointers and the current torch
+stream's handle to the C call and raises FtarError on a non-zero status.
+There is no fallback: if libftar.so is missing or fails to load, the first call
+raises.
+"""
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libftar.so")
+
+FTAR_F32 = 0
+FTAR_BF16 = 1
+
+FTAR_OK = 0
+FTAR_ERR_INVALID_ARG = 1
+FTAR_ERR_NO_LIVE = 2
+FTAR_ERR_BAD_MASK = 3
+FTAR_ERR_BAD_STEP = 4
+FTAR_ERR_STALE_PLAN = 16
+FTAR_ERR_DEVICE = 32
+
+# every symbol include/ftar.h declares
+EXPORTS = [
+    "ftar_plan", "ftar_plan_destroy", "ftar_plan_set_dtype", "ftar_plan_n_live",
+    "ftar_plan_n_steps", "ftar_plan_acc_bytes", "ftar_plan_scale", "ftar_plan_segment",
+    "ftar_reduce_step", "ftar_allgather_step", "ftar_reduce_masked",
+    "ftar_reduce_masked_bucketed", "ftar_last_error", "ftar_status_is_retryable",
+    "ftar_status_str", "ftar_set_tuning",
+]
+
+_lib = None
+
+
+class FtarError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().ftar_status_str(status).decode()
+        super().__init__("%s: %s (status %d)" % (where, msg, status))
+
+
+def lib():
+    """Loads libftar.so once.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libftar.so is not built: run `python -m paper_2602_00277_amd.build` "
+                          "(there is no fallback path)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, u64, sz, ci = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_size_t, ctypes.c_int
+    L.ftar_plan.restype = vp
+    L.ftar_plan.argtypes = [ci, u64, sz, sz]
+    L.ftar_plan_destroy.restype = None
+    L.ftar_plan_destroy.argtypes = [vp]
+    L.ftar_plan_set_dtype.restype = ci
+    L.ftar_plan_set_dtype.argtypes = [vp, ci]
+    L.ftar_plan_n_live.restype = ci
+    L.ftar_plan_n_live.argtypes = [vp]
+    L.ftar_plan_n_steps.restype = ci
+    L.ftar_plan_n_steps.argtypes = [vp]
+    L.ftar_plan_acc_bytes.restype = sz
+    L.ftar_plan_acc_bytes.argtypes = [vp]
+    L.ftar_plan_scale.restype = ctypes.c_float
+    L.ftar_plan_scale.argtypes = [vp]
+    L.ftar_plan_segment.restype = ci
+    L.ftar_plan_segment.argtypes = [vp, ci, ctypes.POINTER(sz), ctypes.POINTER(sz),
+                                    ctypes.POINTER(ci)]
+    L.ftar_reduce_step.restype = ci
+    L.ftar_reduce_step.argtypes = [vp, ci, vp, vp, vp]
+    L.ftar_allgather_step.restype = ci
+    L.ftar_allgather_step.argtypes = [vp, ci, vp, vp]
+    L.ftar_reduce_masked.restype = ci
+    L.ftar_reduce_masked.argtypes = [vp, ci, u64, sz, ci, vp, vp]
+    L.ftar_reduce_masked_bucketed.restype = ci
+    L.ftar_reduce_masked_bucketed.argtypes = [vp, ci, vp, sz, sz, sz, ci, vp, vp]
+    L.ftar_last_error.restype = ci
+    L.ftar_last_error.argtypes = []
+    L.ftar_status_is_retryable.restype = ci
+    L.ftar_status_is_retryable.argtypes = [ci]
+    L.ftar_status_str.restype = ctypes.c_char_p
+    L.ftar_status_str.argtypes = [ci]
+    L.ftar_set_tuning.restype = None
+    L.ftar_set_tuning.argtypes = [ci, ci]
+    _lib = L
+    return L
+
+
+def dtype_code(dtype: torch.dtype) -> int:
+    if dtype == torch.float32:
+        return FTAR_F32
+    if dtype == torch.bfloat16:
+        return FTAR_BF16
+    raise TypeError("FTAR buffers are float32 or bfloat16, not %s" % dtype)
+
+
+def _ptr_array(bufs: Sequence[Optional[torch.Tensor]]):
+    """Host array of device pointers; None (a dead replica without a buffer) becomes NULL."""
+    arr = (ctypes.c_void_p * len(bufs))()
+    for r, b in enumerate(bufs):
+        arr[r] = None if b is None else b.data_ptr()
+    return arr
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _check_bufs(bufs, live_mask, count=None, dtype=None):
+    for r, b in enumerate(bufs):
+        if b is None:
+            continue
+        if not b.is_cuda or not b.is_contiguous():
+            raise ValueError("replica buffer %d must be a contiguous GPU tensor" % r)
+        if dtype is not None and b.dtype != dtype:
+            raise TypeError("replica buffer %d has dtype %s, expected %s" % (r, b.dtype, dtype))
+        if count is not None and (live_mask >> r) & 1 and b.numel() < count:
+            raise ValueError("replica buffer %d is shorter than count" % r)
+
+
+class Plan:
+    """Owner of an ftar_plan_t* (destroyed with the object)."""
+
+    def __init__(self, handle: int, n_replicas: int, live_mask: int, count: int, chunk_elems: int):
+        self.handle = handle
+        self.n_replicas = n_replicas
+        self.live_mask = live_mask
+        self.count = count
+        self.chunk_elems = chunk_elems
+        self.dtype = torch.bfloat16
+
+    @property
+    def n_live(self) -> int:
+        return lib().ftar_plan_n_live(self.handle)
+
+    @property
+    def n_steps(self) -> int:
+        return lib().ftar_plan_n_steps(self.handle)
+
+    @property
+    def acc_bytes(self) -> int:
+        return lib().ftar_plan_acc_bytes(self.handle)
+
+    @property
+    def scale(self) -> float:
+        return lib().ftar_plan_scale(self.handle)
+
+    def segment(self, k: int):
+        b, e, o = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_int()
+        st = lib().ftar_plan_segment(self.handle, k, ctypes.byref(b), ctypes.byref(e), ctypes.byref(o))
+        if st != FTAR_OK:
+            raise FtarError(st, "ftar_plan_segment")
+        return b.value, e.value, o.value
+
+    def destroy(self):
+        if self.handle:
+            lib().ftar_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def ftar_plan(n_replicas: int, live_mask: int, count: int, chunk_elems: int,
+              dtype: Optional[torch.dtype] = None) -> Plan:
+    h = lib().ftar_plan(n_replicas, live_mask, count, chunk_elems)
+    if not h:
+        raise FtarError(lib().ftar_last_error(), "ftar_plan")
+    p = Plan(h, n_replicas, live_mask, count, chunk_elems)
+    if dtype is not None:
+        ftar_plan_set_dtype(p, dtype)
+    return p
+
+
+def ftar_plan_destroy(plan: Plan) -> None:
+    plan.destroy()
+
+
+def ftar_plan_set_dtype(plan: Plan, dtype: torch.dtype) -> None:
+    st = lib().ftar_plan_set_dtype(plan.handle, dtype_code(dtype))
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_plan_set_dtype")
+    plan.dtype = dtype
+
+
+def ftar_reduce_step(plan: Plan, step: int, bufs: Sequence[Optional[torch.Tensor]],
+                     acc: Optional[torch.Tensor], stream=None) -> None:
+    _check_bufs(bufs, plan.live_mask, plan.count, plan.dtype)
+    if len(bufs) != plan.n_replicas:
+        raise ValueError("bufs must have one entry per replica slot")
+    if acc is not None and (acc.dtype != torch.float32 or acc.numel() < plan.count or not acc.is_cuda):
+        raise ValueError("acc must be a GPU float32 tensor of at least count elements")
+    st = lib().ftar_reduce_step(plan.handle, step, _ptr_array(bufs),
+                                None if acc is None else acc.data_ptr(), _stream_handle(stream))
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_reduce_step")
+
+
+def ftar_allgather_step(plan: Plan, step: int, bufs: Sequence[Optional[torch.Tensor]],
+                        stream=None) -> None:
+    _check_bufs(bufs, plan.live_mask, plan.count, plan.dtype)
+    if len(bufs) != plan.n_replicas:
+        raise ValueError("bufs must have one entry per replica slot")
+    st = lib().ftar_allgather_step(plan.handle, step, _ptr_array(bufs), _stream_handle(stream))
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_allgather_step")
+
+
+def ftar_reduce_masked(bufs: Sequence[Optional[torch.Tensor]], live_mask: int, out: torch.Tensor,
+                       count: Optional[int] = None, stream=None) -> torch.Tensor:
+    count = out.numel() if count is None else count
+    _check_bufs(list(bufs) + [out], live_mask | (1 << len(bufs)), count, out.dtype)
+    st = lib().ftar_reduce_masked(_ptr_array(bufs), len(bufs), live_mask, count,
+                                  dtype_code(out.dtype), out.data_ptr(), _stream_handle(stream))
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_reduce_masked")
+    return out
+
+
+def ftar_reduce_masked_bucketed(bufs: Sequence[Optional[torch.Tensor]], masks: Sequence[int],
+                                bucket_elems: int, out: torch.Tensor,
+                                count: Optional[int] = None, stream=None) -> torch.Tensor:
+    count = out.numel() if count is None else count
+    any_live = 0
+    for m in masks:
+        any_live |= m
+    _check_bufs(list(bufs) + [out], any_live | (1 << len(bufs)), count, out.dtype)
+    marr = (ctypes.c_uint64 * len(masks))(*masks)
+    st = lib().ftar_reduce_masked_bucketed(_ptr_array(bufs), len(bufs), marr, len(masks),
+                                           bucket_elems, count, dtype_code(out.dtype),
+                                           out.data_ptr(), _stream_handle(stream))
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_reduce_masked_bucketed")
+    return out
+
+
+def ftar_set_tuning(blocks_per_cu: int = 0, flags: int = 0) -> None:
+    lib().ftar_set_tuning(blocks_per_cu, flags)
+
+
+def ftar_status_is_retryable(status: int) -> bool:
+    return bool(lib().ftar_status_is_retryable(status))
+
+
+def ftar_status_str(status: int) -> str:
+    return lib().ftar_status_str(status).decode()
+
+
+def ftar_last_error() -> int:
+    return lib().ftar_last_error()
+
+
+def ring_allreduce(plan: Plan, bufs: Sequence[Optional[torch.Tensor]], acc: Optional[torch.Tensor],
+                   stream=None) -> None:
+    """The full schedule as the caller would drive it: N-1 ReduceScatter then N-1 AllGather calls."""
+    for s in range(plan.n_steps):
+        ftar_reduce_step(plan, s, bufs, acc, stream)
+    for t in range(plan.n_steps):
+        ftar_allgather_step(plan, t, bufs, stream)

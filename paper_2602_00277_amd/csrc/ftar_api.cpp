@@ -1,0 +1,303 @@
+// Host side of the FTAR data path: the planner (the CPU's part of the ring
+// schedule), argument validation and the C ABI declared in include/ftar.h.
+// Paper section 4.2: the CPU owns membership and control ("CPU-GPU
+// interaction"), the ring is N-1 ReduceScatter plus N-1 AllGather steps with
+// replica i first sending portion i to its right neighbour ("Ring algorithm"),
+// errors are either reported for a retry or fatal ("Timeout and error handling").
+
+#include <atomic>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "ftar_internal.h"
+
+namespace ftar {
+namespace {
+
+constexpr uint32_t kPlanMagic = 0x46544152u;  // "FTAR"
+
+thread_local ftar_status_t t_last_error = FTAR_OK;
+
+ftar_status_t fail(ftar_status_t s) {
+  t_last_error = s;
+  return s;
+}
+
+std::atomic<int> g_blocks_per_cu{0};
+std::atomic<int> g_flags{0};
+std::atomic<bool> g_env_read{false};
+
+void read_env_once() {
+  if (g_env_read.exchange(true)) return;
+  if (const char* e = std::getenv("FTAR_BLOCKS_PER_CU")) g_blocks_per_cu = std::atoi(e);
+  if (const char* e = std::getenv("FTAR_FLAGS")) g_flags = std::atoi(e);
+}
+
+// Live replicas in ascending index order = ring positions 0..N-1.
+ftar_status_t resolve_mask(int n_replicas, uint64_t live_mask, int* ring, int* n_live) {
+  if (n_replicas < 1 || n_replicas > kMaxReplicas) return FTAR_ERR_INVALID_ARG;
+  if (n_replicas < 64 && (live_mask >> n_replicas) != 0) return FTAR_ERR_BAD_MASK;
+  int N = 0;
+  for (int r = 0; r < n_replicas; ++r)
+    if ((live_mask >> r) & 1ull) ring[N++] = r;
+  if (N == 0) return FTAR_ERR_NO_LIVE;
+  *n_live = N;
+  return FTAR_OK;
+}
+
+size_t elem_size(ftar_dtype_t d) { return d == FTAR_F32 ? 4 : 2; }
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+}  // namespace
+
+Tuning current_tuning() {
+  read_env_once();
+  return Tuning{g_blocks_per_cu.load(), g_flags.load()};
+}
+
+int device_cu_count() {
+  static thread_local int cached_dev = -1;
+  static thread_local int cached_cu = 0;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (dev != cached_dev) {
+    int cu = 0;
+    if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu < 1)
+      cu = 256;
+    cached_dev = dev;
+    cached_cu = cu;
+  }
+  return cached_cu;
+}
+
+}  // namespace ftar
+
+using namespace ftar;
+
+struct ftar_plan_s {
+  uint32_t magic;
+  int n_replicas;
+  uint64_t live_mask;
+  size_t count;
+  size_t chunk_elems;
+  int n_live;
+  int ring[kMaxReplicas];  // ring position -> replica id
+  float scale;             // 1.0f/(float)n_live
+  ftar_dtype_t dtype;
+  SegTable seg;            // portion boundaries, n_live+1 entries
+};
+
+extern "C" {
+
+ftar_plan_t* ftar_plan(int n_replicas, uint64_t live_mask, size_t count, size_t chunk_elems) {
+  int ring[kMaxReplicas];
+  int N = 0;
+  ftar_status_t s = resolve_mask(n_replicas, live_mask, ring, &N);
+  if (s != FTAR_OK) { fail(s); return nullptr; }
+  if (count == 0 || chunk_elems == 0) { fail(FTAR_ERR_INVALID_ARG); return nullptr; }
+  ftar_plan_t* p = new (std::nothrow) ftar_plan_t;
+  if (!p) { fail(FTAR_ERR_INVALID_ARG); return nullptr; }
+  std::memset(p, 0, sizeof(*p));
+  p->magic = kPlanMagic;
+  p->n_replicas = n_replicas;
+  p->live_mask = live_mask;
+  p->count = count;
+  p->chunk_elems = chunk_elems;
+  p->n_live = N;
+  std::memcpy(p->ring, ring, sizeof(int) * N);
+  p->scale = 1.0f / static_cast<float>(N);
+  p->dtype = FTAR_BF16;
+  // Portions are whole chunks, as even as whole chunks allow: portion k starts at chunk
+  // floor(k * n_chunks / N).  Only the very last chunk can be short.
+  const size_t n_chunks = count / chunk_elems + (count % chunk_elems ? 1 : 0);
+  for (int k = 0; k < N; ++k) {
+    const unsigned __int128 first_chunk = static_cast<unsigned __int128>(n_chunks) * k / N;
+    const unsigned __int128 b = first_chunk * chunk_elems;
+    p->seg.begin[k] = b < count ? static_cast<unsigned long long>(b) : count;
+  }
+  p->seg.begin[N] = count;
+  return p;
+}
+
+void ftar_plan_destroy(ftar_plan_t* plan) {
+  if (!plan || plan->magic != kPlanMagic) return;
+  plan->magic = 0;
+  delete plan;
+}
+
+static bool plan_ok(const ftar_plan_t* p) { return p && p->magic == kPlanMagic; }
+
+ftar_status_t ftar_plan_set_dtype(ftar_plan_t* plan, ftar_dtype_t dtype) {
+  if (!plan_ok(plan) || (dtype != FTAR_F32 && dtype != FTAR_BF16)) return fail(FTAR_ERR_INVALID_ARG);
+  plan->dtype = dtype;
+  return FTAR_OK;
+}
+
+int ftar_plan_n_live(const ftar_plan_t* plan) { return plan_ok(plan) ? plan->n_live : 0; }
+int ftar_plan_n_steps(const ftar_plan_t* plan) { return plan_ok(plan) ? plan->n_live - 1 : 0; }
+size_t ftar_plan_acc_bytes(const ftar_plan_t* plan) { return plan_ok(plan) ? plan->count * 4 : 0; }
+float ftar_plan_scale(const ftar_plan_t* plan) { return plan_ok(plan) ? plan->scale : 0.0f; }
+
+ftar_status_t ftar_plan_segment(const ftar_plan_t* plan, int k, size_t* begin, size_t* end,
+                                int* owner_replica) {
+  if (!plan_ok(plan) || k < 0 || k >= plan->n_live) return fail(FTAR_ERR_INVALID_ARG);
+  if (begin) *begin = plan->seg.begin[k];
+  if (end) *end = plan->seg.begin[k + 1];
+  if (owner_replica) *owner_replica = plan->ring[(k + plan->n_live - 1) % plan->n_live];
+  return FTAR_OK;
+}
+
+// Gathers the live buffers in ring order and decides between the vector and the
+// element-wise kernels.  Vector kernels need every live pointer 16-byte aligned and
+// every portion to start on a multiple of 8 elements.
+static ftar_status_t ring_table(const ftar_plan_t* plan, void* const* bufs, PtrTable* tab, bool* vec) {
+  const size_t es = elem_size(plan->dtype);
+  bool v = true;
+  for (int p = 0; p < plan->n_live; ++p) {
+    void* b = bufs[plan->ring[p]];
+    if (!b || !aligned(b, es)) return FTAR_ERR_INVALID_ARG;
+    if (!aligned(b, 16)) v = false;
+    tab->p[p] = b;
+  }
+  for (int k = 1; k < plan->n_live; ++k)
+    if (plan->seg.begin[k] % 8 != 0 && plan->seg.begin[k] != plan->count) v = false;
+  *vec = v;
+  return FTAR_OK;
+}
+
+ftar_status_t ftar_reduce_step(const ftar_plan_t* plan, int step, void* const* bufs, float* acc,
+                               void* stream) {
+  if (!plan_ok(plan) || !bufs) return fail(FTAR_ERR_INVALID_ARG);
+  const int N = plan->n_live;
+  if (step < 0 || step > N - 2) return fail(FTAR_ERR_BAD_STEP);
+  PtrTable tab;
+  std::memset(&tab, 0, sizeof(tab));
+  bool vec = true;
+  ftar_status_t s = ring_table(plan, bufs, &tab, &vec);
+  if (s != FTAR_OK) return fail(s);
+  RingMode mode;
+  if (N == 2) mode = kRsOnly;
+  else if (step == 0) mode = kRsFirst;
+  else if (step == N - 2) mode = kRsLast;
+  else mode = kRsMid;
+  if (mode != kRsOnly) {
+    if (!acc || !aligned(acc, 4)) return fail(FTAR_ERR_INVALID_ARG);
+    if (!aligned(acc, 16)) vec = false;
+  }
+  hipError_t e = launch_ring_reduce(mode, tab, N, step, plan->seg, plan->dtype, vec, acc, plan->scale,
+                                    static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
+}
+
+ftar_status_t ftar_allgather_step(const ftar_plan_t* plan, int step, void* const* bufs,
+                                  void* stream) {
+  if (!plan_ok(plan) || !bufs) return fail(FTAR_ERR_INVALID_ARG);
+  const int N = plan->n_live;
+  if (step < 0 || step > N - 2) return fail(FTAR_ERR_BAD_STEP);
+  PtrTable tab;
+  std::memset(&tab, 0, sizeof(tab));
+  bool vec = true;
+  ftar_status_t s = ring_table(plan, bufs, &tab, &vec);
+  if (s != FTAR_OK) return fail(s);
+  hipError_t e = launch_ring_allgather(tab, N, step, plan->seg, plan->dtype, vec,
+                                       static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
+}
+
+ftar_status_t ftar_reduce_masked(const void* const* bufs, int n_replicas, uint64_t live_mask,
+                                 size_t count, ftar_dtype_t dtype, void* out, void* stream) {
+  if (!bufs || !out || count == 0 || (dtype != FTAR_F32 && dtype != FTAR_BF16))
+    return fail(FTAR_ERR_INVALID_ARG);
+  int ring[kMaxReplicas];
+  int N = 0;
+  ftar_status_t s = resolve_mask(n_replicas, live_mask, ring, &N);
+  if (s != FTAR_OK) return fail(s);
+  const size_t es = elem_size(dtype);
+  if (!aligned(out, es)) return fail(FTAR_ERR_INVALID_ARG);
+  bool vec = aligned(out, 16);
+  PtrTable tab;
+  std::memset(&tab, 0, sizeof(tab));
+  for (int j = 0; j < N; ++j) {
+    const void* b = bufs[ring[j]];
+    if (!b || !aligned(b, es)) return fail(FTAR_ERR_INVALID_ARG);
+    if (!aligned(b, 16)) vec = false;
+    tab.p[j] = const_cast<void*>(b);
+  }
+  hipError_t e = launch_reduce_masked(tab, N, count, dtype, vec, out, 1.0f / static_cast<float>(N),
+                                      static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
+}
+
+ftar_status_t ftar_reduce_masked_bucketed(const void* const* bufs, int n_replicas,
+                                          const uint64_t* masks, size_t n_buckets,
+                                          size_t bucket_elems, size_t count, ftar_dtype_t dtype,
+                                          void* out, void* stream) {
+  if (!bufs || !out || !masks || count == 0 || bucket_elems == 0 ||
+      (dtype != FTAR_F32 && dtype != FTAR_BF16))
+    return fail(FTAR_ERR_INVALID_ARG);
+  if (n_replicas < 1 || n_replicas > kMaxReplicas) return fail(FTAR_ERR_INVALID_ARG);
+  if (n_buckets != count / bucket_elems + (count % bucket_elems ? 1 : 0))
+    return fail(FTAR_ERR_INVALID_ARG);
+  const size_t es = elem_size(dtype);
+  if (!aligned(out, es)) return fail(FTAR_ERR_INVALID_ARG);
+  bool vec = aligned(out, 16) && (bucket_elems % 8 == 0 || n_buckets == 1);
+  uint64_t any_live = 0;
+  for (size_t b = 0; b < n_buckets; ++b) {
+    int ring[kMaxReplicas];
+    int N = 0;
+    ftar_status_t s = resolve_mask(n_replicas, masks[b], ring, &N);
+    if (s != FTAR_OK) return fail(s);
+    any_live |= masks[b];
+  }
+  PtrTable tab;
+  std::memset(&tab, 0, sizeof(tab));
+  for (int r = 0; r < n_replicas; ++r) {
+    if (!((any_live >> r) & 1ull)) continue;  // never live in any bucket: never dereferenced
+    const void* b = bufs[r];
+    if (!b || !aligned(b, es)) return fail(FTAR_ERR_INVALID_ARG);
+    if (!aligned(b, 16)) vec = false;
+    tab.p[r] = const_cast<void*>(b);
+  }
+  ScaleTable scales;
+  scales.s[0] = 0.0f;
+  for (int n = 1; n <= kMaxReplicas; ++n) scales.s[n] = 1.0f / static_cast<float>(n);
+  for (size_t b0 = 0; b0 < n_buckets; b0 += kMaxBucketsPerLaunch) {
+    const size_t nb = n_buckets - b0 < static_cast<size_t>(kMaxBucketsPerLaunch)
+                          ? n_buckets - b0 : static_cast<size_t>(kMaxBucketsPerLaunch);
+    BucketTable bt;
+    std::memset(&bt, 0, sizeof(bt));
+    for (size_t i = 0; i < nb; ++i) bt.mask[i] = masks[b0 + i];
+    hipError_t e = launch_reduce_bucketed(tab, n_replicas, bt, static_cast<int>(nb), b0 * bucket_elems,
+                                          bucket_elems, count, scales, dtype, vec, out,
+                                          static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(FTAR_ERR_DEVICE);
+  }
+  return FTAR_OK;
+}
+
+ftar_status_t ftar_last_error(void) { return t_last_error; }
+
+int ftar_status_is_retryable(ftar_status_t s) { return s == FTAR_ERR_STALE_PLAN ? 1 : 0; }
+
+const char* ftar_status_str(ftar_status_t s) {
+  switch (s) {
+    case FTAR_OK: return "ok";
+    case FTAR_ERR_INVALID_ARG: return "invalid argument";
+    case FTAR_ERR_NO_LIVE: return "live mask selects no replica";
+    case FTAR_ERR_BAD_MASK: return "live mask has a bit at or above n_replicas";
+    case FTAR_ERR_BAD_STEP: return "step outside [0, n_live-2]";
+    case FTAR_ERR_STALE_PLAN: return "plan is stale: re-plan over the new group and restart";
+    case FTAR_ERR_DEVICE: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+void ftar_set_tuning(int blocks_per_cu, int flags) {
+  read_env_once();
+  g_blocks_per_cu = blocks_per_cu < 0 ? 0 : blocks_per_cu;
+  g_flags = flags;
+}
+
+}  // extern "C"

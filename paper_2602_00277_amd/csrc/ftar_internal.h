@@ -1,0 +1,73 @@
+// Internal interface between the host API (ftar_api.cpp, ftar_plan.cpp) and the
+// kernel launchers (ftar_kernels.hip).  Not installed; the public surface is
+// include/ftar.h.
+#ifndef FTAR_INTERNAL_H_
+#define FTAR_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ftar.h"
+
+namespace ftar {
+
+constexpr int kMaxReplicas = FTAR_MAX_REPLICAS;
+constexpr int kMaxBucketsPerLaunch = 256;
+
+// Compact pointer table: the live-mask indirection already resolved on the CPU.
+// Passed to the kernels by value (kernel-argument segment) and staged in LDS there.
+struct PtrTable {
+  void* p[kMaxReplicas];
+};
+
+// Portion boundaries in elements, N+1 entries used.
+struct SegTable {
+  unsigned long long begin[kMaxReplicas + 1];
+};
+
+struct BucketTable {
+  unsigned long long mask[kMaxBucketsPerLaunch];
+};
+
+// 1.0f/(float)N for N = 0..64, computed on the host (entry 0 unused).
+struct ScaleTable {
+  float s[kMaxReplicas + 1];
+};
+
+enum RingMode {
+  kRsFirst = 0,  // acc = x_k + x_{k+1}
+  kRsMid = 1,    // acc = acc + x_{k+s+1}
+  kRsLast = 2,   // buf_o = cvt(scale * (acc + x_o)), o = k+N-1
+  kRsOnly = 3,   // N == 2: buf_o = cvt(scale * (x_k + x_o)), o = k+1
+};
+
+struct Tuning {
+  int blocks_per_cu;  // 0 = default
+  int flags;          // bit 0: plain (temporal) loads/stores
+};
+
+Tuning current_tuning();
+int device_cu_count();  // of the current device; cached
+
+// All launchers enqueue on `stream` and return hipGetLastError().
+// `vec` selects the 128-bit vector kernels (caller has checked alignment).
+hipError_t launch_reduce_masked(const PtrTable& live, int n_live, size_t count, ftar_dtype_t dtype,
+                                bool vec, void* out, float scale, hipStream_t stream);
+
+hipError_t launch_reduce_bucketed(const PtrTable& all, int n_replicas, const BucketTable& masks,
+                                  int n_buckets, size_t first_elem, size_t bucket_elems,
+                                  size_t count, const ScaleTable& scales, ftar_dtype_t dtype,
+                                  bool vec, void* out, hipStream_t stream);
+
+// ring: table of the N live buffers in ring order
+hipError_t launch_ring_reduce(RingMode mode, const PtrTable& ring, int n_live, int step,
+                              const SegTable& seg, ftar_dtype_t dtype, bool vec, float* acc,
+                              float scale, hipStream_t stream);
+
+hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, const SegTable& seg,
+                                 ftar_dtype_t dtype, bool vec, hipStream_t stream);
+
+}  // namespace ftar
+
+#endif  // FTAR_INTERNAL_H_

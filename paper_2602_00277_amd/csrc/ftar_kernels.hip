@@ -1,0 +1,547 @@
+// HIP kernels (gfx950 / CDNA4) of the FTAR data path and their launchers.
+//
+// Everything here is a streaming, HBM-bandwidth-bound elementwise pass: a few
+// fp32 additions per 16-byte load, no data reuse, no contraction - so no MFMA
+// and no LDS tiling of data.  What matters is (1) every wave instruction
+// touching a contiguous run of full cache lines (lane t reads 16 bytes at
+// 16*t: 1 KiB per wave instruction), (2) many independent loads in flight per
+// lane before the first use (the paper's instruction-level-parallelism remark,
+// section 4.2 "Optimizations", applied at full rather than minimal occupancy),
+// (3) a persistent grid that strides over tiles so consecutive tiles are in
+// flight on different XCDs at the same time, and (4) non-temporal accesses,
+// since no byte is touched twice.  LDS holds only the compact pointer table the
+// CPU resolved from the live mask; pointers are pulled from it into scalar
+// registers, so address arithmetic stays on the scalar unit.
+//
+// Arithmetic contract (identical in every kernel): exact widening to fp32,
+// fp32 additions in the stated order starting from the first operand, one
+// multiplication by `scale`, one rounding (nearest-even) to the output type.
+// Compiled with -ffp-contract=off; fp32 denormals are not flushed.
+
+#include "ftar_internal.h"
+
+namespace ftar {
+namespace {
+
+constexpr int kThreads = 256;          // 4 waves of 64 lanes: one per SIMD of a CU
+constexpr int kDefaultBlocksPerCu = 8;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+struct bf16 {  // storage tag: the upper 16 bits of an IEEE-754 binary32
+  uint16_t bits;
+};
+
+// Raw<T, VEC>: the register image of VEC consecutive elements of T.
+template <typename T, int VEC> struct Raw;
+template <> struct Raw<float, 4> { typedef f32x4 type; };
+template <> struct Raw<float, 1> { typedef float type; };
+template <> struct Raw<bf16, 8> { typedef u32x4 type; };
+template <> struct Raw<bf16, 4> { typedef u32x2 type; };
+template <> struct Raw<bf16, 1> { typedef uint16_t type; };
+
+template <bool NT, typename R>
+__device__ __forceinline__ R ld(const R* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+
+template <bool NT, typename R>
+__device__ __forceinline__ void st(R* p, R v) {
+  if constexpr (NT) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+
+// ---- widening: exact -------------------------------------------------------
+__device__ __forceinline__ void widen(f32x4 r, float (&x)[4]) {
+  x[0] = r[0]; x[1] = r[1]; x[2] = r[2]; x[3] = r[3];
+}
+__device__ __forceinline__ void widen(float r, float (&x)[1]) { x[0] = r; }
+__device__ __forceinline__ void widen(u32x4 r, float (&x)[8]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    x[2 * i] = __uint_as_float(r[i] << 16);
+    x[2 * i + 1] = __uint_as_float(r[i] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ void widen(u32x2 r, float (&x)[4]) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    x[2 * i] = __uint_as_float(r[i] << 16);
+    x[2 * i + 1] = __uint_as_float(r[i] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ void widen(uint16_t r, float (&x)[1]) {
+  x[0] = __uint_as_float(static_cast<uint32_t>(r) << 16);
+}
+
+// ---- narrowing: round to nearest, ties to even; NaN stays a (quiet) NaN ------
+__device__ __forceinline__ uint32_t bf16_rne(float f) {
+  const uint32_t u = __float_as_uint(f);
+  const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+  const uint32_t quiet = ((u >> 16) | 0x40u) & 0xffffu;
+  return ((u & 0x7fffffffu) > 0x7f800000u) ? quiet : rounded;
+}
+
+template <typename R, int VEC>
+__device__ __forceinline__ R narrow(const float (&x)[VEC]) {
+  if constexpr (__is_same(R, f32x4)) {
+    f32x4 r = {x[0], x[1], x[2], x[3]};
+    return r;
+  } else if constexpr (__is_same(R, float)) {
+    return x[0];
+  } else if constexpr (__is_same(R, u32x4)) {
+    u32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = bf16_rne(x[2 * i]) | (bf16_rne(x[2 * i + 1]) << 16);
+    return r;
+  } else if constexpr (__is_same(R, u32x2)) {
+    u32x2 r;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) r[i] = bf16_rne(x[2 * i]) | (bf16_rne(x[2 * i + 1]) << 16);
+    return r;
+  } else {
+    return static_cast<uint16_t>(bf16_rne(x[0]));
+  }
+}
+
+// A pointer read from LDS is the same in every lane: move it to scalar registers.
+template <typename P>
+__device__ __forceinline__ P* uniform_ptr(P* p) {
+  const uint64_t u = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u >> 32));
+  return reinterpret_cast<P*>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
+// ---- one tile of the sum --------------------------------------------------
+// For U vectors per lane (vector v + u*kThreads):
+//   a = ACC_IN ? acc_in : x_0 ;  a = a + x_j for the remaining sources in order;
+//   ACC_OUT ? acc_out = a  :  out = cvt(scale * a)
+// Every load of the tile is issued before the first use.  `out` may alias
+// src[NSRC-1] (the in-place last ReduceScatter step): a lane only ever writes
+// the elements it has itself already loaded.
+template <typename T, int VEC, int NSRC, bool ACC_IN, bool ACC_OUT, int U, bool NT>
+__device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc_in, float* acc_out,
+                                         T* out, float scale, size_t v) {
+  static_assert(!(ACC_IN || ACC_OUT) || VEC <= 4, "fp32 partials are moved 4 at a time");
+  typedef typename Raw<T, VEC>::type R;
+  typedef typename Raw<float, (VEC == 1 ? 1 : 4)>::type A;
+  R raw[U][NSRC];
+  A ain[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+#pragma unroll
+    for (int j = 0; j < NSRC; ++j)
+      raw[u][j] = ld<NT>(reinterpret_cast<const R*>(src[j]) + v + u * kThreads);
+  }
+  if constexpr (ACC_IN) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) ain[u] = ld<NT>(reinterpret_cast<const A*>(acc_in) + v + u * kThreads);
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    float a[VEC], x[VEC];
+    if constexpr (ACC_IN) widen(ain[u], a);
+    else widen(raw[u][0], a);
+#pragma unroll
+    for (int j = (ACC_IN ? 0 : 1); j < NSRC; ++j) {
+      widen(raw[u][j], x);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) a[e] = a[e] + x[e];
+    }
+    if constexpr (ACC_OUT) {
+      st<NT>(reinterpret_cast<A*>(acc_out) + v + u * kThreads, narrow<A, VEC>(a));
+    } else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) a[e] = a[e] * scale;
+      st<NT>(reinterpret_cast<R*>(out) + v + u * kThreads, narrow<R, VEC>(a));
+    }
+  }
+}
+
+// Persistent loop of block bx of gx over the `len` elements that start at the
+// given pointers: full tiles grid-strided, then one block finishes the whole
+// vectors past the last full tile and the last len % VEC single elements.
+template <typename T, int VEC, int NSRC, bool ACC_IN, bool ACC_OUT, int U, bool NT>
+__device__ __forceinline__ void sum_range(T* const (&src)[NSRC], const float* acc_in, float* acc_out,
+                                          T* out, float scale, size_t len, unsigned bx,
+                                          unsigned gx) {
+  const unsigned tid = threadIdx.x;
+  const size_t n_vec = len / VEC;
+  constexpr size_t kTile = static_cast<size_t>(kThreads) * U;
+  const size_t n_tiles = n_vec / kTile;
+  for (size_t t = bx; t < n_tiles; t += gx)
+    sum_tile<T, VEC, NSRC, ACC_IN, ACC_OUT, U, NT>(src, acc_in, acc_out, out, scale, t * kTile + tid);
+  if (bx == n_tiles % gx) {
+    for (size_t v = n_tiles * kTile + tid; v < n_vec; v += kThreads)
+      sum_tile<T, VEC, NSRC, ACC_IN, ACC_OUT, 1, NT>(src, acc_in, acc_out, out, scale, v);
+    if constexpr (VEC > 1) {
+      const size_t e = n_vec * VEC + tid;
+      if (e < len) sum_tile<T, 1, NSRC, ACC_IN, ACC_OUT, 1, NT>(src, acc_in, acc_out, out, scale, e);
+    }
+  }
+}
+
+// Vectors per lane per tile for an N-source sum: aim at 16 x 16-byte loads in flight per lane.
+__host__ __device__ constexpr int unroll_for(int n_src) {
+  return n_src <= 2 ? 8 : n_src <= 4 ? 4 : n_src <= 8 ? 2 : 1;
+}
+
+// ---- any number of sources (runtime N): loads in groups of 8 ---------------
+template <typename T, int VEC, bool NT>
+__device__ __forceinline__ void sum_any_one(T* const* s_tab, int N, T* out, float scale, size_t v) {
+  typedef typename Raw<T, VEC>::type R;
+  float a[VEC];
+  for (int j0 = 0; j0 < N; j0 += 8) {
+    R raw[8];
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj)
+      if (j0 + jj < N) raw[jj] = ld<NT>(reinterpret_cast<const R*>(uniform_ptr(s_tab[j0 + jj])) + v);
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) {
+      if (j0 + jj < N) {
+        float x[VEC];
+        widen(raw[jj], x);
+        if (j0 + jj == 0) {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) a[e] = x[e];
+        } else {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) a[e] = a[e] + x[e];
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) a[e] = a[e] * scale;
+  st<NT>(reinterpret_cast<R*>(out) + v, narrow<R, VEC>(a));
+}
+
+template <typename T, int VEC, bool NT>
+__device__ __forceinline__ void sum_any_range(T* const* s_tab, int N, T* out, float scale, size_t len,
+                                              unsigned bx, unsigned gx) {
+  const size_t n_vec = len / VEC;
+  for (size_t v = static_cast<size_t>(bx) * kThreads + threadIdx.x; v < n_vec;
+       v += static_cast<size_t>(gx) * kThreads)
+    sum_any_one<T, VEC, NT>(s_tab, N, out, scale, v);
+  if constexpr (VEC > 1) {
+    if (bx == 0) {
+      const size_t e = n_vec * VEC + threadIdx.x;
+      if (e < len) sum_any_one<T, 1, NT>(s_tab, N, out, scale, e);
+    }
+  }
+}
+
+// ---- kernels -------------------------------------------------------------
+
+// One-shot masked mean over N live buffers (N fixed at compile time, 1..16).
+template <typename T, int VEC, int N, bool NT>
+__global__ void __launch_bounds__(kThreads)
+k_reduce_masked(PtrTable live, T* out, float scale, size_t count) {
+  __shared__ T* s_tab[kMaxReplicas];
+  if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<T*>(live.p[threadIdx.x]);
+  __syncthreads();
+  T* src[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) src[j] = uniform_ptr(s_tab[j]);
+  sum_range<T, VEC, N, false, false, unroll_for(N), NT>(src, nullptr, nullptr, out, scale, count,
+                                                        blockIdx.x, gridDim.x);
+}
+
+// One-shot masked mean, any N up to 64 (also the element-wise path for unaligned buffers).
+template <typename T, int VEC, bool NT>
+__global__ void __launch_bounds__(kThreads)
+k_reduce_masked_any(PtrTable live, int N, T* out, float scale, size_t count) {
+  __shared__ T* s_tab[kMaxReplicas];
+  if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<T*>(live.p[threadIdx.x]);
+  __syncthreads();
+  sum_any_range<T, VEC, NT>(s_tab, N, out, scale, count, blockIdx.x, gridDim.x);
+}
+
+template <typename T, int VEC, int N, bool NT>
+__device__ __forceinline__ void bucket_fixed_n(T* const* s_tab, T* out, float scale, size_t len) {
+  T* src[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) src[j] = uniform_ptr(s_tab[j]);
+  sum_range<T, VEC, N, false, false, unroll_for(N), NT>(src, nullptr, nullptr, out, scale, len,
+                                                        blockIdx.x, gridDim.x);
+}
+
+// Masked mean with one live mask per bucket; blockIdx.y = bucket.  Each block
+// compacts its bucket's mask into the LDS pointer table (lane r places replica
+// r at the rank of its bit), then runs the N-specialised loop.
+template <typename T, int VEC, bool NT>
+__global__ void __launch_bounds__(kThreads)
+k_reduce_bucketed(PtrTable all, int n_replicas, BucketTable masks, ScaleTable scales,
+                  size_t first_elem, size_t bucket_elems, size_t count, T* out) {
+  __shared__ T* s_tab[kMaxReplicas];
+  const size_t begin = first_elem + static_cast<size_t>(blockIdx.y) * bucket_elems;
+  const size_t len = (count - begin < bucket_elems) ? count - begin : bucket_elems;
+  const unsigned long long mask = masks.mask[blockIdx.y];
+  const unsigned r = threadIdx.x;
+  if (r < static_cast<unsigned>(n_replicas) && ((mask >> r) & 1ull)) {
+    const int pos = __popcll(mask & ((1ull << r) - 1ull));
+    s_tab[pos] = static_cast<T*>(all.p[r]) + begin;
+  }
+  __syncthreads();
+  const int N = __popcll(mask);
+  const float scale = scales.s[N];
+  T* o = out + begin;
+  if constexpr (VEC > 1) {
+    switch (N) {
+#define FTAR_CASE(n) case n: bucket_fixed_n<T, VEC, n, NT>(s_tab, o, scale, len); return;
+      FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
+      FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
+      FTAR_CASE(14) FTAR_CASE(15) FTAR_CASE(16)
+#undef FTAR_CASE
+      default: break;
+    }
+  }
+  sum_any_range<T, VEC, NT>(s_tab, N, o, scale, len, blockIdx.x, gridDim.x);
+}
+
+// One ReduceScatter step over all N portions; blockIdx.y = portion k.
+template <typename T, int VEC, int MODE, bool NT>
+__global__ void __launch_bounds__(kThreads)
+k_ring_reduce(PtrTable ring, SegTable seg, int N, int step, float* acc, float scale) {
+  __shared__ T* s_tab[kMaxReplicas];
+  const int k = blockIdx.y;
+  const size_t begin = seg.begin[k];
+  const size_t len = seg.begin[k + 1] - begin;
+  if (len == 0) return;  // uniform for the block
+  if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<T*>(ring.p[threadIdx.x]);
+  __syncthreads();
+  constexpr int U = 8;
+  float* a = acc ? acc + begin : nullptr;
+  if constexpr (MODE == kRsFirst) {
+    T* src[2] = {uniform_ptr(s_tab[k]) + begin, uniform_ptr(s_tab[(k + 1) % N]) + begin};
+    sum_range<T, VEC, 2, false, true, U, NT>(src, nullptr, a, nullptr, scale, len, blockIdx.x, gridDim.x);
+  } else if constexpr (MODE == kRsMid) {
+    T* src[1] = {uniform_ptr(s_tab[(k + step + 1) % N]) + begin};
+    sum_range<T, VEC, 1, true, true, U, NT>(src, a, a, nullptr, scale, len, blockIdx.x, gridDim.x);
+  } else if constexpr (MODE == kRsLast) {
+    T* src[1] = {uniform_ptr(s_tab[(k + N - 1) % N]) + begin};
+    sum_range<T, VEC, 1, true, false, U, NT>(src, a, nullptr, src[0], scale, len, blockIdx.x, gridDim.x);
+  } else {  // kRsOnly, N == 2
+    T* src[2] = {uniform_ptr(s_tab[k]) + begin, uniform_ptr(s_tab[(k + 1) % N]) + begin};
+    sum_range<T, VEC, 2, false, false, U, NT>(src, nullptr, nullptr, src[1], scale, len, blockIdx.x, gridDim.x);
+  }
+}
+
+// One AllGather step over all N portions: bit copy from ring position k+t-1 to k+t.
+template <typename T, int VEC, bool NT>
+__global__ void __launch_bounds__(kThreads)
+k_ring_allgather(PtrTable ring, SegTable seg, int N, int step) {
+  __shared__ T* s_tab[kMaxReplicas];
+  typedef typename Raw<T, VEC>::type R;
+  typedef typename Raw<T, 1>::type R1;
+  const int k = blockIdx.y;
+  const size_t begin = seg.begin[k];
+  const size_t len = seg.begin[k + 1] - begin;
+  if (len == 0) return;
+  if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<T*>(ring.p[threadIdx.x]);
+  __syncthreads();
+  const T* from = uniform_ptr(s_tab[(k + step + N - 1) % N]) + begin;
+  T* to = uniform_ptr(s_tab[(k + step) % N]) + begin;
+  constexpr int U = 8;
+  constexpr size_t kTile = static_cast<size_t>(kThreads) * U;
+  const unsigned tid = threadIdx.x;
+  const size_t n_vec = len / VEC;
+  const size_t n_tiles = n_vec / kTile;
+  for (size_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+    const size_t v = t * kTile + tid;
+    R raw[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) raw[u] = ld<NT>(reinterpret_cast<const R*>(from) + v + u * kThreads);
+#pragma unroll
+    for (int u = 0; u < U; ++u) st<NT>(reinterpret_cast<R*>(to) + v + u * kThreads, raw[u]);
+  }
+  if (blockIdx.x == n_tiles % gridDim.x) {
+    for (size_t v = n_tiles * kTile + tid; v < n_vec; v += kThreads)
+      st<NT>(reinterpret_cast<R*>(to) + v, ld<NT>(reinterpret_cast<const R*>(from) + v));
+    if constexpr (VEC > 1) {
+      const size_t e = n_vec * VEC + tid;
+      if (e < len) reinterpret_cast<R1*>(to)[e] = reinterpret_cast<const R1*>(from)[e];
+    }
+  }
+}
+
+// ---- launch geometry -------------------------------------------------------
+unsigned total_blocks() {
+  const Tuning t = current_tuning();
+  const int per_cu = t.blocks_per_cu > 0 ? t.blocks_per_cu : kDefaultBlocksPerCu;
+  return static_cast<unsigned>(device_cu_count()) * static_cast<unsigned>(per_cu);
+}
+
+unsigned grid_x_for(size_t n_tiles, unsigned budget) {
+  if (budget < 1) budget = 1;
+  if (n_tiles < 1) return 1;
+  return n_tiles < budget ? static_cast<unsigned>(n_tiles) : budget;
+}
+
+bool plain_access() { return (current_tuning().flags & 1) != 0; }
+
+template <typename T, int VEC, bool NT>
+hipError_t launch_reduce_fixed(const PtrTable& live, int N, size_t count, T* out, float scale,
+                               hipStream_t stream) {
+  const size_t tiles = count / VEC / (static_cast<size_t>(kThreads) * unroll_for(N));
+  const dim3 grid(grid_x_for(tiles, total_blocks())), block(kThreads);
+  switch (N) {
+#define FTAR_CASE(n) \
+  case n: k_reduce_masked<T, VEC, n, NT><<<grid, block, 0, stream>>>(live, out, scale, count); break;
+    FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
+    FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
+    FTAR_CASE(14) FTAR_CASE(15) FTAR_CASE(16)
+#undef FTAR_CASE
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+template <typename T, int VEC, bool NT>
+hipError_t launch_reduce_any(const PtrTable& live, int N, size_t count, T* out, float scale,
+                             hipStream_t stream) {
+  const size_t tiles = (count / VEC + kThreads - 1) / kThreads;
+  const dim3 grid(grid_x_for(tiles, total_blocks())), block(kThreads);
+  k_reduce_masked_any<T, VEC, NT><<<grid, block, 0, stream>>>(live, N, out, scale, count);
+  return hipGetLastError();
+}
+
+template <typename T, int VECW>
+hipError_t reduce_masked_typed(const PtrTable& live, int N, size_t count, bool vec, void* out,
+                               float scale, hipStream_t stream) {
+  T* o = static_cast<T*>(out);
+  const bool plain = plain_access();
+  if (vec && N <= 16) {
+    return plain ? launch_reduce_fixed<T, VECW, false>(live, N, count, o, scale, stream)
+                 : launch_reduce_fixed<T, VECW, true>(live, N, count, o, scale, stream);
+  }
+  if (vec) {
+    return plain ? launch_reduce_any<T, VECW, false>(live, N, count, o, scale, stream)
+                 : launch_reduce_any<T, VECW, true>(live, N, count, o, scale, stream);
+  }
+  return plain ? launch_reduce_any<T, 1, false>(live, N, count, o, scale, stream)
+               : launch_reduce_any<T, 1, true>(live, N, count, o, scale, stream);
+}
+
+template <typename T, int VEC, bool NT>
+hipError_t launch_bucketed_t(const PtrTable& all, int n_replicas, const BucketTable& masks,
+                             int n_buckets, size_t first_elem, size_t bucket_elems, size_t count,
+                             const ScaleTable& scales, T* out, hipStream_t stream) {
+  const size_t tiles = (bucket_elems / VEC + kThreads - 1) / kThreads;
+  unsigned budget = total_blocks() / static_cast<unsigned>(n_buckets);
+  const dim3 grid(grid_x_for(tiles, budget), static_cast<unsigned>(n_buckets)), block(kThreads);
+  k_reduce_bucketed<T, VEC, NT><<<grid, block, 0, stream>>>(all, n_replicas, masks, scales,
+                                                            first_elem, bucket_elems, count, out);
+  return hipGetLastError();
+}
+
+template <typename T, int VECW>
+hipError_t bucketed_typed(const PtrTable& all, int n_replicas, const BucketTable& masks,
+                          int n_buckets, size_t first_elem, size_t bucket_elems, size_t count,
+                          const ScaleTable& scales, bool vec, void* out, hipStream_t stream) {
+  T* o = static_cast<T*>(out);
+  const bool plain = plain_access();
+#define FTAR_GO(V, NTV) \
+  launch_bucketed_t<T, V, NTV>(all, n_replicas, masks, n_buckets, first_elem, bucket_elems, count, \
+                               scales, o, stream)
+  if (vec) return plain ? FTAR_GO(VECW, false) : FTAR_GO(VECW, true);
+  return plain ? FTAR_GO(1, false) : FTAR_GO(1, true);
+#undef FTAR_GO
+}
+
+size_t longest_segment(const SegTable& seg, int N) {
+  size_t m = 0;
+  for (int k = 0; k < N; ++k) {
+    const size_t len = seg.begin[k + 1] - seg.begin[k];
+    if (len > m) m = len;
+  }
+  return m;
+}
+
+template <typename T, int VEC, bool NT>
+hipError_t launch_ring_reduce_t(RingMode mode, const PtrTable& ring, int N, int step,
+                                const SegTable& seg, float* acc, float scale, hipStream_t stream) {
+  const size_t tiles = longest_segment(seg, N) / VEC / (static_cast<size_t>(kThreads) * 8);
+  const dim3 grid(grid_x_for(tiles, total_blocks() / static_cast<unsigned>(N)),
+                  static_cast<unsigned>(N)), block(kThreads);
+  switch (mode) {
+    case kRsFirst:
+      k_ring_reduce<T, VEC, kRsFirst, NT><<<grid, block, 0, stream>>>(ring, seg, N, step, acc, scale);
+      break;
+    case kRsMid:
+      k_ring_reduce<T, VEC, kRsMid, NT><<<grid, block, 0, stream>>>(ring, seg, N, step, acc, scale);
+      break;
+    case kRsLast:
+      k_ring_reduce<T, VEC, kRsLast, NT><<<grid, block, 0, stream>>>(ring, seg, N, step, acc, scale);
+      break;
+    case kRsOnly:
+      k_ring_reduce<T, VEC, kRsOnly, NT><<<grid, block, 0, stream>>>(ring, seg, N, step, acc, scale);
+      break;
+  }
+  return hipGetLastError();
+}
+
+template <typename T, int VEC, bool NT>
+hipError_t launch_ring_allgather_t(const PtrTable& ring, int N, int step, const SegTable& seg,
+                                   hipStream_t stream) {
+  const size_t tiles = longest_segment(seg, N) / VEC / (static_cast<size_t>(kThreads) * 8);
+  const dim3 grid(grid_x_for(tiles, total_blocks() / static_cast<unsigned>(N)),
+                  static_cast<unsigned>(N)), block(kThreads);
+  k_ring_allgather<T, VEC, NT><<<grid, block, 0, stream>>>(ring, seg, N, step);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// ---- exported launchers ----------------------------------------------------
+
+hipError_t launch_reduce_masked(const PtrTable& live, int n_live, size_t count, ftar_dtype_t dtype,
+                                bool vec, void* out, float scale, hipStream_t stream) {
+  if (dtype == FTAR_F32) return reduce_masked_typed<float, 4>(live, n_live, count, vec, out, scale, stream);
+  return reduce_masked_typed<bf16, 8>(live, n_live, count, vec, out, scale, stream);
+}
+
+hipError_t launch_reduce_bucketed(const PtrTable& all, int n_replicas, const BucketTable& masks,
+                                  int n_buckets, size_t first_elem, size_t bucket_elems,
+                                  size_t count, const ScaleTable& scales, ftar_dtype_t dtype,
+                                  bool vec, void* out, hipStream_t stream) {
+  if (dtype == FTAR_F32)
+    return bucketed_typed<float, 4>(all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
+                                    count, scales, vec, out, stream);
+  return bucketed_typed<bf16, 8>(all, n_replicas, masks, n_buckets, first_elem, bucket_elems, count,
+                                 scales, vec, out, stream);
+}
+
+hipError_t launch_ring_reduce(RingMode mode, const PtrTable& ring, int n_live, int step,
+                              const SegTable& seg, ftar_dtype_t dtype, bool vec, float* acc,
+                              float scale, hipStream_t stream) {
+  const bool plain = plain_access();
+#define FTAR_GO(T, V, NTV) \
+  launch_ring_reduce_t<T, V, NTV>(mode, ring, n_live, step, seg, acc, scale, stream)
+  if (dtype == FTAR_F32) {
+    if (vec) return plain ? FTAR_GO(float, 4, false) : FTAR_GO(float, 4, true);
+    return plain ? FTAR_GO(float, 1, false) : FTAR_GO(float, 1, true);
+  }
+  if (vec) return plain ? FTAR_GO(bf16, 4, false) : FTAR_GO(bf16, 4, true);
+  return plain ? FTAR_GO(bf16, 1, false) : FTAR_GO(bf16, 1, true);
+#undef FTAR_GO
+}
+
+hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, const SegTable& seg,
+                                 ftar_dtype_t dtype, bool vec, hipStream_t stream) {
+  const bool plain = plain_access();
+#define FTAR_GO(T, V, NTV) launch_ring_allgather_t<T, V, NTV>(ring, n_live, step, seg, stream)
+  if (dtype == FTAR_F32) {
+    if (vec) return plain ? FTAR_GO(float, 4, false) : FTAR_GO(float, 4, true);
+    return plain ? FTAR_GO(float, 1, false) : FTAR_GO(float, 1, true);
+  }
+  if (vec) return plain ? FTAR_GO(bf16, 8, false) : FTAR_GO(bf16, 8, true);
+  return plain ? FTAR_GO(bf16, 1, false) : FTAR_GO(bf16, 1, true);
+#undef FTAR_GO
+}
+
+}  // namespace ftar

@@ -1,0 +1,83 @@
+"""Host-only checks of the C-ABI library: it loads without a GPU, exports every symbol the
+header declares, and its planner agrees with the oracle's independently written geometry."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2602_00277_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build(verbose=False)
+    binding.lib()
+    return binding
+
+
+def test_exports_every_declared_symbol(B):
+    header = open(os.path.join(ROOT, "include", "ftar.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ftar_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
+    raw = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert getattr(raw, name) is not None, name
+
+
+def test_status_strings_and_classes(B):
+    for s in (0, 1, 2, 3, 4, 16, 32):
+        assert B.ftar_status_str(s)
+    assert B.ftar_status_is_retryable(B.FTAR_ERR_STALE_PLAN)
+    assert not any(B.ftar_status_is_retryable(s) for s in (0, 1, 2, 3, 4, 32))
+
+
+def test_plan_rejects_bad_arguments(B):
+    cases = [((0, 1, 10, 1), B.FTAR_ERR_INVALID_ARG), ((65, 1, 10, 1), B.FTAR_ERR_INVALID_ARG),
+             ((4, 0, 10, 1), B.FTAR_ERR_NO_LIVE), ((4, 0x10, 10, 1), B.FTAR_ERR_BAD_MASK),
+             ((4, 0xF, 0, 1), B.FTAR_ERR_INVALID_ARG), ((4, 0xF, 10, 0), B.FTAR_ERR_INVALID_ARG)]
+    for args, status in cases:
+        with pytest.raises(B.FtarError) as e:
+            B.ftar_plan(*args)
+        assert e.value.status == status, args
+
+
+def test_planner_matches_oracle_geometry(B, oracle):
+    cases = [(16, 0xFFFF, 1 << 28, 16384), (16, 0xFDFF, 1 << 28, 16384), (8, 0xF7, 1000, 16),
+             (5, 0b10101, 17, 4), (6, 0b111111, 3, 1), (4, 0xF, 100, 1000),
+             (64, (1 << 64) - 1, 12345, 7), (8, 0xFF, 2_000_000_000, 16384), (3, 0b101, 1, 1)]
+    for n, mask, count, chunk in cases:
+        p = B.ftar_plan(n, mask, count, chunk)
+        ring = oracle.live_ring(n, mask)
+        N = len(ring)
+        assert p.n_live == N and p.n_steps == N - 1 and p.acc_bytes == count * 4
+        sb = oracle.geometry(n, mask, count, chunk)
+        for k in range(N):
+            b, e, owner = p.segment(k)
+            assert (b, e) == (sb[k], sb[k + 1])
+            assert owner == ring[(k + N - 1) % N]
+        import numpy as np
+        assert np.float32(p.scale) == oracle.scale(N)
+        p.destroy()
+
+
+def test_plan_is_pure(B):
+    a = B.ftar_plan(16, 0xFDFF, 1 << 28, 16384)
+    b = B.ftar_plan(16, 0xFDFF, 1 << 28, 16384)
+    assert [a.segment(k) for k in range(15)] == [b.segment(k) for k in range(15)]
+
+
+def test_oracle_is_not_reachable_from_the_product(B):
+    # the package must not import the oracle, and the oracle must not import the package
+    pkg = os.path.join(ROOT, "paper_2602_00277_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "ftar_oracle" not in src and "oracle/" not in src, f
+    osrc = open(os.path.join(ROOT, "oracle", "ftar_oracle.py")).read() + \
+        open(os.path.join(ROOT, "oracle", "ftar_oracle.cpp")).read()
+    assert "paper_2602_00277_amd" not in osrc and "ftar.h" not in osrc and "libftar.so" not in osrc

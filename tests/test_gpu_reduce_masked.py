@@ -1,0 +1,194 @@
+"""GPU parity: ftar_reduce_masked / ftar_reduce_masked_bucketed against the CPU oracle,
+element by element and bit-exact (same fixed accumulation order on both sides)."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import BF16, F32, assert_same, code, host, rand_bufs, say
+
+pytestmark = pytest.mark.gpu
+
+DTYPES = [torch.float32, torch.bfloat16]
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2602_00277_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 7, 8, 9, 12, 16])
+def test_all_live_every_specialised_n(B, oracle, dtype, n):
+    # spans several tiles of every unroll factor plus whole-vector leftovers and a ragged tail
+    count = 3 * 256 * 8 * 8 + 5 * 256 * 8 + 13
+    say("reduce_masked all-live", dtype, n, count)
+    bufs = rand_bufs(n, count, dtype, seed=n)
+    out = torch.empty(count, dtype=dtype, device="cuda")
+    B.ftar_reduce_masked(bufs, (1 << n) - 1, out)
+    torch.cuda.synchronize()
+    want = oracle.reduce_masked([host(b) for b in bufs], (1 << n) - 1, code(dtype))
+    assert_same(host(out), want, "n=%d" % n)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+@pytest.mark.parametrize("count", [1, 3, 7, 8, 9, 255, 2048, 2049, 65536 + 17, (1 << 20) + 3])
+def test_ragged_counts_with_dead_replicas(B, oracle, dtype, count):
+    n, mask = 8, 0b11110111
+    say("reduce_masked ragged", dtype, count)
+    bufs = rand_bufs(n, count, dtype, seed=count % 1000, mask=mask)   # replica 3 is NaN-poisoned
+    out = torch.full((count + 64,), 7.0, dtype=dtype, device="cuda")
+    B.ftar_reduce_masked(bufs, mask, out, count=count)
+    torch.cuda.synchronize()
+    want = oracle.reduce_masked([host(b) for b in bufs], mask, code(dtype))
+    got = host(out)
+    assert_same(got[:count], want, "count=%d" % count)
+    assert np.all(host(out[count:]) == host(torch.full((64,), 7.0, dtype=dtype)))  # nothing past the end
+    # a dead replica may have no buffer at all
+    bufs2 = [None if r == 3 else b for r, b in enumerate(bufs)]
+    out2 = torch.empty(count, dtype=dtype, device="cuda")
+    B.ftar_reduce_masked(bufs2, mask, out2)
+    torch.cuda.synchronize()
+    assert_same(host(out2), want, "NULL dead buffer")
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_every_mask_of_six_replicas(B, oracle, dtype):
+    n, count = 6, 4096 + 11
+    bufs = rand_bufs(n, count, dtype, seed=66)
+    hb = [host(b) for b in bufs]
+    out = torch.empty(count, dtype=dtype, device="cuda")
+    say("reduce_masked every mask", dtype)
+    for mask in range(1, 1 << n):
+        B.ftar_reduce_masked(bufs, mask, out)
+        torch.cuda.synchronize()
+        assert_same(host(out), oracle.reduce_masked(hb, mask, code(dtype)), "mask=%d" % mask)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+@pytest.mark.parametrize("n,mask", [(17, (1 << 17) - 1), (33, (1 << 33) - 1 - (1 << 20)),
+                                    (64, (1 << 64) - 1), (64, 0xF0F0F0F0F0F0F0F1)])
+def test_more_than_sixteen_live(B, oracle, dtype, n, mask):
+    count = 10000 + 3
+    say("reduce_masked many replicas", dtype, n, hex(mask))
+    bufs = rand_bufs(n, count, dtype, seed=n, mask=mask)
+    out = torch.empty(count, dtype=dtype, device="cuda")
+    B.ftar_reduce_masked(bufs, mask, out)
+    torch.cuda.synchronize()
+    assert_same(host(out), oracle.reduce_masked([host(b) for b in bufs], mask, code(dtype)))
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_special_values(B, oracle, dtype):
+    sp = np.array([0.0, -0.0, 1e-45, -1e-45, 1.1754942e-38, 5e-39, 1.0, 1.0 + 2 ** -23, 2 ** -24,
+                   -2 ** -24, 3.0e38, -3.0e38, 1e30, -1e30, 1e-30, np.inf, -np.inf, np.nan,
+                   3.3895314e38, 1e8, -1e8, 65504.0], dtype=np.float32)
+    rng = np.random.default_rng(5)
+    n, count = 5, 4096
+    hb = [sp[rng.integers(0, sp.size, count)].copy() for _ in range(n)]
+    say("reduce_masked specials", dtype)
+    if dtype == torch.bfloat16:
+        hb = [oracle.f32_to_bf16(h) for h in hb]
+    from paper_2602_00277_amd import workloads as W
+    bufs = [W.from_numpy_bits(h, "cuda") for h in hb]
+    out = torch.empty(count, dtype=dtype, device="cuda")
+    for mask in (0b11111, 0b10101, 0b00100, 0b11000):
+        B.ftar_reduce_masked(bufs, mask, out)
+        torch.cuda.synchronize()
+        assert_same(host(out), oracle.reduce_masked(hb, mask, code(dtype)), "mask=%d" % mask)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_unaligned_buffers_take_the_elementwise_path(B, oracle, dtype):
+    n, count = 4, 5000
+    say("reduce_masked unaligned", dtype)
+    big = rand_bufs(n, count + 8, dtype, seed=9)
+    bufs = [b[1 + r:1 + r + count] for r, b in enumerate(big)]       # element-aligned only
+    out_big = torch.zeros(count + 8, dtype=dtype, device="cuda")
+    out = out_big[3:3 + count]
+    B.ftar_reduce_masked(bufs, 0b1111, out)
+    torch.cuda.synchronize()
+    assert_same(host(out), oracle.reduce_masked([host(b) for b in bufs], 0b1111, code(dtype)))
+    assert float(out_big[:3].abs().sum()) == 0.0 and float(out_big[3 + count:].abs().sum()) == 0.0
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+def test_in_place_on_a_live_replica_and_determinism(B, oracle, dtype):
+    n, count, mask = 8, 100003, 0b10111101
+    say("reduce_masked in place", dtype)
+    bufs = rand_bufs(n, count, dtype, seed=21, mask=mask)
+    hb = [host(b) for b in bufs]
+    want = oracle.reduce_masked(hb, mask, code(dtype))
+    o1 = torch.empty(count, dtype=dtype, device="cuda")
+    o2 = torch.empty(count, dtype=dtype, device="cuda")
+    B.ftar_reduce_masked(bufs, mask, o1)
+    B.ftar_reduce_masked(bufs, mask, o2)
+    torch.cuda.synchronize()
+    assert_same(host(o1), want)
+    assert torch.equal(o1.view(torch.int16 if dtype == torch.bfloat16 else torch.int32),
+                       o2.view(torch.int16 if dtype == torch.bfloat16 else torch.int32))
+    B.ftar_reduce_masked(bufs, mask, bufs[2])     # out aliases live replica 2
+    torch.cuda.synchronize()
+    assert_same(host(bufs[2]), want, "in place")
+
+
+def test_error_codes(B):
+    x = [torch.zeros(16, device="cuda") for _ in range(3)]
+    out = torch.zeros(16, device="cuda")
+    say("reduce_masked error codes")
+    for mask, status in ((0, B.FTAR_ERR_NO_LIVE), (0b1000, B.FTAR_ERR_BAD_MASK)):
+        with pytest.raises(B.FtarError) as e:
+            B.ftar_reduce_masked(x, mask, out)
+        assert e.value.status == status
+        assert B.ftar_last_error() == status
+    with pytest.raises(B.FtarError) as e:
+        B.ftar_reduce_masked([x[0], None, x[2]], 0b111, out)      # live replica without a buffer
+    assert e.value.status == B.FTAR_ERR_INVALID_ARG
+    assert not B.ftar_status_is_retryable(B.FTAR_ERR_INVALID_ARG)
+    assert not B.ftar_status_is_retryable(B.FTAR_ERR_DEVICE)
+    assert B.ftar_status_is_retryable(B.FTAR_ERR_STALE_PLAN)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+@pytest.mark.parametrize("bucket_elems,count", [(4096, 4096 * 5 + 1000), (1000, 10007), (25600, 25600 * 21 - 13),
+                                                 (17, 1000)])
+def test_bucketed_masks(B, oracle, dtype, bucket_elems, count):
+    from paper_2602_00277_amd import workloads as W
+    n = 8
+    n_buckets = (count + bucket_elems - 1) // bucket_elems
+    masks = W.bucket_masks(n, n_buckets, 0.7, seed=bucket_elems)
+    masks[0] = 0b00010000            # single live replica
+    if n_buckets > 2:
+        masks[2] = 0xFF
+    say("bucketed", dtype, bucket_elems, count, n_buckets)
+    bufs = rand_bufs(n, count, dtype, seed=31)
+    hb = [host(b) for b in bufs]
+    out = torch.empty(count, dtype=dtype, device="cuda")
+    B.ftar_reduce_masked_bucketed(bufs, masks, bucket_elems, out)
+    torch.cuda.synchronize()
+    got = host(out)
+    for b in range(n_buckets):
+        lo, hi = b * bucket_elems, min(count, (b + 1) * bucket_elems)
+        want = oracle.reduce_masked([h[lo:hi].copy() for h in hb], masks[b], code(dtype))
+        assert_same(got[lo:hi], want, "bucket %d mask %s" % (b, bin(masks[b])))
+
+
+def test_bucketed_more_than_one_launch_and_many_replicas(B, oracle):
+    from paper_2602_00277_amd import workloads as W
+    n, bucket_elems = 20, 64
+    count = bucket_elems * 600 + 5                     # 601 buckets: three launches
+    masks = W.bucket_masks(n, 601, 0.9, seed=1)
+    say("bucketed 601 buckets, 20 replicas")
+    bufs = rand_bufs(n, count, torch.float32, seed=41)
+    hb = [host(b) for b in bufs]
+    out = torch.empty(count, dtype=torch.float32, device="cuda")
+    B.ftar_reduce_masked_bucketed(bufs, masks, bucket_elems, out)
+    torch.cuda.synchronize()
+    got = host(out)
+    for b in range(601):
+        lo, hi = b * bucket_elems, min(count, (b + 1) * bucket_elems)
+        assert_same(got[lo:hi], oracle.reduce_masked([h[lo:hi].copy() for h in hb], masks[b], F32), "bucket %d" % b)
+    with pytest.raises(B.FtarError) as e:
+        B.ftar_reduce_masked_bucketed(bufs, [0] + masks[1:], bucket_elems, out)
+    assert e.value.status == B.FTAR_ERR_NO_LIVE
