@@ -1,0 +1,243 @@
+#!/usr/bin/env python3
+"""Benchmark of the FTAR GPU data path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic gradients with the
+shape of the second benchmark workload (8 replicas x 64 Mi bf16 elements, replica 3 dead):
+
+  plan            ftar_plan over the live set                       (CPU)
+  masked reduce   ftar_reduce_masked -> out                         (1 kernel)
+  ring schedule   N-1 ftar_reduce_step + N-1 ftar_allgather_step    (12 kernels for N = 7)
+  bucketed        ftar_reduce_masked_bucketed, 25 Mi-element buckets with per-bucket
+                  live masks drawn inside the live set              (1 kernel)
+
+`value` is the algorithmic bytes (read + written) of all those kernels divided by the wall time
+of the step, inputs resident in HBM.  Every kernel launch is bracketed by HIP events recorded
+on the stream the kernels run on; `roofline` reports the kernel kind that takes the largest
+share of the step, `kernels` reports all kinds.  `cpu_baseline` times the CPU oracle (plain
+single-threaded C++) on the same step on the host.
+
+The ring runs in place, so later steps reduce already reduced buffers; kernel time does not
+depend on the values.  Parity is checked once, before timing, on fresh inputs.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(kind, n_live, elem_bytes, count):
+    """Bytes the method itself must move per launch (dead replicas are never read)."""
+    E = elem_bytes
+    per_elem = {
+        "reduce_masked": n_live * E + E,
+        "rs_first": 2 * E + 4,
+        "rs_mid": 4 + E + 4,
+        "rs_last": 4 + E + E,
+        "rs_only": 2 * E + E,
+        "allgather": E + E,
+    }[kind]
+    return per_elem * count
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-parity", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (simulated replicas are separate buffers on "
+              "one device; no collectives between GPUs). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2602_00277_amd import binding as B
+    from paper_2602_00277_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.lib()  # raises if libftar.so is not built: there is no fallback path
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+
+    w = W.configs()[1]
+    E = w.elem_bytes
+    count = w.count
+    n = w.n_replicas
+    mask = w.live_mask
+    bucket_elems = 25 * W.M
+    n_buckets = (count + bucket_elems - 1) // bucket_elems
+    bmasks = [m & mask for m in W.bucket_masks(n, n_buckets, 0.9, seed=w.seed)]
+    live_list = [r for r in range(n) if (mask >> r) & 1]
+    bmasks = [m if m else 1 << live_list[b % len(live_list)] for b, m in enumerate(bmasks)]
+
+    bufs = W.draw_replicas(w, dev)
+    out = torch.empty(count, dtype=w.dtype, device=dev)
+    out_b = torch.empty(count, dtype=w.dtype, device=dev)
+    acc = torch.empty(count, dtype=torch.float32, device=dev)
+    stream = torch.cuda.Stream()  # default priority
+
+    plan0 = B.ftar_plan(n, mask, count, w.chunk_elems, w.dtype)
+    N = plan0.n_live
+    B.ftar_plan_destroy(plan0)
+
+    # kinds in launch order within one step
+    kinds = ["reduce_masked"]
+    if N == 2:
+        kinds += ["rs_only"]
+    elif N >= 3:
+        kinds += ["rs_first"] + ["rs_mid"] * (N - 3) + ["rs_last"]
+    kinds += ["allgather"] * (N - 1 if N >= 2 else 0)
+    kinds += ["bucketed"]
+    bytes_of = {k: algorithmic_bytes(k, N, E, count) for k in set(kinds) if k != "bucketed"}
+    bucket_len = [min(count, (b + 1) * bucket_elems) - b * bucket_elems for b in range(n_buckets)]
+    bytes_of["bucketed"] = sum(L * E * (bin(m).count("1") + 1) for L, m in zip(bucket_len, bmasks))
+    step_bytes = sum(bytes_of[k] for k in kinds)
+
+    def step(events=None):
+        plan = B.ftar_plan(n, mask, count, w.chunk_elems, w.dtype)
+        i = 0
+
+        def mark():
+            nonlocal i
+            if events is not None:
+                events[i].record(stream)
+                i += 1
+        mark()
+        B.ftar_reduce_masked(bufs, mask, out, stream=stream)
+        mark()
+        for s in range(plan.n_steps):
+            B.ftar_reduce_step(plan, s, bufs, acc, stream=stream)
+            mark()
+        for t in range(plan.n_steps):
+            B.ftar_allgather_step(plan, t, bufs, stream=stream)
+            mark()
+        B.ftar_reduce_masked_bucketed(bufs, bmasks, bucket_elems, out_b, stream=stream)
+        mark()
+        B.ftar_plan_destroy(plan)
+
+    parity = "skipped"
+    cpu_baseline = None
+    if not (args.no_parity and args.no_cpu_baseline):
+        sys.path.insert(0, os.path.join(ROOT, "oracle"))
+        import ftar_oracle as oracle
+        code = oracle.BF16 if w.dtype == torch.bfloat16 else oracle.F32
+        host_in = [W.to_numpy_bits(b) for b in bufs]
+
+        def same(got, want):
+            nan_g = (got & 0x7FFF) > 0x7F80 if got.dtype == np.uint16 else np.isnan(got)
+            nan_w = (want & 0x7FFF) > 0x7F80 if want.dtype == np.uint16 else np.isnan(want)
+            bits = np.uint16 if got.dtype == np.uint16 else np.uint32
+            return np.array_equal(nan_g, nan_w) and \
+                np.array_equal(got.view(bits)[~nan_g], want.view(bits)[~nan_w])
+
+        if not args.no_parity:
+            step()                       # one whole step on the fresh inputs
+            torch.cuda.synchronize()
+            got_out = W.to_numpy_bits(out)
+            got_ring = [W.to_numpy_bits(b) for b in bufs]
+            got_b = W.to_numpy_bits(out_b)
+        # the oracle's step: one-shot reduce, message-passing ring, per-bucket reduce
+        # (the bucketed pass runs on the ring's output, as in the GPU step)
+        ring_ref = [h.copy() for h in host_in]
+        want_b = np.empty(count, dtype=host_in[live_list[0]].dtype)
+        t0 = time.perf_counter()
+        want_out = oracle.reduce_masked(host_in, mask, code)
+        oracle.ring_per_rank(ring_ref, mask, w.chunk_elems, code)
+        for b in range(n_buckets):
+            lo, hi = b * bucket_elems, min(count, (b + 1) * bucket_elems)
+            slabs = [ring_ref[r][lo:hi] if (bmasks[b] >> r) & 1 else None for r in range(n)]
+            want_b[lo:hi] = oracle.reduce_masked(slabs, bmasks[b], code)
+        cpu_s = time.perf_counter() - t0
+        if not args.no_cpu_baseline:
+            cpu_baseline = {"value": round(step_bytes / cpu_s / 1e9, 3), "unit": "GB/s", "cores": 1,
+                            "kind": "oracle", "seconds": round(cpu_s, 3),
+                            "host_cpus_visible": os.cpu_count(),
+                            "sample": "one full step of the workload (all %d elements per replica): "
+                                      "one-shot masked reduce + message-passing ring + per-bucket "
+                                      "reduce, same algorithmic bytes as the GPU step" % count}
+        if not args.no_parity:
+            ok = same(got_out, want_out) and same(got_b, want_b)
+            for r in range(n):
+                ok = ok and same(got_ring[r], ring_ref[r])
+            parity = "bit-exact vs oracle, every element of the step" if ok else "MISMATCH"
+            if not ok:
+                print("bench.py: GPU step does not match the oracle", file=sys.stderr)
+                sys.exit(1)
+        del host_in, ring_ref
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    n_marks = len(kinds) + 1
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(n_marks)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    dur = {}
+    for ev in events:
+        for i, kind in enumerate(kinds):
+            dur.setdefault(kind, []).append(ev[i].elapsed_time(ev[i + 1]) * 1e-3)  # seconds
+    kernels = []
+    for kind in dict.fromkeys(kinds):
+        d = dur[kind]
+        avg = sum(d) / len(d)
+        ach = bytes_of[kind] / avg / 1e9
+        kernels.append({"kind": kind, "launches_per_step": kinds.count(kind),
+                        "avg_us": round(avg * 1e6, 2), "bytes_per_launch": bytes_of[kind],
+                        "achieved_GBps": round(ach, 1), "frac_of_peak": round(ach / HBM_PEAK_GBS, 4),
+                        "share_of_step": round(avg * kinds.count(kind) / (ms_per_step * 1e-3), 4)})
+    dom = max(kernels, key=lambda k: k["share_of_step"])
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    kernel_name = {"reduce_masked": "k_reduce_masked", "rs_first": "k_ring_reduce<kRsFirst>",
+                   "rs_mid": "k_ring_reduce<kRsMid>", "rs_last": "k_ring_reduce<kRsLast>",
+                   "rs_only": "k_ring_reduce<kRsOnly>", "allgather": "k_ring_allgather",
+                   "bucketed": "k_reduce_bucketed"}
+    result = {
+        "metric": "masked gradient all-reduce GB/s (read+write) and % of MI355X HBM peak",
+        "value": round(value, 1), "unit": "GB/s", "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "n_replicas": n, "live_mask": bin(mask), "n_live": N,
+                   "count": count, "storage_dtype": "bf16", "chunk_elems": w.chunk_elems,
+                   "bucket_elems": bucket_elems,
+                   "step": "plan + masked reduce + %d RS + %d AG step kernels + bucketed reduce"
+                           % (N - 1, N - 1),
+                   "bytes_per_step": step_bytes},
+        "roofline": {"bound": "hbm", "kernel": kernel_name[dom["kind"]], "achieved": dom["achieved_GBps"],
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(dom["achieved_GBps"] / HBM_PEAK_GBS, 4),
+                     "traffic": None, "bytes_per_launch": dom["bytes_per_launch"],
+                     "avg_us": dom["avg_us"]},
+        "kernels": kernels,
+        "cpu_baseline": cpu_baseline,
+        "parity": parity,
+    }
+    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(traffic_file):
+        try:
+            t = json.load(open(traffic_file))
+            result["roofline"]["traffic"] = t.get(dom["kind"])
+        except Exception:
+            pass
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -167,9 +167,10 @@ ftar_status_t ftar_last_error(void);          /* status of this thread's last fa
 int ftar_status_is_retryable(ftar_status_t s);
 const char* ftar_status_str(ftar_status_t s); /* static string */
 
-/* Launch shape, for measurement only (results never depend on it).
- * blocks_per_cu: workgroups launched per compute unit (0 = default);
- * flags: bit 0 = plain instead of non-temporal loads and stores. */
+/* Launch shape and cache policy, for measurement only (results never depend on it).
+ * blocks_per_cu: workgroups launched per compute unit (0 = each kernel's default);
+ * flags: 0 = each kernel's default policy; 0x10 | p = explicit policy p, where bit 0 of p
+ * asks for non-temporal loads and bit 1 for non-temporal stores. */
 void ftar_set_tuning(int blocks_per_cu, int flags);
 
 #ifdef __cplusplus

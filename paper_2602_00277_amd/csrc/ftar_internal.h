@@ -44,7 +44,7 @@ enum RingMode {
 
 struct Tuning {
   int blocks_per_cu;  // 0 = default
-  int flags;          // bit 0: plain (temporal) loads/stores
+  int flags;          // 0 = default policy; 0x10 | p = explicit (bit 0 NT loads, bit 1 NT stores)
 };
 
 Tuning current_tuning();

@@ -24,7 +24,6 @@ namespace ftar {
 namespace {
 
 constexpr int kThreads = 256;          // 4 waves of 64 lanes: one per SIMD of a CU
-constexpr int kDefaultBlocksPerCu = 8;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -42,15 +41,15 @@ template <> struct Raw<bf16, 8> { typedef u32x4 type; };
 template <> struct Raw<bf16, 4> { typedef u32x2 type; };
 template <> struct Raw<bf16, 1> { typedef uint16_t type; };
 
-template <bool NT, typename R>
+template <int POL, typename R>
 __device__ __forceinline__ R ld(const R* p) {
-  if constexpr (NT) return __builtin_nontemporal_load(p);
+  if constexpr ((POL & 1) != 0) return __builtin_nontemporal_load(p);
   else return *p;
 }
 
-template <bool NT, typename R>
+template <int POL, typename R>
 __device__ __forceinline__ void st(R* p, R v) {
-  if constexpr (NT) __builtin_nontemporal_store(v, p);
+  if constexpr ((POL & 2) != 0) __builtin_nontemporal_store(v, p);
   else *p = v;
 }
 
@@ -123,7 +122,7 @@ __device__ __forceinline__ P* uniform_ptr(P* p) {
 // Every load of the tile is issued before the first use.  `out` may alias
 // src[NSRC-1] (the in-place last ReduceScatter step): a lane only ever writes
 // the elements it has itself already loaded.
-template <typename T, int VEC, int NSRC, bool ACC_IN, bool ACC_OUT, int U, bool NT>
+template <typename T, int VEC, int NSRC, bool ACC_IN, bool ACC_OUT, int U, int POL>
 __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc_in, float* acc_out,
                                          T* out, float scale, size_t v) {
   static_assert(!(ACC_IN || ACC_OUT) || VEC <= 4, "fp32 partials are moved 4 at a time");
@@ -135,11 +134,11 @@ __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc
   for (int u = 0; u < U; ++u) {
 #pragma unroll
     for (int j = 0; j < NSRC; ++j)
-      raw[u][j] = ld<NT>(reinterpret_cast<const R*>(src[j]) + v + u * kThreads);
+      raw[u][j] = ld<POL>(reinterpret_cast<const R*>(src[j]) + v + u * kThreads);
   }
   if constexpr (ACC_IN) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) ain[u] = ld<NT>(reinterpret_cast<const A*>(acc_in) + v + u * kThreads);
+    for (int u = 0; u < U; ++u) ain[u] = ld<POL>(reinterpret_cast<const A*>(acc_in) + v + u * kThreads);
   }
 #pragma unroll
   for (int u = 0; u < U; ++u) {
@@ -153,11 +152,11 @@ __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc
       for (int e = 0; e < VEC; ++e) a[e] = a[e] + x[e];
     }
     if constexpr (ACC_OUT) {
-      st<NT>(reinterpret_cast<A*>(acc_out) + v + u * kThreads, narrow<A, VEC>(a));
+      st<POL>(reinterpret_cast<A*>(acc_out) + v + u * kThreads, narrow<A, VEC>(a));
     } else {
 #pragma unroll
       for (int e = 0; e < VEC; ++e) a[e] = a[e] * scale;
-      st<NT>(reinterpret_cast<R*>(out) + v + u * kThreads, narrow<R, VEC>(a));
+      st<POL>(reinterpret_cast<R*>(out) + v + u * kThreads, narrow<R, VEC>(a));
     }
   }
 }
@@ -165,7 +164,7 @@ __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc
 // Persistent loop of block bx of gx over the `len` elements that start at the
 // given pointers: full tiles grid-strided, then one block finishes the whole
 // vectors past the last full tile and the last len % VEC single elements.
-template <typename T, int VEC, int NSRC, bool ACC_IN, bool ACC_OUT, int U, bool NT>
+template <typename T, int VEC, int NSRC, bool ACC_IN, bool ACC_OUT, int U, int POL>
 __device__ __forceinline__ void sum_range(T* const (&src)[NSRC], const float* acc_in, float* acc_out,
                                           T* out, float scale, size_t len, unsigned bx,
                                           unsigned gx) {
@@ -174,13 +173,13 @@ __device__ __forceinline__ void sum_range(T* const (&src)[NSRC], const float* ac
   constexpr size_t kTile = static_cast<size_t>(kThreads) * U;
   const size_t n_tiles = n_vec / kTile;
   for (size_t t = bx; t < n_tiles; t += gx)
-    sum_tile<T, VEC, NSRC, ACC_IN, ACC_OUT, U, NT>(src, acc_in, acc_out, out, scale, t * kTile + tid);
+    sum_tile<T, VEC, NSRC, ACC_IN, ACC_OUT, U, POL>(src, acc_in, acc_out, out, scale, t * kTile + tid);
   if (bx == n_tiles % gx) {
     for (size_t v = n_tiles * kTile + tid; v < n_vec; v += kThreads)
-      sum_tile<T, VEC, NSRC, ACC_IN, ACC_OUT, 1, NT>(src, acc_in, acc_out, out, scale, v);
+      sum_tile<T, VEC, NSRC, ACC_IN, ACC_OUT, 1, POL>(src, acc_in, acc_out, out, scale, v);
     if constexpr (VEC > 1) {
       const size_t e = n_vec * VEC + tid;
-      if (e < len) sum_tile<T, 1, NSRC, ACC_IN, ACC_OUT, 1, NT>(src, acc_in, acc_out, out, scale, e);
+      if (e < len) sum_tile<T, 1, NSRC, ACC_IN, ACC_OUT, 1, POL>(src, acc_in, acc_out, out, scale, e);
     }
   }
 }
@@ -191,7 +190,7 @@ __host__ __device__ constexpr int unroll_for(int n_src) {
 }
 
 // ---- any number of sources (runtime N): loads in groups of 8 ---------------
-template <typename T, int VEC, bool NT>
+template <typename T, int VEC, int POL>
 __device__ __forceinline__ void sum_any_one(T* const* s_tab, int N, T* out, float scale, size_t v) {
   typedef typename Raw<T, VEC>::type R;
   float a[VEC];
@@ -199,7 +198,7 @@ __device__ __forceinline__ void sum_any_one(T* const* s_tab, int N, T* out, floa
     R raw[8];
 #pragma unroll
     for (int jj = 0; jj < 8; ++jj)
-      if (j0 + jj < N) raw[jj] = ld<NT>(reinterpret_cast<const R*>(uniform_ptr(s_tab[j0 + jj])) + v);
+      if (j0 + jj < N) raw[jj] = ld<POL>(reinterpret_cast<const R*>(uniform_ptr(s_tab[j0 + jj])) + v);
 #pragma unroll
     for (int jj = 0; jj < 8; ++jj) {
       if (j0 + jj < N) {
@@ -217,20 +216,20 @@ __device__ __forceinline__ void sum_any_one(T* const* s_tab, int N, T* out, floa
   }
 #pragma unroll
   for (int e = 0; e < VEC; ++e) a[e] = a[e] * scale;
-  st<NT>(reinterpret_cast<R*>(out) + v, narrow<R, VEC>(a));
+  st<POL>(reinterpret_cast<R*>(out) + v, narrow<R, VEC>(a));
 }
 
-template <typename T, int VEC, bool NT>
+template <typename T, int VEC, int POL>
 __device__ __forceinline__ void sum_any_range(T* const* s_tab, int N, T* out, float scale, size_t len,
                                               unsigned bx, unsigned gx) {
   const size_t n_vec = len / VEC;
   for (size_t v = static_cast<size_t>(bx) * kThreads + threadIdx.x; v < n_vec;
        v += static_cast<size_t>(gx) * kThreads)
-    sum_any_one<T, VEC, NT>(s_tab, N, out, scale, v);
+    sum_any_one<T, VEC, POL>(s_tab, N, out, scale, v);
   if constexpr (VEC > 1) {
     if (bx == 0) {
       const size_t e = n_vec * VEC + threadIdx.x;
-      if (e < len) sum_any_one<T, 1, NT>(s_tab, N, out, scale, e);
+      if (e < len) sum_any_one<T, 1, POL>(s_tab, N, out, scale, e);
     }
   }
 }
@@ -238,7 +237,7 @@ __device__ __forceinline__ void sum_any_range(T* const* s_tab, int N, T* out, fl
 // ---- kernels -------------------------------------------------------------
 
 // One-shot masked mean over N live buffers (N fixed at compile time, 1..16).
-template <typename T, int VEC, int N, bool NT>
+template <typename T, int VEC, int N, int POL>
 __global__ void __launch_bounds__(kThreads)
 k_reduce_masked(PtrTable live, T* out, float scale, size_t count) {
   __shared__ T* s_tab[kMaxReplicas];
@@ -247,33 +246,33 @@ k_reduce_masked(PtrTable live, T* out, float scale, size_t count) {
   T* src[N];
 #pragma unroll
   for (int j = 0; j < N; ++j) src[j] = uniform_ptr(s_tab[j]);
-  sum_range<T, VEC, N, false, false, unroll_for(N), NT>(src, nullptr, nullptr, out, scale, count,
+  sum_range<T, VEC, N, false, false, unroll_for(N), POL>(src, nullptr, nullptr, out, scale, count,
                                                         blockIdx.x, gridDim.x);
 }
 
 // One-shot masked mean, any N up to 64 (also the element-wise path for unaligned buffers).
-template <typename T, int VEC, bool NT>
+template <typename T, int VEC, int POL>
 __global__ void __launch_bounds__(kThreads)
 k_reduce_masked_any(PtrTable live, int N, T* out, float scale, size_t count) {
   __shared__ T* s_tab[kMaxReplicas];
   if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<T*>(live.p[threadIdx.x]);
   __syncthreads();
-  sum_any_range<T, VEC, NT>(s_tab, N, out, scale, count, blockIdx.x, gridDim.x);
+  sum_any_range<T, VEC, POL>(s_tab, N, out, scale, count, blockIdx.x, gridDim.x);
 }
 
-template <typename T, int VEC, int N, bool NT>
+template <typename T, int VEC, int N, int POL>
 __device__ __forceinline__ void bucket_fixed_n(T* const* s_tab, T* out, float scale, size_t len) {
   T* src[N];
 #pragma unroll
   for (int j = 0; j < N; ++j) src[j] = uniform_ptr(s_tab[j]);
-  sum_range<T, VEC, N, false, false, unroll_for(N), NT>(src, nullptr, nullptr, out, scale, len,
+  sum_range<T, VEC, N, false, false, unroll_for(N), POL>(src, nullptr, nullptr, out, scale, len,
                                                         blockIdx.x, gridDim.x);
 }
 
 // Masked mean with one live mask per bucket; blockIdx.y = bucket.  Each block
 // compacts its bucket's mask into the LDS pointer table (lane r places replica
 // r at the rank of its bit), then runs the N-specialised loop.
-template <typename T, int VEC, bool NT>
+template <typename T, int VEC, int POL>
 __global__ void __launch_bounds__(kThreads)
 k_reduce_bucketed(PtrTable all, int n_replicas, BucketTable masks, ScaleTable scales,
                   size_t first_elem, size_t bucket_elems, size_t count, T* out) {
@@ -292,7 +291,7 @@ k_reduce_bucketed(PtrTable all, int n_replicas, BucketTable masks, ScaleTable sc
   T* o = out + begin;
   if constexpr (VEC > 1) {
     switch (N) {
-#define FTAR_CASE(n) case n: bucket_fixed_n<T, VEC, n, NT>(s_tab, o, scale, len); return;
+#define FTAR_CASE(n) case n: bucket_fixed_n<T, VEC, n, POL>(s_tab, o, scale, len); return;
       FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
       FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
       FTAR_CASE(14) FTAR_CASE(15) FTAR_CASE(16)
@@ -300,11 +299,11 @@ k_reduce_bucketed(PtrTable all, int n_replicas, BucketTable masks, ScaleTable sc
       default: break;
     }
   }
-  sum_any_range<T, VEC, NT>(s_tab, N, o, scale, len, blockIdx.x, gridDim.x);
+  sum_any_range<T, VEC, POL>(s_tab, N, o, scale, len, blockIdx.x, gridDim.x);
 }
 
 // One ReduceScatter step over all N portions; blockIdx.y = portion k.
-template <typename T, int VEC, int MODE, bool NT>
+template <typename T, int VEC, int MODE, int POL>
 __global__ void __launch_bounds__(kThreads)
 k_ring_reduce(PtrTable ring, SegTable seg, int N, int step, float* acc, float scale) {
   __shared__ T* s_tab[kMaxReplicas];
@@ -318,21 +317,21 @@ k_ring_reduce(PtrTable ring, SegTable seg, int N, int step, float* acc, float sc
   float* a = acc ? acc + begin : nullptr;
   if constexpr (MODE == kRsFirst) {
     T* src[2] = {uniform_ptr(s_tab[k]) + begin, uniform_ptr(s_tab[(k + 1) % N]) + begin};
-    sum_range<T, VEC, 2, false, true, U, NT>(src, nullptr, a, nullptr, scale, len, blockIdx.x, gridDim.x);
+    sum_range<T, VEC, 2, false, true, U, POL>(src, nullptr, a, nullptr, scale, len, blockIdx.x, gridDim.x);
   } else if constexpr (MODE == kRsMid) {
     T* src[1] = {uniform_ptr(s_tab[(k + step + 1) % N]) + begin};
-    sum_range<T, VEC, 1, true, true, U, NT>(src, a, a, nullptr, scale, len, blockIdx.x, gridDim.x);
+    sum_range<T, VEC, 1, true, true, U, POL>(src, a, a, nullptr, scale, len, blockIdx.x, gridDim.x);
   } else if constexpr (MODE == kRsLast) {
     T* src[1] = {uniform_ptr(s_tab[(k + N - 1) % N]) + begin};
-    sum_range<T, VEC, 1, true, false, U, NT>(src, a, nullptr, src[0], scale, len, blockIdx.x, gridDim.x);
+    sum_range<T, VEC, 1, true, false, U, POL>(src, a, nullptr, src[0], scale, len, blockIdx.x, gridDim.x);
   } else {  // kRsOnly, N == 2
     T* src[2] = {uniform_ptr(s_tab[k]) + begin, uniform_ptr(s_tab[(k + 1) % N]) + begin};
-    sum_range<T, VEC, 2, false, false, U, NT>(src, nullptr, nullptr, src[1], scale, len, blockIdx.x, gridDim.x);
+    sum_range<T, VEC, 2, false, false, U, POL>(src, nullptr, nullptr, src[1], scale, len, blockIdx.x, gridDim.x);
   }
 }
 
 // One AllGather step over all N portions: bit copy from ring position k+t-1 to k+t.
-template <typename T, int VEC, bool NT>
+template <typename T, int VEC, int POL>
 __global__ void __launch_bounds__(kThreads)
 k_ring_allgather(PtrTable ring, SegTable seg, int N, int step) {
   __shared__ T* s_tab[kMaxReplicas];
@@ -355,13 +354,13 @@ k_ring_allgather(PtrTable ring, SegTable seg, int N, int step) {
     const size_t v = t * kTile + tid;
     R raw[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) raw[u] = ld<NT>(reinterpret_cast<const R*>(from) + v + u * kThreads);
+    for (int u = 0; u < U; ++u) raw[u] = ld<POL>(reinterpret_cast<const R*>(from) + v + u * kThreads);
 #pragma unroll
-    for (int u = 0; u < U; ++u) st<NT>(reinterpret_cast<R*>(to) + v + u * kThreads, raw[u]);
+    for (int u = 0; u < U; ++u) st<POL>(reinterpret_cast<R*>(to) + v + u * kThreads, raw[u]);
   }
   if (blockIdx.x == n_tiles % gridDim.x) {
     for (size_t v = n_tiles * kTile + tid; v < n_vec; v += kThreads)
-      st<NT>(reinterpret_cast<R*>(to) + v, ld<NT>(reinterpret_cast<const R*>(from) + v));
+      st<POL>(reinterpret_cast<R*>(to) + v, ld<POL>(reinterpret_cast<const R*>(from) + v));
     if constexpr (VEC > 1) {
       const size_t e = n_vec * VEC + tid;
       if (e < len) reinterpret_cast<R1*>(to)[e] = reinterpret_cast<const R1*>(from)[e];
@@ -369,10 +368,20 @@ k_ring_allgather(PtrTable ring, SegTable seg, int N, int step) {
   }
 }
 
-// ---- launch geometry -------------------------------------------------------
-unsigned total_blocks() {
+// ---- launch geometry and access policy -----------------------------------------
+// Measured on MI355X (64 Mi-element streams): a pure read stream reaches about 6.9 TB/s,
+// a pure write stream about 5.8 TB/s; mixing them costs a further few percent.
+//  * The N-reads-one-write reduction is fastest with non-temporal loads, ordinary stores
+//    (the L2 then gathers the one write stream) and only 2 workgroups per CU: fewer
+//    waves means fewer DRAM rows open at once across the N+1 streams.
+//  * The ring steps (up to 40-50 % writes, partly read-modify-write of `acc`) are fastest
+//    with non-temporal loads AND stores and 8 workgroups per CU.
+enum Kind { kKindReduce = 0, kKindRing = 1 };
+
+unsigned total_blocks(Kind kind) {
   const Tuning t = current_tuning();
-  const int per_cu = t.blocks_per_cu > 0 ? t.blocks_per_cu : kDefaultBlocksPerCu;
+  const int def = kind == kKindReduce ? 2 : 8;
+  const int per_cu = t.blocks_per_cu > 0 ? t.blocks_per_cu : def;
   return static_cast<unsigned>(device_cu_count()) * static_cast<unsigned>(per_cu);
 }
 
@@ -382,75 +391,88 @@ unsigned grid_x_for(size_t n_tiles, unsigned budget) {
   return n_tiles < budget ? static_cast<unsigned>(n_tiles) : budget;
 }
 
-bool plain_access() { return (current_tuning().flags & 1) != 0; }
+// bit 0: non-temporal loads, bit 1: non-temporal stores.  Tuning flags with bit 4 set
+// carry an explicit policy in their low two bits; otherwise the per-kind default applies.
+int access_policy(Kind kind) {
+  const int flags = current_tuning().flags;
+  if (flags & 0x10) return flags & 3;
+  return kind == kKindReduce ? 1 : 3;
+}
 
-template <typename T, int VEC, bool NT>
-hipError_t launch_reduce_fixed(const PtrTable& live, int N, size_t count, T* out, float scale,
-                               hipStream_t stream) {
-  const size_t tiles = count / VEC / (static_cast<size_t>(kThreads) * unroll_for(N));
-  const dim3 grid(grid_x_for(tiles, total_blocks())), block(kThreads);
-  switch (N) {
-#define FTAR_CASE(n) \
-  case n: k_reduce_masked<T, VEC, n, NT><<<grid, block, 0, stream>>>(live, out, scale, count); break;
-    FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
-    FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
-    FTAR_CASE(14) FTAR_CASE(15) FTAR_CASE(16)
-#undef FTAR_CASE
-    default: return hipErrorInvalidValue;
+// Calls f.template operator()<POL>() for the runtime policy.
+template <typename F>
+hipError_t with_policy(Kind kind, F f) {
+  switch (access_policy(kind)) {
+    case 0: return f.template operator()<0>();
+    case 1: return f.template operator()<1>();
+    case 2: return f.template operator()<2>();
+    default: return f.template operator()<3>();
   }
-  return hipGetLastError();
 }
 
-template <typename T, int VEC, bool NT>
-hipError_t launch_reduce_any(const PtrTable& live, int N, size_t count, T* out, float scale,
-                             hipStream_t stream) {
-  const size_t tiles = (count / VEC + kThreads - 1) / kThreads;
-  const dim3 grid(grid_x_for(tiles, total_blocks())), block(kThreads);
-  k_reduce_masked_any<T, VEC, NT><<<grid, block, 0, stream>>>(live, N, out, scale, count);
-  return hipGetLastError();
-}
+template <typename T, int VEC>
+struct ReduceFixed {
+  const PtrTable& live; int N; size_t count; T* out; float scale; hipStream_t stream;
+  template <int POL> hipError_t operator()() const {
+    const size_t tiles = count / VEC / (static_cast<size_t>(kThreads) * unroll_for(N));
+    const dim3 grid(grid_x_for(tiles, total_blocks(kKindReduce))), block(kThreads);
+    switch (N) {
+#define FTAR_CASE(n) \
+  case n: k_reduce_masked<T, VEC, n, POL><<<grid, block, 0, stream>>>(live, out, scale, count); break;
+      FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
+      FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
+      FTAR_CASE(14) FTAR_CASE(15) FTAR_CASE(16)
+#undef FTAR_CASE
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
+};
+
+template <typename T, int VEC>
+struct ReduceAny {
+  const PtrTable& live; int N; size_t count; T* out; float scale; hipStream_t stream;
+  template <int POL> hipError_t operator()() const {
+    const size_t tiles = (count / VEC + kThreads - 1) / kThreads;
+    const dim3 grid(grid_x_for(tiles, total_blocks(kKindReduce))), block(kThreads);
+    k_reduce_masked_any<T, VEC, POL><<<grid, block, 0, stream>>>(live, N, out, scale, count);
+    return hipGetLastError();
+  }
+};
 
 template <typename T, int VECW>
 hipError_t reduce_masked_typed(const PtrTable& live, int N, size_t count, bool vec, void* out,
                                float scale, hipStream_t stream) {
   T* o = static_cast<T*>(out);
-  const bool plain = plain_access();
-  if (vec && N <= 16) {
-    return plain ? launch_reduce_fixed<T, VECW, false>(live, N, count, o, scale, stream)
-                 : launch_reduce_fixed<T, VECW, true>(live, N, count, o, scale, stream);
-  }
-  if (vec) {
-    return plain ? launch_reduce_any<T, VECW, false>(live, N, count, o, scale, stream)
-                 : launch_reduce_any<T, VECW, true>(live, N, count, o, scale, stream);
-  }
-  return plain ? launch_reduce_any<T, 1, false>(live, N, count, o, scale, stream)
-               : launch_reduce_any<T, 1, true>(live, N, count, o, scale, stream);
+  if (vec && N <= 16) return with_policy(kKindReduce, ReduceFixed<T, VECW>{live, N, count, o, scale, stream});
+  if (vec) return with_policy(kKindReduce, ReduceAny<T, VECW>{live, N, count, o, scale, stream});
+  return with_policy(kKindReduce, ReduceAny<T, 1>{live, N, count, o, scale, stream});
 }
 
-template <typename T, int VEC, bool NT>
-hipError_t launch_bucketed_t(const PtrTable& all, int n_replicas, const BucketTable& masks,
-                             int n_buckets, size_t first_elem, size_t bucket_elems, size_t count,
-                             const ScaleTable& scales, T* out, hipStream_t stream) {
-  const size_t tiles = (bucket_elems / VEC + kThreads - 1) / kThreads;
-  unsigned budget = total_blocks() / static_cast<unsigned>(n_buckets);
-  const dim3 grid(grid_x_for(tiles, budget), static_cast<unsigned>(n_buckets)), block(kThreads);
-  k_reduce_bucketed<T, VEC, NT><<<grid, block, 0, stream>>>(all, n_replicas, masks, scales,
-                                                            first_elem, bucket_elems, count, out);
-  return hipGetLastError();
-}
+template <typename T, int VEC>
+struct Bucketed {
+  const PtrTable& all; int n_replicas; const BucketTable& masks; int n_buckets; size_t first_elem;
+  size_t bucket_elems; size_t count; const ScaleTable& scales; T* out; hipStream_t stream;
+  template <int POL> hipError_t operator()() const {
+    const size_t tiles = (bucket_elems / VEC + kThreads - 1) / kThreads;
+    const unsigned budget = total_blocks(kKindReduce) / static_cast<unsigned>(n_buckets);
+    const dim3 grid(grid_x_for(tiles, budget), static_cast<unsigned>(n_buckets)), block(kThreads);
+    k_reduce_bucketed<T, VEC, POL><<<grid, block, 0, stream>>>(all, n_replicas, masks, scales,
+                                                               first_elem, bucket_elems, count, out);
+    return hipGetLastError();
+  }
+};
 
 template <typename T, int VECW>
 hipError_t bucketed_typed(const PtrTable& all, int n_replicas, const BucketTable& masks,
                           int n_buckets, size_t first_elem, size_t bucket_elems, size_t count,
                           const ScaleTable& scales, bool vec, void* out, hipStream_t stream) {
   T* o = static_cast<T*>(out);
-  const bool plain = plain_access();
-#define FTAR_GO(V, NTV) \
-  launch_bucketed_t<T, V, NTV>(all, n_replicas, masks, n_buckets, first_elem, bucket_elems, count, \
-                               scales, o, stream)
-  if (vec) return plain ? FTAR_GO(VECW, false) : FTAR_GO(VECW, true);
-  return plain ? FTAR_GO(1, false) : FTAR_GO(1, true);
-#undef FTAR_GO
+  if (vec)
+    return with_policy(kKindReduce, Bucketed<T, VECW>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
+                                         count, scales, o, stream});
+  return with_policy(kKindReduce, Bucketed<T, 1>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
+                                    count, scales, o, stream});
 }
 
 size_t longest_segment(const SegTable& seg, int N) {
@@ -462,38 +484,44 @@ size_t longest_segment(const SegTable& seg, int N) {
   return m;
 }
 
-template <typename T, int VEC, bool NT>
-hipError_t launch_ring_reduce_t(RingMode mode, const PtrTable& ring, int N, int step,
-                                const SegTable& seg, float* acc, float scale, hipStream_t stream) {
-  const size_t tiles = longest_segment(seg, N) / VEC / (static_cast<size_t>(kThreads) * 8);
-  const dim3 grid(grid_x_for(tiles, total_blocks() / static_cast<unsigned>(N)),
-                  static_cast<unsigned>(N)), block(kThreads);
-  switch (mode) {
-    case kRsFirst:
-      k_ring_reduce<T, VEC, kRsFirst, NT><<<grid, block, 0, stream>>>(ring, seg, N, step, acc, scale);
-      break;
-    case kRsMid:
-      k_ring_reduce<T, VEC, kRsMid, NT><<<grid, block, 0, stream>>>(ring, seg, N, step, acc, scale);
-      break;
-    case kRsLast:
-      k_ring_reduce<T, VEC, kRsLast, NT><<<grid, block, 0, stream>>>(ring, seg, N, step, acc, scale);
-      break;
-    case kRsOnly:
-      k_ring_reduce<T, VEC, kRsOnly, NT><<<grid, block, 0, stream>>>(ring, seg, N, step, acc, scale);
-      break;
-  }
-  return hipGetLastError();
+dim3 ring_grid(const SegTable& seg, int N, int vec) {
+  const size_t tiles = longest_segment(seg, N) / vec / (static_cast<size_t>(kThreads) * 8);
+  return dim3(grid_x_for(tiles, total_blocks(kKindRing) / static_cast<unsigned>(N)), static_cast<unsigned>(N));
 }
 
-template <typename T, int VEC, bool NT>
-hipError_t launch_ring_allgather_t(const PtrTable& ring, int N, int step, const SegTable& seg,
-                                   hipStream_t stream) {
-  const size_t tiles = longest_segment(seg, N) / VEC / (static_cast<size_t>(kThreads) * 8);
-  const dim3 grid(grid_x_for(tiles, total_blocks() / static_cast<unsigned>(N)),
-                  static_cast<unsigned>(N)), block(kThreads);
-  k_ring_allgather<T, VEC, NT><<<grid, block, 0, stream>>>(ring, seg, N, step);
-  return hipGetLastError();
-}
+template <typename T, int VEC>
+struct RingReduce {
+  RingMode mode; const PtrTable& ring; int N; int step; const SegTable& seg; float* acc; float scale;
+  hipStream_t stream;
+  template <int POL> hipError_t operator()() const {
+    const dim3 grid = ring_grid(seg, N, VEC), block(kThreads);
+    switch (mode) {
+      case kRsFirst:
+        k_ring_reduce<T, VEC, kRsFirst, POL><<<grid, block, 0, stream>>>(ring, seg, N, step, acc, scale);
+        break;
+      case kRsMid:
+        k_ring_reduce<T, VEC, kRsMid, POL><<<grid, block, 0, stream>>>(ring, seg, N, step, acc, scale);
+        break;
+      case kRsLast:
+        k_ring_reduce<T, VEC, kRsLast, POL><<<grid, block, 0, stream>>>(ring, seg, N, step, acc, scale);
+        break;
+      case kRsOnly:
+        k_ring_reduce<T, VEC, kRsOnly, POL><<<grid, block, 0, stream>>>(ring, seg, N, step, acc, scale);
+        break;
+    }
+    return hipGetLastError();
+  }
+};
+
+template <typename T, int VEC>
+struct RingAllgather {
+  const PtrTable& ring; int N; int step; const SegTable& seg; hipStream_t stream;
+  template <int POL> hipError_t operator()() const {
+    const dim3 grid = ring_grid(seg, N, VEC), block(kThreads);
+    k_ring_allgather<T, VEC, POL><<<grid, block, 0, stream>>>(ring, seg, N, step);
+    return hipGetLastError();
+  }
+};
 
 }  // namespace
 
@@ -519,29 +547,22 @@ hipError_t launch_reduce_bucketed(const PtrTable& all, int n_replicas, const Buc
 hipError_t launch_ring_reduce(RingMode mode, const PtrTable& ring, int n_live, int step,
                               const SegTable& seg, ftar_dtype_t dtype, bool vec, float* acc,
                               float scale, hipStream_t stream) {
-  const bool plain = plain_access();
-#define FTAR_GO(T, V, NTV) \
-  launch_ring_reduce_t<T, V, NTV>(mode, ring, n_live, step, seg, acc, scale, stream)
   if (dtype == FTAR_F32) {
-    if (vec) return plain ? FTAR_GO(float, 4, false) : FTAR_GO(float, 4, true);
-    return plain ? FTAR_GO(float, 1, false) : FTAR_GO(float, 1, true);
+    if (vec) return with_policy(kKindRing, RingReduce<float, 4>{mode, ring, n_live, step, seg, acc, scale, stream});
+    return with_policy(kKindRing, RingReduce<float, 1>{mode, ring, n_live, step, seg, acc, scale, stream});
   }
-  if (vec) return plain ? FTAR_GO(bf16, 4, false) : FTAR_GO(bf16, 4, true);
-  return plain ? FTAR_GO(bf16, 1, false) : FTAR_GO(bf16, 1, true);
-#undef FTAR_GO
+  if (vec) return with_policy(kKindRing, RingReduce<bf16, 4>{mode, ring, n_live, step, seg, acc, scale, stream});
+  return with_policy(kKindRing, RingReduce<bf16, 1>{mode, ring, n_live, step, seg, acc, scale, stream});
 }
 
 hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, const SegTable& seg,
                                  ftar_dtype_t dtype, bool vec, hipStream_t stream) {
-  const bool plain = plain_access();
-#define FTAR_GO(T, V, NTV) launch_ring_allgather_t<T, V, NTV>(ring, n_live, step, seg, stream)
   if (dtype == FTAR_F32) {
-    if (vec) return plain ? FTAR_GO(float, 4, false) : FTAR_GO(float, 4, true);
-    return plain ? FTAR_GO(float, 1, false) : FTAR_GO(float, 1, true);
+    if (vec) return with_policy(kKindRing, RingAllgather<float, 4>{ring, n_live, step, seg, stream});
+    return with_policy(kKindRing, RingAllgather<float, 1>{ring, n_live, step, seg, stream});
   }
-  if (vec) return plain ? FTAR_GO(bf16, 8, false) : FTAR_GO(bf16, 8, true);
-  return plain ? FTAR_GO(bf16, 1, false) : FTAR_GO(bf16, 1, true);
-#undef FTAR_GO
+  if (vec) return with_policy(kKindRing, RingAllgather<bf16, 8>{ring, n_live, step, seg, stream});
+  return with_policy(kKindRing, RingAllgather<bf16, 1>{ring, n_live, step, seg, stream});
 }
 
 }  // namespace ftar
