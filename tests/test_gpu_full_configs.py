@@ -1,0 +1,155 @@
+"""GPU parity at the full sizes of the five benchmark workloads, in the launch configuration
+bench.py times.  Outputs are compared bit for bit with the CPU oracle on sampled slabs
+(always including the first and last elements, portion / bucket boundaries and the places
+where 32-bit offsets would overflow); workloads the oracle finishes in about a second are
+compared on every element."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import assert_same, code, host, host_slab, say
+from paper_2602_00277_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+SLAB = 1 << 16
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2602_00277_amd import binding
+    binding.lib()
+    return binding
+
+
+def _slab_starts(count, special, n_random, seed):
+    rng = np.random.default_rng(seed)
+    starts = {0, max(0, count - SLAB)}
+    for s in special:
+        for d in (-SLAB // 2, 0):
+            starts.add(min(max(0, s + d), max(0, count - SLAB)))
+    for s in rng.integers(0, max(1, count - SLAB), n_random):
+        starts.add(int(s))
+    return sorted(starts)
+
+
+def test_cfg1_all_elements(B, oracle):
+    w = W.configs()[0]
+    say(w.name)
+    bufs = W.draw_replicas(w, "cuda")
+    out = torch.empty(w.count, dtype=w.dtype, device="cuda")
+    B.ftar_reduce_masked(bufs, w.live_mask, out)
+    torch.cuda.synchronize()
+    hb = [host(b) for b in bufs]
+    want = oracle.reduce_masked(hb, w.live_mask, code(w.dtype))
+    assert_same(host(out), want, w.name)
+    # against the exact mean: |got - ref| <= 1e-6 * mean(|x|) per element
+    ref, mag = oracle.reduce_f64(hb, w.live_mask, code(w.dtype))
+    assert np.all(np.abs(host(out).astype(np.float64) - ref) <= 1e-6 * mag)
+
+
+def test_cfg2_all_elements(B, oracle):
+    w = W.configs()[1]
+    say(w.name)
+    bufs = W.draw_replicas(w, "cuda")          # replica 3 is NaN-poisoned
+    out = torch.empty(w.count, dtype=w.dtype, device="cuda")
+    B.ftar_reduce_masked(bufs, w.live_mask, out)
+    torch.cuda.synchronize()
+    want = oracle.reduce_masked([host(b) for b in bufs], w.live_mask, code(w.dtype))
+    assert_same(host(out), want, w.name)
+
+
+def _ring_slabs(B, oracle, w, schedule):
+    """schedule: list of (mask, n_rs_steps or None for the full ring)."""
+    n, count, chunk = w.n_replicas, w.count, w.chunk_elems
+    final_mask = schedule[-1][0]
+    special = oracle.geometry(n, final_mask, count, chunk)[1:-1] + \
+        oracle.geometry(n, schedule[0][0], count, chunk)[1:-1] + [1 << 30 // 1, (1 << 31) // w.elem_bytes]
+    starts = _slab_starts(count, special, 12, seed=w.seed)
+    bufs = W.draw_replicas(w, "cuda")
+    orig = {s: [host_slab(b, s, s + SLAB) for b in bufs] for s in starts}
+    acc = torch.empty(count, dtype=torch.float32, device="cuda")
+    for mask, rs_steps in schedule:
+        plan = B.ftar_plan(n, mask, count, chunk, w.dtype)
+        if rs_steps is None:
+            B.ring_allreduce(plan, bufs, acc)
+        else:
+            for s in range(rs_steps):
+                B.ftar_reduce_step(plan, s, bufs, acc)
+        B.ftar_plan_destroy(plan)
+    torch.cuda.synchronize()
+    for s in starts:
+        want = oracle.ring_closed_form(orig[s], final_mask, count, chunk, code(w.dtype), begin=s, length=SLAB)
+        for r in range(n):
+            got = host_slab(bufs[r], s, s + SLAB)
+            assert_same(got, want if (final_mask >> r) & 1 else orig[s][r], "%s slab %d replica %d" % (w.name, s, r))
+    # every live replica ends bit-identical over the whole buffer (all-reduce postcondition)
+    live = [r for r in range(n) if (final_mask >> r) & 1]
+    for r in live[1:]:
+        assert torch.equal(bufs[r].view(torch.int16), bufs[live[0]].view(torch.int16)), r
+
+
+def test_cfg3a_clean_sixteen_ring(B, oracle):
+    w = W.configs()[2]
+    say(w.name, "clean 16-ring")
+    _ring_slabs(B, oracle, w, [(0xFFFF, None)])
+
+
+def test_cfg3b_replica_leaves_before_step_five(B, oracle):
+    w = W.configs()[2]
+    say(w.name, "5 RS steps, replica 9 leaves, re-plan for 15")
+    _ring_slabs(B, oracle, w, [(0xFFFF, w.replan_before_step), (0xFFFF & ~(1 << w.replan_leaver), None)])
+
+
+def test_cfg4_two_billion_elements(B, oracle):
+    w = W.configs()[3]
+    say(w.name)
+    bufs = W.draw_replicas(w, "cuda")
+    out = torch.empty(w.count, dtype=w.dtype, device="cuda")
+    B.ftar_reduce_masked(bufs, w.live_mask, out)
+    torch.cuda.synchronize()
+    starts = _slab_starts(w.count, [1 << 30, (1 << 31) // 2, w.count // 2], 40, seed=w.seed)
+    zeros = 0
+    for s in starts:
+        hb = [host_slab(b, s, s + SLAB) for b in bufs]
+        zeros += int(sum((h & 0x7FFF == 0).sum() for h in hb))
+        want = oracle.reduce_masked(hb, w.live_mask, code(w.dtype))
+        assert_same(host_slab(out, s, s + SLAB), want, "%s slab %d" % (w.name, s))
+    assert zeros > 0            # the workload really contains exact zeros
+    # at any size: the same sum written with torch's fp32 ops in the same order, every element
+    step = 1 << 27
+    for lo in range(0, w.count, step):
+        hi = min(w.count, lo + step)
+        a = bufs[0][lo:hi].float()
+        for r in range(1, w.n_replicas):
+            a = a + bufs[r][lo:hi].float()
+        a = (a * 0.125).to(torch.bfloat16)
+        assert torch.equal(a.view(torch.int16), out[lo:hi].view(torch.int16)), lo
+
+
+def test_cfg5_bucketed_dynamic_membership(B, oracle):
+    w = W.configs()[4]
+    say(w.name)
+    edges = W.bucket_bounds(w.count, w.bucket_elems)
+    n_buckets = len(edges) - 1
+    assert n_buckets == 21 and edges[-1] - edges[-2] == 12 * W.M
+    masks = W.bucket_masks(w.n_replicas, n_buckets, w.bucket_p_live, w.seed)
+    assert any(m != 0xFF for m in masks)
+    bufs = W.draw_replicas(w, "cuda")
+    out = torch.empty(w.count, dtype=w.dtype, device="cuda")
+    B.ftar_reduce_masked_bucketed(bufs, masks, w.bucket_elems, out)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(w.seed)
+    for b in range(n_buckets):
+        lo, hi = edges[b], edges[b + 1]
+        for s in sorted({lo, hi - SLAB, int(rng.integers(lo, hi - SLAB))}):
+            hb = [host_slab(x, s, s + SLAB) if (masks[b] >> r) & 1 else None for r, x in enumerate(bufs)]
+            want = oracle.reduce_masked(hb, masks[b], code(w.dtype))
+            assert_same(host_slab(out, s, s + SLAB), want, "%s bucket %d slab %d" % (w.name, b, s))
+    # the same through the caller-side loop of one-shot calls with offset pointers
+    out2 = torch.empty(w.count, dtype=w.dtype, device="cuda")
+    for b in range(n_buckets):
+        lo, hi = edges[b], edges[b + 1]
+        B.ftar_reduce_masked([x[lo:hi] for x in bufs], masks[b], out2[lo:hi])
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int32), out2.view(torch.int32))
