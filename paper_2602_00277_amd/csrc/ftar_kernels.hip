@@ -184,21 +184,27 @@ __device__ __forceinline__ void sum_range(T* const (&src)[NSRC], const float* ac
   }
 }
 
-// Vectors per lane per tile for an N-source sum: aim at 16 x 16-byte loads in flight per lane.
-__host__ __device__ constexpr int unroll_for(int n_src) {
+// Vectors per lane per tile for an N-source sum.  Two choices per N are compiled: "wide"
+// (about 16 x 16-byte loads in flight per lane) and "narrow" (half of that).
+__host__ __device__ constexpr int unroll_wide(int n_src) {
   return n_src <= 2 ? 8 : n_src <= 4 ? 4 : n_src <= 8 ? 2 : 1;
+}
+__host__ __device__ constexpr int unroll_narrow(int n_src) {
+  return unroll_wide(n_src) > 1 ? unroll_wide(n_src) / 2 : 1;
 }
 
 // ---- any number of sources (runtime N): loads in groups of 8 ---------------
 template <typename T, int VEC, int POL>
-__device__ __forceinline__ void sum_any_one(T* const* s_tab, int N, T* out, float scale, size_t v) {
+__device__ __forceinline__ void sum_any_one(T* const* s_tab, size_t base, int N, T* out, float scale,
+                                            size_t v) {
   typedef typename Raw<T, VEC>::type R;
   float a[VEC];
   for (int j0 = 0; j0 < N; j0 += 8) {
     R raw[8];
 #pragma unroll
     for (int jj = 0; jj < 8; ++jj)
-      if (j0 + jj < N) raw[jj] = ld<POL>(reinterpret_cast<const R*>(uniform_ptr(s_tab[j0 + jj])) + v);
+      if (j0 + jj < N)
+        raw[jj] = ld<POL>(reinterpret_cast<const R*>(uniform_ptr(s_tab[j0 + jj]) + base) + v);
 #pragma unroll
     for (int jj = 0; jj < 8; ++jj) {
       if (j0 + jj < N) {
@@ -220,16 +226,16 @@ __device__ __forceinline__ void sum_any_one(T* const* s_tab, int N, T* out, floa
 }
 
 template <typename T, int VEC, int POL>
-__device__ __forceinline__ void sum_any_range(T* const* s_tab, int N, T* out, float scale, size_t len,
-                                              unsigned bx, unsigned gx) {
+__device__ __forceinline__ void sum_any_range(T* const* s_tab, size_t base, int N, T* out, float scale,
+                                              size_t len, unsigned bx, unsigned gx) {
   const size_t n_vec = len / VEC;
   for (size_t v = static_cast<size_t>(bx) * kThreads + threadIdx.x; v < n_vec;
        v += static_cast<size_t>(gx) * kThreads)
-    sum_any_one<T, VEC, POL>(s_tab, N, out, scale, v);
+    sum_any_one<T, VEC, POL>(s_tab, base, N, out, scale, v);
   if constexpr (VEC > 1) {
     if (bx == 0) {
       const size_t e = n_vec * VEC + threadIdx.x;
-      if (e < len) sum_any_one<T, 1, POL>(s_tab, N, out, scale, e);
+      if (e < len) sum_any_one<T, 1, POL>(s_tab, base, N, out, scale, e);
     }
   }
 }
@@ -237,7 +243,7 @@ __device__ __forceinline__ void sum_any_range(T* const* s_tab, int N, T* out, fl
 // ---- kernels -------------------------------------------------------------
 
 // One-shot masked mean over N live buffers (N fixed at compile time, 1..16).
-template <typename T, int VEC, int N, int POL>
+template <typename T, int VEC, int N, int U, int POL>
 __global__ void __launch_bounds__(kThreads)
 k_reduce_masked(PtrTable live, T* out, float scale, size_t count) {
   __shared__ T* s_tab[kMaxReplicas];
@@ -246,8 +252,8 @@ k_reduce_masked(PtrTable live, T* out, float scale, size_t count) {
   T* src[N];
 #pragma unroll
   for (int j = 0; j < N; ++j) src[j] = uniform_ptr(s_tab[j]);
-  sum_range<T, VEC, N, false, false, unroll_for(N), POL>(src, nullptr, nullptr, out, scale, count,
-                                                        blockIdx.x, gridDim.x);
+  sum_range<T, VEC, N, false, false, U, POL>(src, nullptr, nullptr, out, scale, count, blockIdx.x,
+                                             gridDim.x);
 }
 
 // One-shot masked mean, any N up to 64 (also the element-wise path for unaligned buffers).
@@ -257,113 +263,194 @@ k_reduce_masked_any(PtrTable live, int N, T* out, float scale, size_t count) {
   __shared__ T* s_tab[kMaxReplicas];
   if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<T*>(live.p[threadIdx.x]);
   __syncthreads();
-  sum_any_range<T, VEC, POL>(s_tab, N, out, scale, count, blockIdx.x, gridDim.x);
+  sum_any_range<T, VEC, POL>(s_tab, 0, N, out, scale, count, blockIdx.x, gridDim.x);
 }
+
+__device__ __forceinline__ unsigned long long uniform_u64(unsigned long long x) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(x));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(x >> 32));
+  return (static_cast<unsigned long long>(hi) << 32) | lo;
+}
+
+// One block-wide tile starting at the given pointers, `rem` = elements left in the portion
+// from there: the unrolled body when a whole tile is left, the checked loop over `rem` otherwise.
+// (Written as a branch on `rem`, not as min(rem, tile): hipcc 7.2 miscompiles a select on a
+// wave-uniform 64-bit unsigned compare here, reading a stale SCC.)
+template <typename T, int VEC, int NSRC, bool ACC_IN, bool ACC_OUT, int U, int POL>
+__device__ __forceinline__ void sum_block_tile(T* const (&src)[NSRC], const float* acc_in,
+                                               float* acc_out, T* out, float scale, size_t rem) {
+  if (rem >= static_cast<size_t>(kThreads) * U * VEC)
+    sum_tile<T, VEC, NSRC, ACC_IN, ACC_OUT, U, POL>(src, acc_in, acc_out, out, scale, threadIdx.x);
+  else
+    sum_range<T, VEC, NSRC, ACC_IN, ACC_OUT, 1, POL>(src, acc_in, acc_out, out, scale, rem, 0u, 1u);
+}
+
+// The kernels below walk the whole element range as ONE sequence of tiles, grid-strided, and
+// look up which portion (or bucket) a tile belongs to.  All blocks then work inside one narrow
+// moving window of `acc` and of one or two replica buffers, which keeps few DRAM rows open;
+// giving every portion its own share of the grid instead opens N windows in 2N buffers at once
+// and costs about 10 % of the bandwidth at 16 portions.
+
+constexpr int kBucketUnroll = 4;  // vectors per lane in one tile of the bucketed kernel
 
 template <typename T, int VEC, int N, int POL>
-__device__ __forceinline__ void bucket_fixed_n(T* const* s_tab, T* out, float scale, size_t len) {
+__device__ __forceinline__ void bucket_tile_n(T* const* s_tab, T* out, float scale, size_t begin,
+                                              size_t rem) {
+  constexpr int UN = unroll_narrow(N) < kBucketUnroll ? unroll_narrow(N) : kBucketUnroll;
   T* src[N];
 #pragma unroll
-  for (int j = 0; j < N; ++j) src[j] = uniform_ptr(s_tab[j]);
-  sum_range<T, VEC, N, false, false, unroll_for(N), POL>(src, nullptr, nullptr, out, scale, len,
-                                                        blockIdx.x, gridDim.x);
+  for (int j = 0; j < N; ++j) src[j] = uniform_ptr(s_tab[j]) + begin;
+  if (rem >= static_cast<size_t>(kThreads) * kBucketUnroll * VEC) {
+#pragma unroll
+    for (int it = 0; it < kBucketUnroll / UN; ++it)
+      sum_tile<T, VEC, N, false, false, UN, POL>(src, nullptr, nullptr, out + begin, scale,
+                                                 static_cast<size_t>(it) * kThreads * UN + threadIdx.x);
+  } else {
+    sum_range<T, VEC, N, false, false, 1, POL>(src, nullptr, nullptr, out + begin, scale, rem, 0u, 1u);
+  }
 }
 
-// Masked mean with one live mask per bucket; blockIdx.y = bucket.  Each block
-// compacts its bucket's mask into the LDS pointer table (lane r places replica
-// r at the rank of its bit), then runs the N-specialised loop.
+// Masked mean with one live mask per bucket.  When a block's next tile lies in another bucket it
+// re-compacts that bucket's mask into the LDS pointer table (lane r places replica r at the rank
+// of its bit) and switches to the loop specialised for that bucket's N.
 template <typename T, int VEC, int POL>
 __global__ void __launch_bounds__(kThreads)
 k_reduce_bucketed(PtrTable all, int n_replicas, BucketTable masks, ScaleTable scales,
-                  size_t first_elem, size_t bucket_elems, size_t count, T* out) {
+                  size_t first_elem, size_t bucket_elems, size_t last_len, int n_buckets,
+                  size_t tiles_per_bucket, size_t total_tiles, T* out) {
+  // last_len = length of this launch's last bucket; tiles_per_bucket = ceil(bucket_elems / tile);
+  // total_tiles = (n_buckets-1)*tiles_per_bucket + ceil(last_len / tile): all computed on the host.
   __shared__ T* s_tab[kMaxReplicas];
-  const size_t begin = first_elem + static_cast<size_t>(blockIdx.y) * bucket_elems;
-  const size_t len = (count - begin < bucket_elems) ? count - begin : bucket_elems;
-  const unsigned long long mask = masks.mask[blockIdx.y];
-  const unsigned r = threadIdx.x;
-  if (r < static_cast<unsigned>(n_replicas) && ((mask >> r) & 1ull)) {
-    const int pos = __popcll(mask & ((1ull << r) - 1ull));
-    s_tab[pos] = static_cast<T*>(all.p[r]) + begin;
-  }
-  __syncthreads();
-  const int N = __popcll(mask);
-  const float scale = scales.s[N];
-  T* o = out + begin;
-  if constexpr (VEC > 1) {
-    switch (N) {
-#define FTAR_CASE(n) case n: bucket_fixed_n<T, VEC, n, POL>(s_tab, o, scale, len); return;
-      FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
-      FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
-      FTAR_CASE(14) FTAR_CASE(15) FTAR_CASE(16)
+  constexpr size_t kTileElems = static_cast<size_t>(kThreads) * kBucketUnroll * VEC;
+  int cur = -1, N = 0;
+  float scale = 0.0f;
+  for (size_t g = blockIdx.x; g < total_tiles; g += gridDim.x) {
+    const int b = static_cast<int>(g / tiles_per_bucket);
+    const size_t in_bucket = (g - b * tiles_per_bucket) * kTileElems;  // offset of the tile in its bucket
+    const size_t begin = first_elem + b * bucket_elems + in_bucket;
+    const size_t rem = (b == n_buckets - 1 ? last_len : bucket_elems) - in_bucket;
+    if (b != cur) {  // same for every lane of the block
+      __syncthreads();                 // nobody still reads the previous bucket's table
+      const unsigned long long mask = masks.mask[b];
+      const unsigned r = threadIdx.x;
+      if (r < static_cast<unsigned>(n_replicas) && ((mask >> r) & 1ull))
+        s_tab[__popcll(mask & ((1ull << r) - 1ull))] = static_cast<T*>(all.p[r]);
+      __syncthreads();
+      cur = b;
+      N = __popcll(mask);
+      scale = scales.s[N];
+    }
+    bool done = false;
+    if constexpr (VEC > 1) {
+      done = true;
+      switch (N) {
+#define FTAR_CASE(n) case n: bucket_tile_n<T, VEC, n, POL>(s_tab, out, scale, begin, rem); break;
+        FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
+        FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
+        FTAR_CASE(14) FTAR_CASE(15) FTAR_CASE(16)
 #undef FTAR_CASE
-      default: break;
+        default: done = false; break;
+      }
+    }
+    if (!done) {
+      if (rem >= kTileElems) sum_any_range<T, VEC, POL>(s_tab, begin, N, out + begin, scale, kTileElems, 0u, 1u);
+      else sum_any_range<T, VEC, POL>(s_tab, begin, N, out + begin, scale, rem, 0u, 1u);
     }
   }
-  sum_any_range<T, VEC, POL>(s_tab, N, o, scale, len, blockIdx.x, gridDim.x);
 }
 
-// One ReduceScatter step over all N portions; blockIdx.y = portion k.
-template <typename T, int VEC, int MODE, int POL>
+// Portion lookup shared by the ring kernels: tile g of the flat sequence -> portion k and the
+// tile's first element.  s_tile[k] = number of tiles before portion k.
+struct RingTile {
+  int k;
+  size_t begin, rem;  // rem = elements from `begin` to the end of portion k (may exceed one tile)
+};
+
+template <size_t kTileElems>
+__device__ __forceinline__ RingTile ring_tile_of(size_t g, int& k, size_t& next,
+                                                 const unsigned long long* s_seg,
+                                                 const unsigned long long* s_tile) {
+  while (g >= next) {  // also steps over empty portions
+    ++k;
+    next = uniform_u64(s_tile[k + 1]);
+  }
+  const size_t begin = uniform_u64(s_seg[k]) + (g - uniform_u64(s_tile[k])) * kTileElems;
+  return RingTile{k, begin, uniform_u64(s_seg[k + 1]) - begin};
+}
+
+// One ReduceScatter step over all N portions.
+template <typename T, int VEC, int MODE, int U, int POL>
 __global__ void __launch_bounds__(kThreads)
-k_ring_reduce(PtrTable ring, SegTable seg, int N, int step, float* acc, float scale) {
+k_ring_reduce(PtrTable ring, SegTable seg, SegTable tile0, int N, int step, float* acc, float scale) {
   __shared__ T* s_tab[kMaxReplicas];
-  const int k = blockIdx.y;
-  const size_t begin = seg.begin[k];
-  const size_t len = seg.begin[k + 1] - begin;
-  if (len == 0) return;  // uniform for the block
-  if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<T*>(ring.p[threadIdx.x]);
+  __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
+  const unsigned tid = threadIdx.x;
+  if (tid < static_cast<unsigned>(N)) s_tab[tid] = static_cast<T*>(ring.p[tid]);
+  if (tid <= static_cast<unsigned>(N)) {
+    s_seg[tid] = seg.begin[tid];
+    s_tile[tid] = tile0.begin[tid];
+  }
   __syncthreads();
-  constexpr int U = 8;
-  float* a = acc ? acc + begin : nullptr;
-  if constexpr (MODE == kRsFirst) {
-    T* src[2] = {uniform_ptr(s_tab[k]) + begin, uniform_ptr(s_tab[(k + 1) % N]) + begin};
-    sum_range<T, VEC, 2, false, true, U, POL>(src, nullptr, a, nullptr, scale, len, blockIdx.x, gridDim.x);
-  } else if constexpr (MODE == kRsMid) {
-    T* src[1] = {uniform_ptr(s_tab[(k + step + 1) % N]) + begin};
-    sum_range<T, VEC, 1, true, true, U, POL>(src, a, a, nullptr, scale, len, blockIdx.x, gridDim.x);
-  } else if constexpr (MODE == kRsLast) {
-    T* src[1] = {uniform_ptr(s_tab[(k + N - 1) % N]) + begin};
-    sum_range<T, VEC, 1, true, false, U, POL>(src, a, nullptr, src[0], scale, len, blockIdx.x, gridDim.x);
-  } else {  // kRsOnly, N == 2
-    T* src[2] = {uniform_ptr(s_tab[k]) + begin, uniform_ptr(s_tab[(k + 1) % N]) + begin};
-    sum_range<T, VEC, 2, false, false, U, POL>(src, nullptr, nullptr, src[1], scale, len, blockIdx.x, gridDim.x);
+  constexpr size_t kTileElems = static_cast<size_t>(kThreads) * U * VEC;
+  const size_t total = uniform_u64(s_tile[N]);
+  int k = 0;
+  size_t next = uniform_u64(s_tile[1]);
+  for (size_t g = blockIdx.x; g < total; g += gridDim.x) {
+    const RingTile t = ring_tile_of<kTileElems>(g, k, next, s_seg, s_tile);
+    float* a = acc + t.begin;  // never dereferenced in the N == 2 mode
+    if constexpr (MODE == kRsFirst) {
+      T* src[2] = {uniform_ptr(s_tab[t.k]) + t.begin, uniform_ptr(s_tab[(t.k + 1) % N]) + t.begin};
+      sum_block_tile<T, VEC, 2, false, true, U, POL>(src, nullptr, a, nullptr, scale, t.rem);
+    } else if constexpr (MODE == kRsMid) {
+      T* src[1] = {uniform_ptr(s_tab[(t.k + step + 1) % N]) + t.begin};
+      sum_block_tile<T, VEC, 1, true, true, U, POL>(src, a, a, nullptr, scale, t.rem);
+    } else if constexpr (MODE == kRsLast) {
+      T* src[1] = {uniform_ptr(s_tab[(t.k + N - 1) % N]) + t.begin};
+      sum_block_tile<T, VEC, 1, true, false, U, POL>(src, a, nullptr, src[0], scale, t.rem);
+    } else {  // kRsOnly, N == 2
+      T* src[2] = {uniform_ptr(s_tab[t.k]) + t.begin, uniform_ptr(s_tab[(t.k + 1) % N]) + t.begin};
+      sum_block_tile<T, VEC, 2, false, false, U, POL>(src, nullptr, nullptr, src[1], scale, t.rem);
+    }
   }
 }
 
 // One AllGather step over all N portions: bit copy from ring position k+t-1 to k+t.
-template <typename T, int VEC, int POL>
+template <typename T, int VEC, int U, int POL>
 __global__ void __launch_bounds__(kThreads)
-k_ring_allgather(PtrTable ring, SegTable seg, int N, int step) {
+k_ring_allgather(PtrTable ring, SegTable seg, SegTable tile0, int N, int step) {
   __shared__ T* s_tab[kMaxReplicas];
+  __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
   typedef typename Raw<T, VEC>::type R;
   typedef typename Raw<T, 1>::type R1;
-  const int k = blockIdx.y;
-  const size_t begin = seg.begin[k];
-  const size_t len = seg.begin[k + 1] - begin;
-  if (len == 0) return;
-  if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<T*>(ring.p[threadIdx.x]);
-  __syncthreads();
-  const T* from = uniform_ptr(s_tab[(k + step + N - 1) % N]) + begin;
-  T* to = uniform_ptr(s_tab[(k + step) % N]) + begin;
-  constexpr int U = 8;
-  constexpr size_t kTile = static_cast<size_t>(kThreads) * U;
   const unsigned tid = threadIdx.x;
-  const size_t n_vec = len / VEC;
-  const size_t n_tiles = n_vec / kTile;
-  for (size_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-    const size_t v = t * kTile + tid;
-    R raw[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) raw[u] = ld<POL>(reinterpret_cast<const R*>(from) + v + u * kThreads);
-#pragma unroll
-    for (int u = 0; u < U; ++u) st<POL>(reinterpret_cast<R*>(to) + v + u * kThreads, raw[u]);
+  if (tid < static_cast<unsigned>(N)) s_tab[tid] = static_cast<T*>(ring.p[tid]);
+  if (tid <= static_cast<unsigned>(N)) {
+    s_seg[tid] = seg.begin[tid];
+    s_tile[tid] = tile0.begin[tid];
   }
-  if (blockIdx.x == n_tiles % gridDim.x) {
-    for (size_t v = n_tiles * kTile + tid; v < n_vec; v += kThreads)
-      st<POL>(reinterpret_cast<R*>(to) + v, ld<POL>(reinterpret_cast<const R*>(from) + v));
-    if constexpr (VEC > 1) {
-      const size_t e = n_vec * VEC + tid;
-      if (e < len) reinterpret_cast<R1*>(to)[e] = reinterpret_cast<const R1*>(from)[e];
+  __syncthreads();
+  constexpr size_t kTileElems = static_cast<size_t>(kThreads) * U * VEC;
+  const size_t total = uniform_u64(s_tile[N]);
+  int k = 0;
+  size_t next = uniform_u64(s_tile[1]);
+  for (size_t g = blockIdx.x; g < total; g += gridDim.x) {
+    const RingTile t = ring_tile_of<kTileElems>(g, k, next, s_seg, s_tile);
+    const T* from = uniform_ptr(s_tab[(t.k + step + N - 1) % N]) + t.begin;
+    T* to = uniform_ptr(s_tab[(t.k + step) % N]) + t.begin;
+    if (t.rem >= kTileElems) {
+      R raw[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) raw[u] = ld<POL>(reinterpret_cast<const R*>(from) + tid + u * kThreads);
+#pragma unroll
+      for (int u = 0; u < U; ++u) st<POL>(reinterpret_cast<R*>(to) + tid + u * kThreads, raw[u]);
+    } else {
+      const size_t n_vec = t.rem / VEC;
+      for (size_t v = tid; v < n_vec; v += kThreads)
+        st<POL>(reinterpret_cast<R*>(to) + v, ld<POL>(reinterpret_cast<const R*>(from) + v));
+      if constexpr (VEC > 1) {
+        const size_t e = n_vec * VEC + tid;
+        if (e < t.rem) reinterpret_cast<R1*>(to)[e] = reinterpret_cast<const R1*>(from)[e];
+      }
     }
   }
 }
@@ -399,6 +486,9 @@ int access_policy(Kind kind) {
   return kind == kKindReduce ? 1 : 3;
 }
 
+// Tuning flag bit 5 selects the wide tiles for the one-shot reduce (default: narrow).
+bool wide_tiles() { return (current_tuning().flags & 0x20) != 0; }
+
 // Calls f.template operator()<POL>() for the runtime policy.
 template <typename F>
 hipError_t with_policy(Kind kind, F f) {
@@ -414,11 +504,20 @@ template <typename T, int VEC>
 struct ReduceFixed {
   const PtrTable& live; int N; size_t count; T* out; float scale; hipStream_t stream;
   template <int POL> hipError_t operator()() const {
-    const size_t tiles = count / VEC / (static_cast<size_t>(kThreads) * unroll_for(N));
+    const bool wide = wide_tiles();
+    const int U = wide ? unroll_wide(N) : unroll_narrow(N);
+    const size_t tiles = count / VEC / (static_cast<size_t>(kThreads) * U);
     const dim3 grid(grid_x_for(tiles, total_blocks(kKindReduce))), block(kThreads);
     switch (N) {
-#define FTAR_CASE(n) \
-  case n: k_reduce_masked<T, VEC, n, POL><<<grid, block, 0, stream>>>(live, out, scale, count); break;
+#define FTAR_CASE(n)                                                                              \
+  case n:                                                                                         \
+    if (wide)                                                                                     \
+      k_reduce_masked<T, VEC, n, unroll_wide(n), POL><<<grid, block, 0, stream>>>(live, out, scale, \
+                                                                                  count);         \
+    else                                                                                          \
+      k_reduce_masked<T, VEC, n, unroll_narrow(n), POL><<<grid, block, 0, stream>>>(live, out,    \
+                                                                                    scale, count); \
+    break;
       FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
       FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
       FTAR_CASE(14) FTAR_CASE(15) FTAR_CASE(16)
@@ -454,11 +553,16 @@ struct Bucketed {
   const PtrTable& all; int n_replicas; const BucketTable& masks; int n_buckets; size_t first_elem;
   size_t bucket_elems; size_t count; const ScaleTable& scales; T* out; hipStream_t stream;
   template <int POL> hipError_t operator()() const {
-    const size_t tiles = (bucket_elems / VEC + kThreads - 1) / kThreads;
-    const unsigned budget = total_blocks(kKindReduce) / static_cast<unsigned>(n_buckets);
-    const dim3 grid(grid_x_for(tiles, budget), static_cast<unsigned>(n_buckets)), block(kThreads);
+    const size_t tile_elems = static_cast<size_t>(kThreads) * kBucketUnroll * VEC;
+    const size_t tiles_per_bucket = (bucket_elems + tile_elems - 1) / tile_elems;
+    const size_t last_begin = first_elem + static_cast<size_t>(n_buckets - 1) * bucket_elems;
+    const size_t last_len = count - last_begin < bucket_elems ? count - last_begin : bucket_elems;
+    const size_t tiles = static_cast<size_t>(n_buckets - 1) * tiles_per_bucket +
+                         (last_len + tile_elems - 1) / tile_elems;
+    const dim3 grid(grid_x_for(tiles, total_blocks(kKindReduce))), block(kThreads);
     k_reduce_bucketed<T, VEC, POL><<<grid, block, 0, stream>>>(all, n_replicas, masks, scales,
-                                                               first_elem, bucket_elems, count, out);
+                                                               first_elem, bucket_elems, last_len,
+                                                               n_buckets, tiles_per_bucket, tiles, out);
     return hipGetLastError();
   }
 };
@@ -475,39 +579,44 @@ hipError_t bucketed_typed(const PtrTable& all, int n_replicas, const BucketTable
                                     count, scales, o, stream});
 }
 
-size_t longest_segment(const SegTable& seg, int N) {
-  size_t m = 0;
-  for (int k = 0; k < N; ++k) {
-    const size_t len = seg.begin[k + 1] - seg.begin[k];
-    if (len > m) m = len;
-  }
-  return m;
+// Vectors per lane per tile in the ring kernels: tuning flag bits 8..11 (2, 4 or 8), default 4.
+int ring_unroll() {
+  const int u = (current_tuning().flags >> 8) & 0xf;
+  return (u == 2 || u == 8) ? u : 4;
 }
 
-dim3 ring_grid(const SegTable& seg, int N, int vec) {
-  const size_t tiles = longest_segment(seg, N) / vec / (static_cast<size_t>(kThreads) * 8);
-  return dim3(grid_x_for(tiles, total_blocks(kKindRing) / static_cast<unsigned>(N)), static_cast<unsigned>(N));
+// Tiles before each portion (tile = kThreads*U*vec elements; the last tile of a portion may be short).
+SegTable ring_tiles(const SegTable& seg, int N, int vec, int U) {
+  SegTable t;
+  const size_t tile_elems = static_cast<size_t>(kThreads) * U * vec;
+  t.begin[0] = 0;
+  for (int k = 0; k < N; ++k)
+    t.begin[k + 1] = t.begin[k] + (seg.begin[k + 1] - seg.begin[k] + tile_elems - 1) / tile_elems;
+  for (int k = N + 1; k <= kMaxReplicas; ++k) t.begin[k] = t.begin[N];
+  return t;
 }
 
 template <typename T, int VEC>
 struct RingReduce {
   RingMode mode; const PtrTable& ring; int N; int step; const SegTable& seg; float* acc; float scale;
   hipStream_t stream;
+  template <int MODE, int U, int POL> void go() const {
+    const SegTable tiles = ring_tiles(seg, N, VEC, U);
+    const dim3 grid(grid_x_for(tiles.begin[N], total_blocks(kKindRing))), block(kThreads);
+    k_ring_reduce<T, VEC, MODE, U, POL><<<grid, block, 0, stream>>>(ring, seg, tiles, N, step, acc, scale);
+  }
+  template <int MODE, int POL> void pick_unroll() const {
+    const int U = ring_unroll();
+    if (U == 2) go<MODE, 2, POL>();
+    else if (U == 8) go<MODE, 8, POL>();
+    else go<MODE, 4, POL>();
+  }
   template <int POL> hipError_t operator()() const {
-    const dim3 grid = ring_grid(seg, N, VEC), block(kThreads);
     switch (mode) {
-      case kRsFirst:
-        k_ring_reduce<T, VEC, kRsFirst, POL><<<grid, block, 0, stream>>>(ring, seg, N, step, acc, scale);
-        break;
-      case kRsMid:
-        k_ring_reduce<T, VEC, kRsMid, POL><<<grid, block, 0, stream>>>(ring, seg, N, step, acc, scale);
-        break;
-      case kRsLast:
-        k_ring_reduce<T, VEC, kRsLast, POL><<<grid, block, 0, stream>>>(ring, seg, N, step, acc, scale);
-        break;
-      case kRsOnly:
-        k_ring_reduce<T, VEC, kRsOnly, POL><<<grid, block, 0, stream>>>(ring, seg, N, step, acc, scale);
-        break;
+      case kRsFirst: pick_unroll<kRsFirst, POL>(); break;
+      case kRsMid: pick_unroll<kRsMid, POL>(); break;
+      case kRsLast: pick_unroll<kRsLast, POL>(); break;
+      case kRsOnly: pick_unroll<kRsOnly, POL>(); break;
     }
     return hipGetLastError();
   }
@@ -516,9 +625,16 @@ struct RingReduce {
 template <typename T, int VEC>
 struct RingAllgather {
   const PtrTable& ring; int N; int step; const SegTable& seg; hipStream_t stream;
+  template <int U, int POL> void go() const {
+    const SegTable tiles = ring_tiles(seg, N, VEC, U);
+    const dim3 grid(grid_x_for(tiles.begin[N], total_blocks(kKindRing))), block(kThreads);
+    k_ring_allgather<T, VEC, U, POL><<<grid, block, 0, stream>>>(ring, seg, tiles, N, step);
+  }
   template <int POL> hipError_t operator()() const {
-    const dim3 grid = ring_grid(seg, N, VEC), block(kThreads);
-    k_ring_allgather<T, VEC, POL><<<grid, block, 0, stream>>>(ring, seg, N, step);
+    const int U = ring_unroll();
+    if (U == 2) go<2, POL>();
+    else if (U == 8) go<8, POL>();
+    else go<4, POL>();
     return hipGetLastError();
   }
 };
