@@ -456,20 +456,44 @@ k_ring_allgather(PtrTable ring, SegTable seg, SegTable tile0, int N, int step) {
 }
 
 // ---- launch geometry and access policy -----------------------------------------
-// Measured on MI355X (64 Mi-element streams): a pure read stream reaches about 6.9 TB/s,
-// a pure write stream about 5.8 TB/s; mixing them costs a further few percent.
-//  * The N-reads-one-write reduction is fastest with non-temporal loads, ordinary stores
-//    (the L2 then gathers the one write stream) and only 2 workgroups per CU: fewer
-//    waves means fewer DRAM rows open at once across the N+1 streams.
-//  * The ring steps (up to 40-50 % writes, partly read-modify-write of `acc`) are fastest
-//    with non-temporal loads AND stores and 8 workgroups per CU.
-enum Kind { kKindReduce = 0, kKindRing = 1 };
+// Defaults come from sweeps on MI355X.  Bare probe kernels there reach about 6.9 TB/s for pure
+// reads, 5.8 TB/s for pure writes and 6.0-6.4 TB/s for 7 reads + 1 write.  Two things matter:
+//  * Few waves.  One workgroup per CU (one wave per SIMD) with just enough loads in flight
+//    beats high occupancy by 5-10 %: all blocks then advance through one narrow window of
+//    every stream and few DRAM rows are open at a time.  Kernels with little in flight per
+//    wave (one or two streams) need 2-4 workgroups per CU instead.
+//  * The 256 MB Infinity Cache.  Non-temporal loads always help.  Stores: what one ring step
+//    writes is what the next step reads; when that fits the cache, ordinary stores keep it
+//    there (up to 6.8 TB/s of algorithmic bytes); when it does not, non-temporal stores are
+//    10-20 % faster than ordinary ones.
+struct LaunchCfg {
+  unsigned blocks;  // grid budget
+  int pol;          // bit 0: non-temporal loads, bit 1: non-temporal stores
+};
 
-unsigned total_blocks(Kind kind) {
+constexpr size_t kMiB = static_cast<size_t>(1) << 20;
+
+// Tuning overrides: blocks_per_cu > 0 replaces the default; flags with bit 4 set carry an
+// explicit policy in their low two bits.
+LaunchCfg launch_cfg(int default_blocks_per_cu, int default_pol) {
   const Tuning t = current_tuning();
-  const int def = kind == kKindReduce ? 2 : 8;
-  const int per_cu = t.blocks_per_cu > 0 ? t.blocks_per_cu : def;
-  return static_cast<unsigned>(device_cu_count()) * static_cast<unsigned>(per_cu);
+  const int per_cu = t.blocks_per_cu > 0 ? t.blocks_per_cu : default_blocks_per_cu;
+  LaunchCfg c;
+  c.blocks = static_cast<unsigned>(device_cu_count()) * static_cast<unsigned>(per_cu);
+  c.pol = (t.flags & 0x10) ? (t.flags & 3) : default_pol;
+  return c;
+}
+
+// N-reads-one-write reduction: ordinary stores; fewer workgroups the more streams there are.
+LaunchCfg reduce_cfg(int n_live) { return launch_cfg(n_live <= 2 ? 4 : n_live <= 4 ? 2 : 1, 1); }
+
+LaunchCfg ring_reduce_cfg(RingMode mode, size_t count) {
+  if (mode == kRsMid) return launch_cfg(1, count * 4 <= 256 * kMiB ? 1 : 3);
+  return launch_cfg(2, 3);
+}
+
+LaunchCfg ring_allgather_cfg(size_t count, size_t elem_bytes) {
+  return launch_cfg(2, count * elem_bytes <= 192 * kMiB ? 1 : 3);
 }
 
 unsigned grid_x_for(size_t n_tiles, unsigned budget) {
@@ -478,36 +502,28 @@ unsigned grid_x_for(size_t n_tiles, unsigned budget) {
   return n_tiles < budget ? static_cast<unsigned>(n_tiles) : budget;
 }
 
-// bit 0: non-temporal loads, bit 1: non-temporal stores.  Tuning flags with bit 4 set
-// carry an explicit policy in their low two bits; otherwise the per-kind default applies.
-int access_policy(Kind kind) {
-  const int flags = current_tuning().flags;
-  if (flags & 0x10) return flags & 3;
-  return kind == kKindReduce ? 1 : 3;
+// Calls f.template operator()<POL>(blocks) for the runtime policy.
+template <typename F>
+hipError_t with_policy(const LaunchCfg& cfg, F f) {
+  switch (cfg.pol) {
+    case 0: return f.template operator()<0>(cfg.blocks);
+    case 1: return f.template operator()<1>(cfg.blocks);
+    case 2: return f.template operator()<2>(cfg.blocks);
+    default: return f.template operator()<3>(cfg.blocks);
+  }
 }
 
 // Tuning flag bit 5 selects the wide tiles for the one-shot reduce (default: narrow).
 bool wide_tiles() { return (current_tuning().flags & 0x20) != 0; }
 
-// Calls f.template operator()<POL>() for the runtime policy.
-template <typename F>
-hipError_t with_policy(Kind kind, F f) {
-  switch (access_policy(kind)) {
-    case 0: return f.template operator()<0>();
-    case 1: return f.template operator()<1>();
-    case 2: return f.template operator()<2>();
-    default: return f.template operator()<3>();
-  }
-}
-
 template <typename T, int VEC>
 struct ReduceFixed {
   const PtrTable& live; int N; size_t count; T* out; float scale; hipStream_t stream;
-  template <int POL> hipError_t operator()() const {
+  template <int POL> hipError_t operator()(unsigned blocks) const {
     const bool wide = wide_tiles();
     const int U = wide ? unroll_wide(N) : unroll_narrow(N);
     const size_t tiles = count / VEC / (static_cast<size_t>(kThreads) * U);
-    const dim3 grid(grid_x_for(tiles, total_blocks(kKindReduce))), block(kThreads);
+    const dim3 grid(grid_x_for(tiles, blocks)), block(kThreads);
     switch (N) {
 #define FTAR_CASE(n)                                                                              \
   case n:                                                                                         \
@@ -531,9 +547,9 @@ struct ReduceFixed {
 template <typename T, int VEC>
 struct ReduceAny {
   const PtrTable& live; int N; size_t count; T* out; float scale; hipStream_t stream;
-  template <int POL> hipError_t operator()() const {
+  template <int POL> hipError_t operator()(unsigned blocks) const {
     const size_t tiles = (count / VEC + kThreads - 1) / kThreads;
-    const dim3 grid(grid_x_for(tiles, total_blocks(kKindReduce))), block(kThreads);
+    const dim3 grid(grid_x_for(tiles, blocks)), block(kThreads);
     k_reduce_masked_any<T, VEC, POL><<<grid, block, 0, stream>>>(live, N, out, scale, count);
     return hipGetLastError();
   }
@@ -543,23 +559,23 @@ template <typename T, int VECW>
 hipError_t reduce_masked_typed(const PtrTable& live, int N, size_t count, bool vec, void* out,
                                float scale, hipStream_t stream) {
   T* o = static_cast<T*>(out);
-  if (vec && N <= 16) return with_policy(kKindReduce, ReduceFixed<T, VECW>{live, N, count, o, scale, stream});
-  if (vec) return with_policy(kKindReduce, ReduceAny<T, VECW>{live, N, count, o, scale, stream});
-  return with_policy(kKindReduce, ReduceAny<T, 1>{live, N, count, o, scale, stream});
+  if (vec && N <= 16) return with_policy(reduce_cfg(N), ReduceFixed<T, VECW>{live, N, count, o, scale, stream});
+  if (vec) return with_policy(reduce_cfg(N), ReduceAny<T, VECW>{live, N, count, o, scale, stream});
+  return with_policy(reduce_cfg(N), ReduceAny<T, 1>{live, N, count, o, scale, stream});
 }
 
 template <typename T, int VEC>
 struct Bucketed {
   const PtrTable& all; int n_replicas; const BucketTable& masks; int n_buckets; size_t first_elem;
   size_t bucket_elems; size_t count; const ScaleTable& scales; T* out; hipStream_t stream;
-  template <int POL> hipError_t operator()() const {
+  template <int POL> hipError_t operator()(unsigned blocks) const {
     const size_t tile_elems = static_cast<size_t>(kThreads) * kBucketUnroll * VEC;
     const size_t tiles_per_bucket = (bucket_elems + tile_elems - 1) / tile_elems;
     const size_t last_begin = first_elem + static_cast<size_t>(n_buckets - 1) * bucket_elems;
     const size_t last_len = count - last_begin < bucket_elems ? count - last_begin : bucket_elems;
     const size_t tiles = static_cast<size_t>(n_buckets - 1) * tiles_per_bucket +
                          (last_len + tile_elems - 1) / tile_elems;
-    const dim3 grid(grid_x_for(tiles, total_blocks(kKindReduce))), block(kThreads);
+    const dim3 grid(grid_x_for(tiles, blocks)), block(kThreads);
     k_reduce_bucketed<T, VEC, POL><<<grid, block, 0, stream>>>(all, n_replicas, masks, scales,
                                                                first_elem, bucket_elems, last_len,
                                                                n_buckets, tiles_per_bucket, tiles, out);
@@ -573,9 +589,9 @@ hipError_t bucketed_typed(const PtrTable& all, int n_replicas, const BucketTable
                           const ScaleTable& scales, bool vec, void* out, hipStream_t stream) {
   T* o = static_cast<T*>(out);
   if (vec)
-    return with_policy(kKindReduce, Bucketed<T, VECW>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
+    return with_policy(reduce_cfg(n_replicas), Bucketed<T, VECW>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
                                          count, scales, o, stream});
-  return with_policy(kKindReduce, Bucketed<T, 1>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
+  return with_policy(reduce_cfg(n_replicas), Bucketed<T, 1>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
                                     count, scales, o, stream});
 }
 
@@ -600,23 +616,23 @@ template <typename T, int VEC>
 struct RingReduce {
   RingMode mode; const PtrTable& ring; int N; int step; const SegTable& seg; float* acc; float scale;
   hipStream_t stream;
-  template <int MODE, int U, int POL> void go() const {
+  template <int MODE, int U, int POL> void go(unsigned blocks) const {
     const SegTable tiles = ring_tiles(seg, N, VEC, U);
-    const dim3 grid(grid_x_for(tiles.begin[N], total_blocks(kKindRing))), block(kThreads);
+    const dim3 grid(grid_x_for(tiles.begin[N], blocks)), block(kThreads);
     k_ring_reduce<T, VEC, MODE, U, POL><<<grid, block, 0, stream>>>(ring, seg, tiles, N, step, acc, scale);
   }
-  template <int MODE, int POL> void pick_unroll() const {
+  template <int MODE, int POL> void pick_unroll(unsigned blocks) const {
     const int U = ring_unroll();
-    if (U == 2) go<MODE, 2, POL>();
-    else if (U == 8) go<MODE, 8, POL>();
-    else go<MODE, 4, POL>();
+    if (U == 2) go<MODE, 2, POL>(blocks);
+    else if (U == 8) go<MODE, 8, POL>(blocks);
+    else go<MODE, 4, POL>(blocks);
   }
-  template <int POL> hipError_t operator()() const {
+  template <int POL> hipError_t operator()(unsigned blocks) const {
     switch (mode) {
-      case kRsFirst: pick_unroll<kRsFirst, POL>(); break;
-      case kRsMid: pick_unroll<kRsMid, POL>(); break;
-      case kRsLast: pick_unroll<kRsLast, POL>(); break;
-      case kRsOnly: pick_unroll<kRsOnly, POL>(); break;
+      case kRsFirst: pick_unroll<kRsFirst, POL>(blocks); break;
+      case kRsMid: pick_unroll<kRsMid, POL>(blocks); break;
+      case kRsLast: pick_unroll<kRsLast, POL>(blocks); break;
+      case kRsOnly: pick_unroll<kRsOnly, POL>(blocks); break;
     }
     return hipGetLastError();
   }
@@ -625,16 +641,16 @@ struct RingReduce {
 template <typename T, int VEC>
 struct RingAllgather {
   const PtrTable& ring; int N; int step; const SegTable& seg; hipStream_t stream;
-  template <int U, int POL> void go() const {
+  template <int U, int POL> void go(unsigned blocks) const {
     const SegTable tiles = ring_tiles(seg, N, VEC, U);
-    const dim3 grid(grid_x_for(tiles.begin[N], total_blocks(kKindRing))), block(kThreads);
+    const dim3 grid(grid_x_for(tiles.begin[N], blocks)), block(kThreads);
     k_ring_allgather<T, VEC, U, POL><<<grid, block, 0, stream>>>(ring, seg, tiles, N, step);
   }
-  template <int POL> hipError_t operator()() const {
+  template <int POL> hipError_t operator()(unsigned blocks) const {
     const int U = ring_unroll();
-    if (U == 2) go<2, POL>();
-    else if (U == 8) go<8, POL>();
-    else go<4, POL>();
+    if (U == 2) go<2, POL>(blocks);
+    else if (U == 8) go<8, POL>(blocks);
+    else go<4, POL>(blocks);
     return hipGetLastError();
   }
 };
@@ -664,21 +680,21 @@ hipError_t launch_ring_reduce(RingMode mode, const PtrTable& ring, int n_live, i
                               const SegTable& seg, ftar_dtype_t dtype, bool vec, float* acc,
                               float scale, hipStream_t stream) {
   if (dtype == FTAR_F32) {
-    if (vec) return with_policy(kKindRing, RingReduce<float, 4>{mode, ring, n_live, step, seg, acc, scale, stream});
-    return with_policy(kKindRing, RingReduce<float, 1>{mode, ring, n_live, step, seg, acc, scale, stream});
+    if (vec) return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<float, 4>{mode, ring, n_live, step, seg, acc, scale, stream});
+    return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<float, 1>{mode, ring, n_live, step, seg, acc, scale, stream});
   }
-  if (vec) return with_policy(kKindRing, RingReduce<bf16, 4>{mode, ring, n_live, step, seg, acc, scale, stream});
-  return with_policy(kKindRing, RingReduce<bf16, 1>{mode, ring, n_live, step, seg, acc, scale, stream});
+  if (vec) return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<bf16, 4>{mode, ring, n_live, step, seg, acc, scale, stream});
+  return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<bf16, 1>{mode, ring, n_live, step, seg, acc, scale, stream});
 }
 
 hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, const SegTable& seg,
                                  ftar_dtype_t dtype, bool vec, hipStream_t stream) {
   if (dtype == FTAR_F32) {
-    if (vec) return with_policy(kKindRing, RingAllgather<float, 4>{ring, n_live, step, seg, stream});
-    return with_policy(kKindRing, RingAllgather<float, 1>{ring, n_live, step, seg, stream});
+    if (vec) return with_policy(ring_allgather_cfg(seg.begin[n_live], 4), RingAllgather<float, 4>{ring, n_live, step, seg, stream});
+    return with_policy(ring_allgather_cfg(seg.begin[n_live], 4), RingAllgather<float, 1>{ring, n_live, step, seg, stream});
   }
-  if (vec) return with_policy(kKindRing, RingAllgather<bf16, 8>{ring, n_live, step, seg, stream});
-  return with_policy(kKindRing, RingAllgather<bf16, 1>{ring, n_live, step, seg, stream});
+  if (vec) return with_policy(ring_allgather_cfg(seg.begin[n_live], 2), RingAllgather<bf16, 8>{ring, n_live, step, seg, stream});
+  return with_policy(ring_allgather_cfg(seg.begin[n_live], 2), RingAllgather<bf16, 1>{ring, n_live, step, seg, stream});
 }
 
 }  // namespace ftar
