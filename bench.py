@@ -11,9 +11,10 @@ shape of the second benchmark workload (8 replicas x 64 Mi bf16 elements, replic
                   live masks drawn inside the live set              (1 kernel)
 
 `value` is the algorithmic bytes (read + written) of all those kernels divided by the wall time
-of the step, inputs resident in HBM.  Every kernel launch is bracketed by HIP events recorded
-on the stream the kernels run on; `roofline` reports the kernel kind that takes the largest
-share of the step, `kernels` reports all kinds.  `cpu_baseline` times the CPU oracle (plain
+of the step, inputs resident in HBM.  Every kernel launch of the timed region carries a pair of
+HIP events that its own dispatch records on the stream it runs on (begin and end of the kernel);
+`roofline` reports the kernel kind that takes the largest share of the step, `kernels` reports
+all kinds.  `cpu_baseline` times the CPU oracle (plain
 single-threaded C++) on the same step on the host.
 
 The ring runs in place, so later steps reduce already reduced buffers; kernel time does not
@@ -43,6 +44,43 @@ def algorithmic_bytes(kind, n_live, elem_bytes, count):
         "allgather": E + E,
     }[kind]
     return per_elem * count
+
+
+class HipEvents:
+    """Raw hipEvent_t pairs from the HIP runtime already loaded in this process (plumbing only)."""
+
+    def __init__(self):
+        import ctypes
+        path = None
+        for line in open("/proc/self/maps"):
+            if "libamdhip64" in line:
+                path = line.split()[-1]
+                break
+        if path is None:
+            raise RuntimeError("HIP runtime not loaded")
+        self.ct = ctypes
+        self.hip = ctypes.CDLL(path)
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p,
+                                                 ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        ev = self.ct.c_void_p()
+        rc = self.hip.hipEventCreate(self.ct.byref(ev))
+        if rc != 0:
+            raise RuntimeError("hipEventCreate failed: %d" % rc)
+        return ev
+
+    def elapsed_s(self, a, b):
+        ms = self.ct.c_float()
+        rc = self.hip.hipEventElapsedTime(self.ct.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError("hipEventElapsedTime failed: %d" % rc)
+        return ms.value * 1e-3
+
+    def destroy(self, ev):
+        self.hip.hipEventDestroy(ev)
 
 
 def main():
@@ -105,25 +143,25 @@ def main():
     step_bytes = sum(bytes_of[k] for k in kinds)
 
     def step(events=None):
+        """events: one (start, stop) hipEvent_t pair per kernel of the step, or None."""
         plan = B.ftar_plan(n, mask, count, w.chunk_elems, w.dtype)
         i = 0
 
-        def mark():
+        def arm():
             nonlocal i
             if events is not None:
-                events[i].record(stream)
+                B.ftar_time_next_launch(events[i][0], events[i][1])
                 i += 1
-        mark()
+        arm()
         B.ftar_reduce_masked(bufs, mask, out, stream=stream)
-        mark()
         for s in range(plan.n_steps):
+            arm()
             B.ftar_reduce_step(plan, s, bufs, acc, stream=stream)
-            mark()
         for t in range(plan.n_steps):
+            arm()
             B.ftar_allgather_step(plan, t, bufs, stream=stream)
-            mark()
+        arm()
         B.ftar_reduce_masked_bucketed(bufs, bmasks, bucket_elems, out_b, stream=stream)
-        mark()
         B.ftar_plan_destroy(plan)
 
     parity = "skipped"
@@ -179,8 +217,8 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    n_marks = len(kinds) + 1
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(n_marks)] for _ in range(args.steps)]
+    hip_events = HipEvents()
+    events = [[(hip_events.create(), hip_events.create()) for _ in kinds] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
@@ -192,7 +230,7 @@ def main():
     dur = {}
     for ev in events:
         for i, kind in enumerate(kinds):
-            dur.setdefault(kind, []).append(ev[i].elapsed_time(ev[i + 1]) * 1e-3)  # seconds
+            dur.setdefault(kind, []).append(hip_events.elapsed_s(ev[i][0], ev[i][1]))
     kernels = []
     for kind in dict.fromkeys(kinds):
         d = dur[kind]

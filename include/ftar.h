@@ -173,6 +173,13 @@ const char* ftar_status_str(ftar_status_t s); /* static string */
  * asks for non-temporal loads and bit 1 for non-temporal stores. */
 void ftar_set_tuning(int blocks_per_cu, int flags);
 
+/* Measurement only: arms two hipEvent_t (passed as void*, either may be NULL) for the NEXT kernel
+ * this thread launches through the library.  That dispatch records them itself: `start` when the
+ * kernel begins on the GPU, `stop` when it ends, so hipEventElapsedTime(start, stop) is the
+ * kernel's own duration.  The pair is consumed by one launch (the first one, for a bucketed call
+ * that needs several) and cleared.  The caller owns the events. */
+void ftar_time_next_launch(void* start_event, void* stop_event);
+
 #ifdef __cplusplus
 }
 #endif

@@ -33,7 +33,7 @@ EXPORTS = [
     "ftar_plan_n_steps", "ftar_plan_acc_bytes", "ftar_plan_scale", "ftar_plan_segment",
     "ftar_reduce_step", "ftar_allgather_step", "ftar_reduce_masked",
     "ftar_reduce_masked_bucketed", "ftar_last_error", "ftar_status_is_retryable",
-    "ftar_status_str", "ftar_set_tuning",
+    "ftar_status_str", "ftar_set_tuning", "ftar_time_next_launch",
 ]
 
 _lib = None
@@ -89,6 +89,8 @@ def lib():
     L.ftar_status_str.argtypes = [ci]
     L.ftar_set_tuning.restype = None
     L.ftar_set_tuning.argtypes = [ci, ci]
+    L.ftar_time_next_launch.restype = None
+    L.ftar_time_next_launch.argtypes = [vp, vp]
     _lib = L
     return L
 
@@ -248,6 +250,11 @@ def ftar_reduce_masked_bucketed(bufs: Sequence[Optional[torch.Tensor]], masks: S
 
 def ftar_set_tuning(blocks_per_cu: int = 0, flags: int = 0) -> None:
     lib().ftar_set_tuning(blocks_per_cu, flags)
+
+
+def ftar_time_next_launch(start_event, stop_event) -> None:
+    """start_event / stop_event: raw hipEvent_t handles (ints or ctypes void pointers) or None."""
+    lib().ftar_time_next_launch(start_event, stop_event)
 
 
 def ftar_status_is_retryable(status: int) -> bool:

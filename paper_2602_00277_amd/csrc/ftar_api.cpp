@@ -24,6 +24,9 @@ ftar_status_t fail(ftar_status_t s) {
   return s;
 }
 
+thread_local hipEvent_t t_time_start = nullptr;
+thread_local hipEvent_t t_time_stop = nullptr;
+
 std::atomic<int> g_blocks_per_cu{0};
 std::atomic<int> g_flags{0};
 std::atomic<bool> g_env_read{false};
@@ -55,6 +58,13 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 Tuning current_tuning() {
   read_env_once();
   return Tuning{g_blocks_per_cu.load(), g_flags.load()};
+}
+
+void take_timing_events(hipEvent_t* start, hipEvent_t* stop) {
+  *start = t_time_start;
+  *stop = t_time_stop;
+  t_time_start = nullptr;
+  t_time_stop = nullptr;
 }
 
 int device_cu_count() {
@@ -292,6 +302,11 @@ const char* ftar_status_str(ftar_status_t s) {
     case FTAR_ERR_DEVICE: return "HIP runtime error";
   }
   return "unknown status";
+}
+
+void ftar_time_next_launch(void* start_event, void* stop_event) {
+  t_time_start = static_cast<hipEvent_t>(start_event);
+  t_time_stop = static_cast<hipEvent_t>(stop_event);
 }
 
 void ftar_set_tuning(int blocks_per_cu, int flags) {

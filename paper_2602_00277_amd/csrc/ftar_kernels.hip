@@ -18,6 +18,8 @@
 // multiplication by `scale`, one rounding (nearest-even) to the output type.
 // Compiled with -ffp-contract=off; fp32 denormals are not flushed.
 
+#include <hip/hip_ext.h>
+
 #include "ftar_internal.h"
 
 namespace ftar {
@@ -496,6 +498,19 @@ LaunchCfg ring_allgather_cfg(size_t count, size_t elem_bytes) {
   return launch_cfg(2, count * elem_bytes <= 192 * kMiB ? 1 : 3);
 }
 
+// Every kernel goes through here.  Normally a plain launch; when the caller armed a pair of
+// timing events for this thread's next launch, the dispatch itself records them (begin and end
+// of the kernel on the GPU, without the command processor's gap between two dispatches).
+template <typename... KArgs, typename... Args>
+void launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t stream, const Args&... args) {
+  hipEvent_t start = nullptr, stop = nullptr;
+  take_timing_events(&start, &stop);
+  if (start || stop)
+    hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, start, stop, 0, static_cast<KArgs>(args)...);
+  else
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, static_cast<KArgs>(args)...);
+}
+
 unsigned grid_x_for(size_t n_tiles, unsigned budget) {
   if (budget < 1) budget = 1;
   if (n_tiles < 1) return 1;
@@ -528,10 +543,10 @@ struct ReduceFixed {
 #define FTAR_CASE(n)                                                                              \
   case n:                                                                                         \
     if (wide)                                                                                     \
-      k_reduce_masked<T, VEC, n, unroll_wide(n), POL><<<grid, block, 0, stream>>>(live, out, scale, \
+      launch(k_reduce_masked<T, VEC, n, unroll_wide(n), POL>, grid, block, stream, live, out, scale, \
                                                                                   count);         \
     else                                                                                          \
-      k_reduce_masked<T, VEC, n, unroll_narrow(n), POL><<<grid, block, 0, stream>>>(live, out,    \
+      launch(k_reduce_masked<T, VEC, n, unroll_narrow(n), POL>, grid, block, stream, live, out,    \
                                                                                     scale, count); \
     break;
       FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
@@ -550,7 +565,7 @@ struct ReduceAny {
   template <int POL> hipError_t operator()(unsigned blocks) const {
     const size_t tiles = (count / VEC + kThreads - 1) / kThreads;
     const dim3 grid(grid_x_for(tiles, blocks)), block(kThreads);
-    k_reduce_masked_any<T, VEC, POL><<<grid, block, 0, stream>>>(live, N, out, scale, count);
+    launch(k_reduce_masked_any<T, VEC, POL>, grid, block, stream, live, N, out, scale, count);
     return hipGetLastError();
   }
 };
@@ -576,7 +591,7 @@ struct Bucketed {
     const size_t tiles = static_cast<size_t>(n_buckets - 1) * tiles_per_bucket +
                          (last_len + tile_elems - 1) / tile_elems;
     const dim3 grid(grid_x_for(tiles, blocks)), block(kThreads);
-    k_reduce_bucketed<T, VEC, POL><<<grid, block, 0, stream>>>(all, n_replicas, masks, scales,
+    launch(k_reduce_bucketed<T, VEC, POL>, grid, block, stream, all, n_replicas, masks, scales,
                                                                first_elem, bucket_elems, last_len,
                                                                n_buckets, tiles_per_bucket, tiles, out);
     return hipGetLastError();
@@ -619,7 +634,7 @@ struct RingReduce {
   template <int MODE, int U, int POL> void go(unsigned blocks) const {
     const SegTable tiles = ring_tiles(seg, N, VEC, U);
     const dim3 grid(grid_x_for(tiles.begin[N], blocks)), block(kThreads);
-    k_ring_reduce<T, VEC, MODE, U, POL><<<grid, block, 0, stream>>>(ring, seg, tiles, N, step, acc, scale);
+    launch(k_ring_reduce<T, VEC, MODE, U, POL>, grid, block, stream, ring, seg, tiles, N, step, acc, scale);
   }
   template <int MODE, int POL> void pick_unroll(unsigned blocks) const {
     const int U = ring_unroll();
@@ -644,7 +659,7 @@ struct RingAllgather {
   template <int U, int POL> void go(unsigned blocks) const {
     const SegTable tiles = ring_tiles(seg, N, VEC, U);
     const dim3 grid(grid_x_for(tiles.begin[N], blocks)), block(kThreads);
-    k_ring_allgather<T, VEC, U, POL><<<grid, block, 0, stream>>>(ring, seg, tiles, N, step);
+    launch(k_ring_allgather<T, VEC, U, POL>, grid, block, stream, ring, seg, tiles, N, step);
   }
   template <int POL> hipError_t operator()(unsigned blocks) const {
     const int U = ring_unroll();
