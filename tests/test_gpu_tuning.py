@@ -1,0 +1,88 @@
+"""GPU: results never depend on the launch shape or the cache policy, and the timing hook works."""
+import ctypes
+
+import pytest
+import torch
+
+from gpu_util import assert_same, code, host, rand_bufs, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2602_00277_amd import binding
+    binding.lib()
+    yield binding
+    binding.ftar_set_tuning(0, 0)
+
+
+TUNINGS = [(1, 0x10 | 0), (8, 0x10 | 1), (3, 0x10 | 2), (2, 0x10 | 3), (1, 0x20), (4, 0x10 | 3 | 0x20),
+           (1, 2 << 8), (2, 8 << 8), (16, (8 << 8) | 0x10), (0, 0)]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_every_tuning_gives_the_same_bits(B, oracle, dtype):
+    n, mask, chunk = 8, 0b11110111, 2048
+    count = 7 * chunk * 9 + 1234
+    bufs0 = rand_bufs(n, count, dtype, seed=3, dist="student_t3", mask=mask)
+    hb = [host(b) for b in bufs0]
+    d = code(dtype)
+    want_reduce = oracle.reduce_masked(hb, mask, d)
+    want_ring = oracle.ring_closed_form(hb, mask, count, chunk, d)
+    from paper_2602_00277_amd import workloads as W
+    bucket = 4096 * 5
+    masks = W.bucket_masks(n, (count + bucket - 1) // bucket, 0.8, seed=9)
+    for bpc, flags in TUNINGS:
+        say("tuning", dtype, bpc, hex(flags))
+        B.ftar_set_tuning(bpc, flags)
+        out = torch.empty(count, dtype=dtype, device="cuda")
+        B.ftar_reduce_masked(bufs0, mask, out)
+        outb = torch.empty(count, dtype=dtype, device="cuda")
+        B.ftar_reduce_masked_bucketed(bufs0, masks, bucket, outb)
+        bufs = [b.clone() for b in bufs0]
+        plan = B.ftar_plan(n, mask, count, chunk, dtype)
+        acc = torch.empty(count, dtype=torch.float32, device="cuda")
+        B.ring_allreduce(plan, bufs, acc)
+        torch.cuda.synchronize()
+        assert_same(host(out), want_reduce, "reduce bpc=%d flags=%#x" % (bpc, flags))
+        got_b = host(outb)
+        for b, m in enumerate(masks):
+            lo, hi = b * bucket, min(count, (b + 1) * bucket)
+            assert_same(got_b[lo:hi], oracle.reduce_masked([h[lo:hi].copy() for h in hb], m, d),
+                        "bucket %d bpc=%d flags=%#x" % (b, bpc, flags))
+        for r in range(n):
+            assert_same(host(bufs[r]), want_ring if (mask >> r) & 1 else hb[r],
+                        "ring buf %d bpc=%d flags=%#x" % (r, bpc, flags))
+    B.ftar_set_tuning(0, 0)
+
+
+def test_time_next_launch_records_the_kernel(B):
+    hip = None
+    for line in open("/proc/self/maps"):
+        if "libamdhip64" in line:
+            hip = ctypes.CDLL(line.split()[-1])
+            break
+    assert hip is not None
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+    hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+    a, b = ctypes.c_void_p(), ctypes.c_void_p()
+    assert hip.hipEventCreate(ctypes.byref(a)) == 0 and hip.hipEventCreate(ctypes.byref(b)) == 0
+    count = 1 << 24
+    bufs = rand_bufs(4, count, torch.float32, seed=1)
+    out = torch.empty(count, device="cuda")
+    say("time_next_launch")
+    B.ftar_reduce_masked(bufs, 0xF, out)          # warm
+    B.ftar_time_next_launch(a, b)
+    B.ftar_reduce_masked(bufs, 0xF, out)
+    B.ftar_reduce_masked(bufs, 0xF, out)          # not timed: the pair was consumed
+    assert hip.hipEventSynchronize(b) == 0
+    ms = ctypes.c_float()
+    assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+    # 320 MiB moved: between 20 us (16 TB/s, impossible) and 5 ms
+    assert 0.02 < ms.value < 5.0, ms.value
+    torch.cuda.synchronize()
+    hip.hipEventDestroy(a)
+    hip.hipEventDestroy(b)
