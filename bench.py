@@ -83,6 +83,168 @@ class HipEvents:
         self.hip.hipEventDestroy(ev)
 
 
+def all_configs_report(path, B, W, torch, np):
+    """The five workloads at full size: per workload the schedule's wall time (median of
+    repetitions, HIP events around the whole schedule), GB/s of algorithmic bytes, % of 8 TB/s,
+    parity on sampled slabs against the oracle, and the oracle's own speed on a sample."""
+    sys.path.insert(0, os.path.join(ROOT, "oracle"))
+    import ftar_oracle as oracle
+    dev = "cuda:0"
+    SLAB = 1 << 18
+    rows = []
+
+    def code(dt):
+        return oracle.BF16 if dt == torch.bfloat16 else oracle.F32
+
+    def same(got, want):
+        nan_g = (got & 0x7FFF) > 0x7F80 if got.dtype == np.uint16 else np.isnan(got)
+        nan_w = (want & 0x7FFF) > 0x7F80 if want.dtype == np.uint16 else np.isnan(want)
+        bits = np.uint16 if got.dtype == np.uint16 else np.uint32
+        return bool(np.array_equal(nan_g, nan_w) and
+                    np.array_equal(got.view(bits)[~nan_g], want.view(bits)[~nan_w]))
+
+    def starts_for(count, special, seed):
+        rng = np.random.default_rng(seed)
+        st = {0, max(0, count - SLAB)}
+        for x in special:
+            st.add(min(max(0, x - SLAB // 2), max(0, count - SLAB)))
+        for x in rng.integers(0, max(1, count - SLAB), 8):
+            st.add(int(x))
+        return sorted(st)
+
+    def time_schedule(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b) * 1e-3)
+        ts.sort()
+        return ts[len(ts) // 2], ts[0]
+
+    def add_row(name, what, gbytes, med, mn, ok, cpu_gbs, cpu_note):
+        rows.append("| %s | %s | %.3f | %.1f | %.0f | %.1f | %.0f | %s | %.2f (%s) |" % (
+            name, what, gbytes, med * 1e6, gbytes / med, 100 * gbytes / med / HBM_PEAK_GBS,
+            gbytes / mn, "bit-exact" if ok else "MISMATCH", cpu_gbs, cpu_note))
+        print(rows[-1], file=sys.stderr, flush=True)
+
+    cfgs = W.configs()
+    # ---- one-shot reduces: cfg 1, 2, 4 -------------------------------------------------
+    for idx in (0, 1, 3):
+        w = cfgs[idx]
+        bufs = W.draw_replicas(w, dev)
+        out = torch.empty(w.count, dtype=w.dtype, device=dev)
+        B.ftar_reduce_masked(bufs, w.live_mask, out)
+        torch.cuda.synchronize()
+        ok, cpu_s, cpu_elems = True, 0.0, 0
+        for st in starts_for(w.count, [1 << 30], w.seed):
+            hb = [None if not (w.live_mask >> r) & 1 else W.to_numpy_bits(b[st:st + SLAB])
+                  for r, b in enumerate(bufs)]
+            t0 = time.perf_counter()
+            want = oracle.reduce_masked(hb, w.live_mask, code(w.dtype))
+            cpu_s += time.perf_counter() - t0
+            cpu_elems += want.size
+            ok = ok and same(W.to_numpy_bits(out[st:st + SLAB]), want)
+        N = bin(w.live_mask).count("1")
+        gb = (N + 1) * w.elem_bytes * w.count / 1e9
+        med, mn = time_schedule(lambda: B.ftar_reduce_masked(bufs, w.live_mask, out), 20)
+        add_row(w.name, "ftar_reduce_masked, N=%d" % N, gb, med, mn, ok,
+                (N + 1) * w.elem_bytes * cpu_elems / cpu_s / 1e9, "%d elems" % cpu_elems)
+        del bufs, out
+        torch.cuda.empty_cache()
+    # ---- ring: cfg 3a (clean 16-ring) and 3b (5 steps, replica 9 leaves, re-plan) ------
+    w = cfgs[2]
+    E = w.elem_bytes
+    for label, schedule in (("3a clean 16-ring, 15 RS + 15 AG", [(0xFFFF, None)]),
+                            ("3b 5 RS steps, replica 9 leaves, 14 RS + 14 AG",
+                             [(0xFFFF, w.replan_before_step), (0xFFFF & ~(1 << w.replan_leaver), None)])):
+        bufs = W.draw_replicas(w, dev)
+        acc = torch.empty(w.count, dtype=torch.float32, device=dev)
+        final_mask = schedule[-1][0]
+        special = oracle.geometry(w.n_replicas, final_mask, w.count, w.chunk_elems)[1:-1]
+        starts = starts_for(w.count, special[:3] + special[-2:], w.seed)
+        orig = {st: [W.to_numpy_bits(b[st:st + SLAB]) for b in bufs] for st in starts}
+        plans = [(B.ftar_plan(w.n_replicas, m, w.count, w.chunk_elems, w.dtype), steps) for m, steps in schedule]
+
+        def run():
+            for plan, steps in plans:
+                if steps is None:
+                    B.ring_allreduce(plan, bufs, acc)
+                else:
+                    for s in range(steps):
+                        B.ftar_reduce_step(plan, s, bufs, acc)
+        run()
+        torch.cuda.synchronize()
+        ok, cpu_s, cpu_elems = True, 0.0, 0
+        for st in starts:
+            t0 = time.perf_counter()
+            want = oracle.ring_closed_form(orig[st], final_mask, w.count, w.chunk_elems, code(w.dtype),
+                                           begin=st, length=SLAB)
+            cpu_s += time.perf_counter() - t0
+            cpu_elems += SLAB
+            for r in range(w.n_replicas):
+                got = W.to_numpy_bits(bufs[r][st:st + SLAB])
+                ok = ok and same(got, want if (final_mask >> r) & 1 else orig[st][r])
+        per_elem = 0
+        for m, steps in schedule:
+            N = bin(m).count("1")
+            full = (2 * E + 4) + (N - 3) * (8 + E) + (4 + 2 * E) + (N - 1) * 2 * E
+            if steps is None:
+                per_elem += full
+            else:
+                per_elem += (2 * E + 4) + (steps - 1) * (8 + E)
+        gb = per_elem * w.count / 1e9
+        med, mn = time_schedule(run, 5)
+        Nf = bin(final_mask).count("1")
+        add_row(w.name, label, gb, med, mn, ok, (Nf + 1) * E * cpu_elems / cpu_s / 1e9,
+                "closed form, %d elems, (N+1)E bytes/elem" % cpu_elems)
+        for plan, _ in plans:
+            B.ftar_plan_destroy(plan)
+        del bufs, acc, orig
+        torch.cuda.empty_cache()
+    # ---- cfg 5: per-bucket live masks ---------------------------------------------------
+    w = cfgs[4]
+    edges = W.bucket_bounds(w.count, w.bucket_elems)
+    masks = W.bucket_masks(w.n_replicas, len(edges) - 1, w.bucket_p_live, w.seed)
+    bufs = W.draw_replicas(w, dev)
+    out = torch.empty(w.count, dtype=w.dtype, device=dev)
+    B.ftar_reduce_masked_bucketed(bufs, masks, w.bucket_elems, out)
+    torch.cuda.synchronize()
+    ok, cpu_s, cpu_bytes = True, 0.0, 0
+    for b in range(len(masks)):
+        for st in (edges[b], edges[b + 1] - SLAB):
+            hb = [W.to_numpy_bits(x[st:st + SLAB]) if (masks[b] >> r) & 1 else None for r, x in enumerate(bufs)]
+            t0 = time.perf_counter()
+            want = oracle.reduce_masked(hb, masks[b], code(w.dtype))
+            cpu_s += time.perf_counter() - t0
+            cpu_bytes += (bin(masks[b]).count("1") + 1) * w.elem_bytes * SLAB
+            ok = ok and same(W.to_numpy_bits(out[st:st + SLAB]), want)
+    gb = sum((edges[b + 1] - edges[b]) * w.elem_bytes * (bin(m).count("1") + 1)
+             for b, m in enumerate(masks)) / 1e9
+    med, mn = time_schedule(lambda: B.ftar_reduce_masked_bucketed(bufs, masks, w.bucket_elems, out), 20)
+    add_row(w.name, "ftar_reduce_masked_bucketed, %d buckets, masks %s.." % (len(masks), hex(masks[0])),
+            gb, med, mn, ok, cpu_bytes / cpu_s / 1e9, "%d slabs" % (2 * len(masks)))
+
+    head = ["# The five benchmark workloads at full size on one MI355X", "",
+            "Command: `python3 bench.py --all-configs %s`. Wall time of the whole call or schedule from "
+            "HIP events on the launch stream (median of repetitions; min in its own column), GB/s of "
+            "algorithmic bytes (read + written), parity against the CPU oracle on sampled slabs of "
+            "%d elements (first, last, portion/bucket boundaries, random), and the oracle's own "
+            "throughput on those slabs on one host core (%d CPUs visible)." % (path, SLAB, os.cpu_count()),
+            "", "cfg 1 is 20 MiB in total: cache-resident and launch-bound, a parity case, not an HBM "
+            "measurement.", "",
+            "| workload | what ran | algorithmic GB | median us | GB/s | % of 8 TB/s | GB/s (best rep) | parity | oracle GB/s, 1 core (sample) |",
+            "|---|---|---|---|---|---|---|---|---|"]
+    with open(path, "w") as f:
+        f.write("\n".join(head + rows) + "\n")
+    if any("MISMATCH" in r for r in rows):
+        sys.exit(1)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -90,6 +252,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
+    ap.add_argument("--all-configs", metavar="PATH", default=None,
+                    help="instead of the step benchmark, run the five benchmark workloads at full "
+                         "size (parity on sampled slabs, timing, oracle timing on a sample) and "
+                         "write a markdown report to PATH")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (simulated replicas are separate buffers on "
@@ -107,6 +273,9 @@ def main():
     B.lib()  # raises if libftar.so is not built: there is no fallback path
     torch.cuda.set_device(0)
     dev = "cuda:0"
+    if args.all_configs:
+        all_configs_report(args.all_configs, B, W, torch, np)
+        return
 
     w = W.configs()[1]
     E = w.elem_bytes

@@ -486,8 +486,13 @@ LaunchCfg launch_cfg(int default_blocks_per_cu, int default_pol) {
   return c;
 }
 
-// N-reads-one-write reduction: ordinary stores; fewer workgroups the more streams there are.
-LaunchCfg reduce_cfg(int n_live) { return launch_cfg(n_live <= 2 ? 4 : n_live <= 4 ? 2 : 1, 1); }
+// N-reads-one-write reduction: fewer workgroups the more streams there are; ordinary stores
+// while the output fits the Infinity Cache, non-temporal ones beyond (matters for N <= 4).
+LaunchCfg reduce_cfg(int n_live, size_t out_bytes) {
+  const bool big = out_bytes > 256 * kMiB;
+  const int per_cu = n_live <= 2 ? 4 : (n_live <= 4 && !big) ? 2 : 1;
+  return launch_cfg(per_cu, big ? 3 : 1);
+}
 
 LaunchCfg ring_reduce_cfg(RingMode mode, size_t count) {
   if (mode == kRsMid) return launch_cfg(1, count * 4 <= 256 * kMiB ? 1 : 3);
@@ -574,9 +579,9 @@ template <typename T, int VECW>
 hipError_t reduce_masked_typed(const PtrTable& live, int N, size_t count, bool vec, void* out,
                                float scale, hipStream_t stream) {
   T* o = static_cast<T*>(out);
-  if (vec && N <= 16) return with_policy(reduce_cfg(N), ReduceFixed<T, VECW>{live, N, count, o, scale, stream});
-  if (vec) return with_policy(reduce_cfg(N), ReduceAny<T, VECW>{live, N, count, o, scale, stream});
-  return with_policy(reduce_cfg(N), ReduceAny<T, 1>{live, N, count, o, scale, stream});
+  if (vec && N <= 16) return with_policy(reduce_cfg(N, count * sizeof(T)), ReduceFixed<T, VECW>{live, N, count, o, scale, stream});
+  if (vec) return with_policy(reduce_cfg(N, count * sizeof(T)), ReduceAny<T, VECW>{live, N, count, o, scale, stream});
+  return with_policy(reduce_cfg(N, count * sizeof(T)), ReduceAny<T, 1>{live, N, count, o, scale, stream});
 }
 
 template <typename T, int VEC>
@@ -604,9 +609,9 @@ hipError_t bucketed_typed(const PtrTable& all, int n_replicas, const BucketTable
                           const ScaleTable& scales, bool vec, void* out, hipStream_t stream) {
   T* o = static_cast<T*>(out);
   if (vec)
-    return with_policy(reduce_cfg(n_replicas), Bucketed<T, VECW>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
+    return with_policy(reduce_cfg(n_replicas, (count - first_elem) * sizeof(T)), Bucketed<T, VECW>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
                                          count, scales, o, stream});
-  return with_policy(reduce_cfg(n_replicas), Bucketed<T, 1>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
+  return with_policy(reduce_cfg(n_replicas, (count - first_elem) * sizeof(T)), Bucketed<T, 1>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
                                     count, scales, o, stream});
 }
 
