@@ -63,7 +63,7 @@ typedef enum {
   FTAR_ERR_BAD_MASK = 3,    /* live_mask has a bit set at or above n_replicas */
   FTAR_ERR_BAD_STEP = 4,    /* step outside [0, n_live-2] */
   /* retryable: re-plan over the new group and restart the schedule */
-  FTAR_ERR_STALE_PLAN = 16, /* reserved */
+  FTAR_ERR_STALE_PLAN = 16, /* the persistent ring was cancelled or timed out before finishing */
   /* fatal: the HIP runtime reported a failure */
   FTAR_ERR_DEVICE = 32
 } ftar_status_t;
@@ -161,6 +161,44 @@ ftar_status_t ftar_reduce_masked_bucketed(const void* const* bufs, int n_replica
                                           const uint64_t* masks, size_t n_buckets,
                                           size_t bucket_elems, size_t count, ftar_dtype_t dtype,
                                           void* out, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * CPU-driven persistent ring: the whole ring all-reduce as ONE kernel whose progress the CPU
+ * gates through flags in host-pinned memory.
+ * Paper: section 4.2, "Optimizations" (one kernel per AllReduce that busy-polls a flag in
+ * host-pinned memory set by a CPU thread; run on few compute units with many loads in flight
+ * per thread) and "Timeout and error handling" (the GPU-side wait is a loop with a timeout so
+ * the GPU never hangs; a recoverable error returns a retryable work and queued operations are
+ * cancelled and marked skipped).
+ *
+ * The kernel runs the 2N-2 steps of the plan in order (ReduceScatter 0..N-2, then AllGather
+ * N-1..2N-3), with the arithmetic of ftar_reduce_step / ftar_allgather_step.  Before step s
+ * every workgroup waits until the CPU has released it (ftar_ctrl_release(ctrl, r) with r > s);
+ * after step s it publishes its progress.  A wait ends without the release when the CPU
+ * cancels (ftar_ctrl_cancel) or when timeout_us microseconds have passed: the workgroup then
+ * records why and exits, so the kernel always terminates.  No user buffer is written before
+ * the last ReduceScatter step (s = N-2) is released: a cancel or timeout before that leaves every
+ * bufs[r] untouched and the caller re-plans and restarts.
+ *
+ * ctrl is a control block in coherent host-pinned memory made by ftar_ctrl_create() (a host
+ * allocation at set-up, not on the hot path).  One control block serves one call at a time;
+ * ftar_ring_persistent re-arms it (released = 0, no cancel) before launching.
+ *   n_blocks    workgroups (= compute units used), 1..1024; 0 = one per compute unit
+ *   timeout_us  per-wait limit in microseconds (> 0)
+ * Returns at once like every other compute call.  After the stream has been synchronised,
+ * ftar_ctrl_result tells how it ended: FTAR_OK (all steps done), or FTAR_ERR_STALE_PLAN
+ * (retryable: cancelled or timed out); *steps_done = steps completed by every workgroup.
+ */
+void* ftar_ctrl_create(void);   /* NULL on failure */
+void ftar_ctrl_destroy(void* ctrl);
+ftar_status_t ftar_ring_persistent(const ftar_plan_t* plan, void* const* bufs, float* acc, void* ctrl,
+                                   int n_blocks, unsigned timeout_us, void* stream);
+/* CPU side of the handshake (plain host stores/loads on the control block; callable from any
+ * thread while the kernel runs). */
+void ftar_ctrl_release(void* ctrl, int n_steps); /* steps [0, n_steps) may run */
+void ftar_ctrl_cancel(void* ctrl);               /* stop at the next wait */
+int ftar_ctrl_progress(const void* ctrl);        /* steps completed by EVERY workgroup so far */
+ftar_status_t ftar_ctrl_result(const void* ctrl, int* steps_done);
 
 /* --------------------------------------------------------------------------- */
 ftar_status_t ftar_last_error(void);          /* status of this thread's last failing call */

@@ -34,6 +34,8 @@ EXPORTS = [
     "ftar_reduce_step", "ftar_allgather_step", "ftar_reduce_masked",
     "ftar_reduce_masked_bucketed", "ftar_last_error", "ftar_status_is_retryable",
     "ftar_status_str", "ftar_set_tuning", "ftar_time_next_launch",
+    "ftar_ctrl_create", "ftar_ctrl_destroy", "ftar_ring_persistent", "ftar_ctrl_release",
+    "ftar_ctrl_cancel", "ftar_ctrl_progress", "ftar_ctrl_result",
 ]
 
 _lib = None
@@ -91,6 +93,20 @@ def lib():
     L.ftar_set_tuning.argtypes = [ci, ci]
     L.ftar_time_next_launch.restype = None
     L.ftar_time_next_launch.argtypes = [vp, vp]
+    L.ftar_ctrl_create.restype = vp
+    L.ftar_ctrl_create.argtypes = []
+    L.ftar_ctrl_destroy.restype = None
+    L.ftar_ctrl_destroy.argtypes = [vp]
+    L.ftar_ring_persistent.restype = ci
+    L.ftar_ring_persistent.argtypes = [vp, vp, vp, vp, ci, ctypes.c_uint, vp]
+    L.ftar_ctrl_release.restype = None
+    L.ftar_ctrl_release.argtypes = [vp, ci]
+    L.ftar_ctrl_cancel.restype = None
+    L.ftar_ctrl_cancel.argtypes = [vp]
+    L.ftar_ctrl_progress.restype = ci
+    L.ftar_ctrl_progress.argtypes = [vp]
+    L.ftar_ctrl_result.restype = ci
+    L.ftar_ctrl_result.argtypes = [vp, ctypes.POINTER(ci)]
     _lib = L
     return L
 
@@ -267,6 +283,80 @@ def ftar_status_str(status: int) -> str:
 
 def ftar_last_error() -> int:
     return lib().ftar_last_error()
+
+
+class Ctrl:
+    """Owner of a control block for ftar_ring_persistent (coherent host-pinned memory)."""
+
+    def __init__(self):
+        self.handle = lib().ftar_ctrl_create()
+        if not self.handle:
+            raise FtarError(lib().ftar_last_error(), "ftar_ctrl_create")
+
+    def release(self, n_steps: int) -> None:
+        lib().ftar_ctrl_release(self.handle, n_steps)
+
+    def cancel(self) -> None:
+        lib().ftar_ctrl_cancel(self.handle)
+
+    def progress(self) -> int:
+        return lib().ftar_ctrl_progress(self.handle)
+
+    def result(self):
+        """(status, steps_done); call after the stream has been synchronised."""
+        done = ctypes.c_int()
+        st = lib().ftar_ctrl_result(self.handle, ctypes.byref(done))
+        return st, done.value
+
+    def destroy(self) -> None:
+        if self.handle:
+            lib().ftar_ctrl_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def ftar_ctrl_create() -> Ctrl:
+    return Ctrl()
+
+
+def ftar_ctrl_destroy(ctrl: Ctrl) -> None:
+    ctrl.destroy()
+
+
+def ftar_ctrl_release(ctrl: Ctrl, n_steps: int) -> None:
+    ctrl.release(n_steps)
+
+
+def ftar_ctrl_cancel(ctrl: Ctrl) -> None:
+    ctrl.cancel()
+
+
+def ftar_ctrl_progress(ctrl: Ctrl) -> int:
+    return ctrl.progress()
+
+
+def ftar_ctrl_result(ctrl: Ctrl):
+    return ctrl.result()
+
+
+def ftar_ring_persistent(plan: Plan, bufs: Sequence[Optional[torch.Tensor]],
+                         acc: Optional[torch.Tensor], ctrl: Ctrl, n_blocks: int = 0,
+                         timeout_us: int = 2_000_000, stream=None) -> None:
+    _check_bufs(bufs, plan.live_mask, plan.count, plan.dtype)
+    if len(bufs) != plan.n_replicas:
+        raise ValueError("bufs must have one entry per replica slot")
+    if acc is not None and (acc.dtype != torch.float32 or acc.numel() < plan.count or not acc.is_cuda):
+        raise ValueError("acc must be a GPU float32 tensor of at least count elements")
+    st = lib().ftar_ring_persistent(plan.handle, _ptr_array(bufs),
+                                    None if acc is None else acc.data_ptr(), ctrl.handle, n_blocks,
+                                    timeout_us, _stream_handle(stream))
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_ring_persistent")
 
 
 def ring_allreduce(plan: Plan, bufs: Sequence[Optional[torch.Tensor]], acc: Optional[torch.Tensor],

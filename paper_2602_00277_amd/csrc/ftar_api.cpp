@@ -287,6 +287,92 @@ ftar_status_t ftar_reduce_masked_bucketed(const void* const* bufs, int n_replica
   return FTAR_OK;
 }
 
+void* ftar_ctrl_create(void) {
+  void* p = nullptr;
+  if (hipHostMalloc(&p, sizeof(Ctrl), hipHostMallocCoherent | hipHostMallocMapped) != hipSuccess || !p) {
+    fail(FTAR_ERR_DEVICE);
+    return nullptr;
+  }
+  std::memset(p, 0, sizeof(Ctrl));
+  return p;
+}
+
+void ftar_ctrl_destroy(void* ctrl) {
+  if (ctrl) (void)hipHostFree(ctrl);
+}
+
+ftar_status_t ftar_ring_persistent(const ftar_plan_t* plan, void* const* bufs, float* acc, void* ctrl,
+                                   int n_blocks, unsigned timeout_us, void* stream) {
+  if (!plan_ok(plan) || !bufs || !ctrl || timeout_us == 0 || n_blocks < 0 ||
+      n_blocks > kMaxPersistentBlocks)
+    return fail(FTAR_ERR_INVALID_ARG);
+  const int N = plan->n_live;
+  Ctrl* c = static_cast<Ctrl*>(ctrl);
+  PtrTable tab;
+  std::memset(&tab, 0, sizeof(tab));
+  bool vec = true;
+  ftar_status_t s = ring_table(plan, bufs, &tab, &vec);
+  if (s != FTAR_OK) return fail(s);
+  if (N >= 3) {
+    if (!acc || !aligned(acc, 4)) return fail(FTAR_ERR_INVALID_ARG);
+    if (!aligned(acc, 16)) vec = false;
+  }
+  unsigned blocks = n_blocks > 0 ? static_cast<unsigned>(n_blocks) : static_cast<unsigned>(device_cu_count());
+  if (blocks > static_cast<unsigned>(kMaxPersistentBlocks)) blocks = kMaxPersistentBlocks;
+  // re-arm the control block; the launch below orders these stores before the kernel's loads
+  c->released = 0;
+  c->cancel = 0;
+  c->status = 0;
+  c->blocked_step = 0;
+  c->n_blocks = N >= 2 ? blocks : 0;
+  c->n_steps = static_cast<unsigned>(2 * N - 2);
+  for (unsigned b = 0; b < blocks; ++b) c->block_step[b] = 0;
+  std::atomic_thread_fence(std::memory_order_seq_cst);
+  if (N < 2) return FTAR_OK;  // a ring of one has no steps: nothing to launch
+  void* dev = nullptr;
+  if (hipHostGetDevicePointer(&dev, ctrl, 0) != hipSuccess || !dev) return fail(FTAR_ERR_INVALID_ARG);
+  hipError_t e = launch_ring_persistent(tab, N, plan->seg, plan->dtype, vec, acc, plan->scale,
+                                        static_cast<Ctrl*>(dev), blocks,
+                                        static_cast<unsigned long long>(timeout_us) * 100ull,
+                                        static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
+}
+
+void ftar_ctrl_release(void* ctrl, int n_steps) {
+  if (!ctrl || n_steps < 0) return;
+  __atomic_store_n(&static_cast<Ctrl*>(ctrl)->released, static_cast<unsigned long long>(n_steps),
+                   __ATOMIC_RELEASE);
+}
+
+void ftar_ctrl_cancel(void* ctrl) {
+  if (!ctrl) return;
+  __atomic_store_n(&static_cast<Ctrl*>(ctrl)->cancel, 1ull, __ATOMIC_RELEASE);
+}
+
+int ftar_ctrl_progress(const void* ctrl) {
+  if (!ctrl) return 0;
+  const Ctrl* c = static_cast<const Ctrl*>(ctrl);
+  const unsigned nb = c->n_blocks;
+  if (nb == 0) return static_cast<int>(c->n_steps);
+  unsigned lo = ~0u;
+  for (unsigned b = 0; b < nb; ++b) {
+    const unsigned v = __atomic_load_n(&c->block_step[b], __ATOMIC_ACQUIRE);
+    if (v < lo) lo = v;
+  }
+  return static_cast<int>(lo);
+}
+
+ftar_status_t ftar_ctrl_result(const void* ctrl, int* steps_done) {
+  if (!ctrl) return fail(FTAR_ERR_INVALID_ARG);
+  const Ctrl* c = static_cast<const Ctrl*>(ctrl);
+  const int done = ftar_ctrl_progress(ctrl);
+  if (steps_done) *steps_done = done;
+  const unsigned long long status = __atomic_load_n(&c->status, __ATOMIC_ACQUIRE);
+  if (status != 0) return fail(FTAR_ERR_STALE_PLAN);  // timed out or cancelled: re-plan and restart
+  if (done != static_cast<int>(c->n_steps)) return fail(FTAR_ERR_INVALID_ARG);  // still running
+  return FTAR_OK;
+}
+
 ftar_status_t ftar_last_error(void) { return t_last_error; }
 
 int ftar_status_is_retryable(ftar_status_t s) { return s == FTAR_ERR_STALE_PLAN ? 1 : 0; }

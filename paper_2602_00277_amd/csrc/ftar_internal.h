@@ -35,6 +35,19 @@ struct ScaleTable {
   float s[kMaxReplicas + 1];
 };
 
+// Control block of the persistent ring, in coherent host-pinned memory.  Each word the two sides
+// exchange sits on its own 64-byte line.
+constexpr int kMaxPersistentBlocks = 1024;
+struct alignas(64) Ctrl {
+  alignas(64) unsigned long long released;  // CPU -> GPU: steps [0, released) may run
+  alignas(64) unsigned long long cancel;    // CPU -> GPU: non-zero = stop at the next wait
+  alignas(64) unsigned long long status;    // GPU -> CPU: 0 ok, 1 a wait timed out, 2 cancelled
+  alignas(64) unsigned long long blocked_step;  // GPU -> CPU: step a workgroup gave up at
+  alignas(64) unsigned int n_blocks;        // set by the launcher
+  unsigned int n_steps;                     // 2N-2, set by the launcher
+  alignas(64) unsigned int block_step[kMaxPersistentBlocks];  // GPU -> CPU: steps done by block b
+};
+
 enum RingMode {
   kRsFirst = 0,  // acc = x_k + x_{k+1}
   kRsMid = 1,    // acc = acc + x_{k+s+1}
@@ -70,6 +83,12 @@ hipError_t launch_ring_reduce(RingMode mode, const PtrTable& ring, int n_live, i
 
 hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, const SegTable& seg,
                                  ftar_dtype_t dtype, bool vec, hipStream_t stream);
+
+// The whole ring in one kernel, gated by the control block (ctrl_dev = device view of it).
+hipError_t launch_ring_persistent(const PtrTable& ring, int n_live, const SegTable& seg,
+                                  ftar_dtype_t dtype, bool vec, float* acc, float scale, Ctrl* ctrl_dev,
+                                  unsigned n_blocks, unsigned long long timeout_ticks,
+                                  hipStream_t stream);
 
 }  // namespace ftar
 

@@ -380,12 +380,12 @@ __device__ __forceinline__ RingTile ring_tile_of(size_t g, int& k, size_t& next,
   return RingTile{k, begin, uniform_u64(s_seg[k + 1]) - begin};
 }
 
-// One ReduceScatter step over all N portions.
-template <typename T, int VEC, int MODE, int U, int POL>
-__global__ void __launch_bounds__(kThreads)
-k_ring_reduce(PtrTable ring, SegTable seg, SegTable tile0, int N, int step, float* acc, float scale) {
-  __shared__ T* s_tab[kMaxReplicas];
-  __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
+// Stages the ring's pointer table, portion boundaries and tile prefix in LDS (block-wide).
+template <typename T>
+__device__ __forceinline__ void stage_ring_tables(const PtrTable& ring, const SegTable& seg,
+                                                  const SegTable& tile0, int N, T** s_tab,
+                                                  unsigned long long* s_seg,
+                                                  unsigned long long* s_tile) {
   const unsigned tid = threadIdx.x;
   if (tid < static_cast<unsigned>(N)) s_tab[tid] = static_cast<T*>(ring.p[tid]);
   if (tid <= static_cast<unsigned>(N)) {
@@ -393,6 +393,13 @@ k_ring_reduce(PtrTable ring, SegTable seg, SegTable tile0, int N, int step, floa
     s_tile[tid] = tile0.begin[tid];
   }
   __syncthreads();
+}
+
+// This block's share of one ReduceScatter step: tiles blockIdx.x, blockIdx.x + gridDim.x, ...
+template <typename T, int VEC, int MODE, int U, int POL>
+__device__ __forceinline__ void ring_reduce_pass(T* const* s_tab, const unsigned long long* s_seg,
+                                                 const unsigned long long* s_tile, int N, int step,
+                                                 float* acc, float scale) {
   constexpr size_t kTileElems = static_cast<size_t>(kThreads) * U * VEC;
   const size_t total = uniform_u64(s_tile[N]);
   int k = 0;
@@ -416,22 +423,14 @@ k_ring_reduce(PtrTable ring, SegTable seg, SegTable tile0, int N, int step, floa
   }
 }
 
-// One AllGather step over all N portions: bit copy from ring position k+t-1 to k+t.
+// This block's share of one AllGather step: bit copy from ring position k+t-1 to k+t.
 template <typename T, int VEC, int U, int POL>
-__global__ void __launch_bounds__(kThreads)
-k_ring_allgather(PtrTable ring, SegTable seg, SegTable tile0, int N, int step) {
-  __shared__ T* s_tab[kMaxReplicas];
-  __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
+__device__ __forceinline__ void ring_allgather_pass(T* const* s_tab, const unsigned long long* s_seg,
+                                                    const unsigned long long* s_tile, int N, int step) {
   typedef typename Raw<T, VEC>::type R;
   typedef typename Raw<T, 1>::type R1;
-  const unsigned tid = threadIdx.x;
-  if (tid < static_cast<unsigned>(N)) s_tab[tid] = static_cast<T*>(ring.p[tid]);
-  if (tid <= static_cast<unsigned>(N)) {
-    s_seg[tid] = seg.begin[tid];
-    s_tile[tid] = tile0.begin[tid];
-  }
-  __syncthreads();
   constexpr size_t kTileElems = static_cast<size_t>(kThreads) * U * VEC;
+  const unsigned tid = threadIdx.x;
   const size_t total = uniform_u64(s_tile[N]);
   int k = 0;
   size_t next = uniform_u64(s_tile[1]);
@@ -453,6 +452,97 @@ k_ring_allgather(PtrTable ring, SegTable seg, SegTable tile0, int N, int step) {
         const size_t e = n_vec * VEC + tid;
         if (e < t.rem) reinterpret_cast<R1*>(to)[e] = reinterpret_cast<const R1*>(from)[e];
       }
+    }
+  }
+}
+
+// One ReduceScatter step over all N portions.
+template <typename T, int VEC, int MODE, int U, int POL>
+__global__ void __launch_bounds__(kThreads)
+k_ring_reduce(PtrTable ring, SegTable seg, SegTable tile0, int N, int step, float* acc, float scale) {
+  __shared__ T* s_tab[kMaxReplicas];
+  __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
+  stage_ring_tables<T>(ring, seg, tile0, N, s_tab, s_seg, s_tile);
+  ring_reduce_pass<T, VEC, MODE, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale);
+}
+
+// One AllGather step over all N portions.
+template <typename T, int VEC, int U, int POL>
+__global__ void __launch_bounds__(kThreads)
+k_ring_allgather(PtrTable ring, SegTable seg, SegTable tile0, int N, int step) {
+  __shared__ T* s_tab[kMaxReplicas];
+  __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
+  stage_ring_tables<T>(ring, seg, tile0, N, s_tab, s_seg, s_tile);
+  ring_allgather_pass<T, VEC, U, POL>(s_tab, s_seg, s_tile, N, step);
+}
+
+// ---- the whole ring as one CPU-gated persistent kernel ----------------------------
+// Element i of acc (and of every replica buffer) is only ever touched by the lane that owns
+// tile position i, and the tile -> block assignment is the same in every step, so consecutive
+// steps need no synchronisation between blocks: program order within a lane is enough.  What
+// the blocks do wait for is the CPU: before step s, lane 0 polls the control block in
+// host-pinned memory until the step is released, the call is cancelled, or the wait has lasted
+// longer than the timeout (wall clock, 100 MHz); in the last two cases the whole block records
+// why and leaves, so the kernel ends no matter what the CPU does.
+__device__ __forceinline__ unsigned long long sys_load(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+template <typename V>
+__device__ __forceinline__ void sys_store(V* p, V v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+constexpr int kPersistentUnroll = 4;
+
+template <typename T, int VEC, int POL>
+__global__ void __launch_bounds__(kThreads)
+k_ring_persistent(PtrTable ring, SegTable seg, SegTable tile0, int N, float* acc, float scale,
+                  Ctrl* ctrl, unsigned long long timeout_ticks, unsigned long long max_spins) {
+  __shared__ T* s_tab[kMaxReplicas];
+  __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
+  __shared__ int s_verdict;  // 0 = run the step, 1 = timed out, 2 = cancelled
+  stage_ring_tables<T>(ring, seg, tile0, N, s_tab, s_seg, s_tile);
+  constexpr int U = kPersistentUnroll;
+  const int n_steps = 2 * N - 2;
+  for (int step = 0; step < n_steps; ++step) {
+    if (threadIdx.x == 0) {
+      // Bounded twice over: by the wall clock and, should the clock ever stand still, by a
+      // spin count (one spin costs two reads of host memory, about a microsecond or more).
+      int verdict = 1;
+      const long long t0 = wall_clock64();
+      for (unsigned long long spin = 0; spin < max_spins; ++spin) {
+        if (sys_load(&ctrl->released) > static_cast<unsigned long long>(step)) { verdict = 0; break; }
+        if (sys_load(&ctrl->cancel) != 0) { verdict = 2; break; }
+        if (static_cast<unsigned long long>(wall_clock64() - t0) > timeout_ticks) break;
+        __builtin_amdgcn_s_sleep(8);
+      }
+      s_verdict = verdict;
+    }
+    __syncthreads();
+    const int verdict = s_verdict;
+    if (verdict != 0) {  // the same for every lane of the block: all leave together
+      if (threadIdx.x == 0) {
+        sys_store(&ctrl->blocked_step, static_cast<unsigned long long>(step));
+        sys_store(&ctrl->status, static_cast<unsigned long long>(verdict));
+      }
+      return;
+    }
+    if (step < N - 1) {
+      if (N == 2) ring_reduce_pass<T, VEC, kRsOnly, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale);
+      else if (step == 0) ring_reduce_pass<T, VEC, kRsFirst, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale);
+      else if (step == N - 2) ring_reduce_pass<T, VEC, kRsLast, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale);
+      else ring_reduce_pass<T, VEC, kRsMid, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale);
+    } else {
+      ring_allgather_pass<T, VEC, U, POL>(s_tab, s_seg, s_tile, N, step - (N - 1));
+    }
+    // Publish progress the way a NIC would need it: every lane's stores have left the CU
+    // (workgroup release + barrier), then one lane makes them visible system-wide (one L2
+    // write-back per block and step, not one per wave) and only then writes the progress word.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();  // also: every lane has read s_verdict before lane 0 writes it again
+    if (threadIdx.x == 0) {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");
+      sys_store(&ctrl->block_step[blockIdx.x], static_cast<unsigned int>(step + 1));
     }
   }
 }
@@ -675,6 +765,19 @@ struct RingAllgather {
   }
 };
 
+template <typename T, int VEC>
+struct RingPersistent {
+  const PtrTable& ring; int N; const SegTable& seg; float* acc; float scale; Ctrl* ctrl;
+  unsigned n_blocks; unsigned long long timeout_ticks; hipStream_t stream;
+  template <int POL> hipError_t operator()(unsigned) const {
+    const SegTable tiles = ring_tiles(seg, N, VEC, kPersistentUnroll);
+    const dim3 grid(n_blocks), block(kThreads);
+    launch(k_ring_persistent<T, VEC, POL>, grid, block, stream, ring, seg, tiles, N, acc, scale, ctrl,
+           timeout_ticks, timeout_ticks / 10 + 100000);
+    return hipGetLastError();
+  }
+};
+
 }  // namespace
 
 // ---- exported launchers ----------------------------------------------------
@@ -715,6 +818,26 @@ hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, con
   }
   if (vec) return with_policy(ring_allgather_cfg(seg.begin[n_live], 2), RingAllgather<bf16, 8>{ring, n_live, step, seg, stream});
   return with_policy(ring_allgather_cfg(seg.begin[n_live], 2), RingAllgather<bf16, 1>{ring, n_live, step, seg, stream});
+}
+
+hipError_t launch_ring_persistent(const PtrTable& ring, int n_live, const SegTable& seg,
+                                  ftar_dtype_t dtype, bool vec, float* acc, float scale, Ctrl* ctrl_dev,
+                                  unsigned n_blocks, unsigned long long timeout_ticks,
+                                  hipStream_t stream) {
+  // same store policy as the middle ReduceScatter step: what a step writes, the next one reads
+  const LaunchCfg cfg = launch_cfg(1, seg.begin[n_live] * 4 <= 256 * kMiB ? 1 : 3);
+  if (dtype == FTAR_F32) {
+    if (vec)
+      return with_policy(cfg, RingPersistent<float, 4>{ring, n_live, seg, acc, scale, ctrl_dev, n_blocks,
+                                                       timeout_ticks, stream});
+    return with_policy(cfg, RingPersistent<float, 1>{ring, n_live, seg, acc, scale, ctrl_dev, n_blocks,
+                                                     timeout_ticks, stream});
+  }
+  if (vec)
+    return with_policy(cfg, RingPersistent<bf16, 4>{ring, n_live, seg, acc, scale, ctrl_dev, n_blocks,
+                                                    timeout_ticks, stream});
+  return with_policy(cfg, RingPersistent<bf16, 1>{ring, n_live, seg, acc, scale, ctrl_dev, n_blocks,
+                                                  timeout_ticks, stream});
 }
 
 }  // namespace ftar

@@ -1,0 +1,177 @@
+"""GPU: the CPU-gated persistent ring kernel (ftar_ring_persistent): same bits as the per-step
+kernels and the oracle; a wait that is never satisfied ends by timeout, a cancel ends the kernel
+at the next wait; in both cases the kernel exits normally and the user buffers are intact."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import assert_same, code, host, rand_bufs, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2602_00277_amd import binding
+    binding.lib()
+    return binding
+
+
+def _wait_progress(ctrl, at_least, limit_s=10.0):
+    t0 = time.time()
+    while ctrl.progress() < at_least:
+        if time.time() - t0 > limit_s:
+            return False
+        time.sleep(0.0005)
+    return True
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("n,mask", [(2, 0b11), (3, 0b111), (8, 0b11110111), (16, 0xFFFF), (16, 0xFDFF)])
+def test_all_steps_released_matches_oracle_and_step_kernels(B, oracle, dtype, n, mask):
+    N = bin(mask).count("1")
+    chunk = 1024
+    count = N * chunk * 21 + 555
+    say("persistent ring", dtype, n, hex(mask), count)
+    bufs = rand_bufs(n, count, dtype, seed=n + 1, dist="student_t3", mask=mask)
+    orig = [host(b) for b in bufs]
+    ref = [b.clone() for b in bufs]
+    plan = B.ftar_plan(n, mask, count, chunk, dtype)
+    acc = torch.empty(count, dtype=torch.float32, device="cuda")
+    B.ring_allreduce(plan, ref, acc)                      # per-step kernels
+    ctrl = B.ftar_ctrl_create()
+    B.ftar_ring_persistent(plan, bufs, acc, ctrl, timeout_us=5_000_000)
+    ctrl.release(2 * N - 2)                               # the CPU lets every step go
+    torch.cuda.synchronize()
+    st, done = ctrl.result()
+    assert st == B.FTAR_OK and done == 2 * N - 2
+    want = oracle.ring_closed_form(orig, mask, count, chunk, code(dtype))
+    for r in range(n):
+        assert_same(host(bufs[r]), want if (mask >> r) & 1 else orig[r], "buf %d" % r)
+        assert torch.equal(bufs[r].view(torch.uint8), ref[r].view(torch.uint8))
+    ctrl.destroy()
+
+
+@pytest.mark.parametrize("n_blocks", [1, 2, 7, 64, 1024])
+def test_any_cu_budget_gives_the_same_bits(B, oracle, n_blocks):
+    n, mask, chunk = 8, 0xFF, 512
+    count = 8 * chunk * 13 + 77
+    say("persistent ring blocks", n_blocks)
+    bufs = rand_bufs(n, count, torch.bfloat16, seed=5, dist="student_t3")
+    orig = [host(b) for b in bufs]
+    plan = B.ftar_plan(n, mask, count, chunk, torch.bfloat16)
+    acc = torch.empty(count, dtype=torch.float32, device="cuda")
+    ctrl = B.ftar_ctrl_create()
+    B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=n_blocks, timeout_us=5_000_000)
+    ctrl.release(14)
+    torch.cuda.synchronize()
+    assert ctrl.result() == (B.FTAR_OK, 14)
+    want = oracle.ring_closed_form(orig, mask, count, chunk, 1)
+    for r in range(n):
+        assert_same(host(bufs[r]), want, "buf %d" % r)
+
+
+def test_cpu_gates_every_step(B, oracle):
+    # the CPU plays the network: it releases step s+1 only after every workgroup reported step s
+    n, mask, chunk = 6, 0b111111, 256
+    count = 6 * chunk * 9 + 3
+    say("persistent ring gated")
+    bufs = rand_bufs(n, count, torch.float32, seed=8)
+    orig = [host(b) for b in bufs]
+    plan = B.ftar_plan(n, mask, count, chunk, torch.float32)
+    acc = torch.empty(count, dtype=torch.float32, device="cuda")
+    ctrl = B.ftar_ctrl_create()
+    B.ftar_ring_persistent(plan, bufs, acc, ctrl, timeout_us=5_000_000)
+    for s in range(10):
+        assert ctrl.progress() <= s
+        ctrl.release(s + 1)
+        assert _wait_progress(ctrl, s + 1), "step %d not reported" % s
+    torch.cuda.synchronize()
+    assert ctrl.result() == (B.FTAR_OK, 10)
+    want = oracle.ring_closed_form(orig, mask, count, chunk, 0)
+    for r in range(n):
+        assert_same(host(bufs[r]), want, "buf %d" % r)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_unreleased_step_times_out_and_leaves_inputs_intact(B, oracle, dtype):
+    # the CPU never releases ReduceScatter step 3: every workgroup's bounded wait ends by itself
+    n, mask, chunk = 8, 0xFF, 512
+    count = 8 * chunk * 5 + 9
+    say("persistent ring timeout", dtype)
+    bufs = rand_bufs(n, count, dtype, seed=9, dist="student_t3")
+    orig = [host(b) for b in bufs]
+    plan = B.ftar_plan(n, mask, count, chunk, dtype)
+    acc = torch.empty(count, dtype=torch.float32, device="cuda")
+    ctrl = B.ftar_ctrl_create()
+    B.ftar_ring_persistent(plan, bufs, acc, ctrl, timeout_us=20_000)     # 20 ms
+    ctrl.release(3)
+    t0 = time.time()
+    torch.cuda.synchronize()
+    assert time.time() - t0 < 5.0
+    st, done = ctrl.result()
+    assert st == B.FTAR_ERR_STALE_PLAN and B.ftar_status_is_retryable(st) and done == 3
+    for r in range(n):
+        assert_same(host(bufs[r]), orig[r], "buf %d untouched" % r)
+    assert_same(host(acc), oracle.ring_partial(orig, mask, count, chunk, code(dtype), 3), "in-flight partials")
+    # retry: a fresh call on the same control block completes
+    B.ftar_ring_persistent(plan, bufs, acc, ctrl, timeout_us=5_000_000)
+    ctrl.release(14)
+    torch.cuda.synchronize()
+    assert ctrl.result() == (B.FTAR_OK, 14)
+    want = oracle.ring_closed_form(orig, mask, count, chunk, code(dtype))
+    for r in range(n):
+        assert_same(host(bufs[r]), want, "buf %d after retry" % r)
+
+
+def test_cancel_then_replan_over_the_survivors(B, oracle):
+    # replica 9 of 16 leaves while the kernel waits for step 5: cancel, re-plan for 15, restart
+    n, chunk = 16, 256
+    count = 16 * 15 * chunk + 31
+    say("persistent ring cancel + replan")
+    bufs = rand_bufs(n, count, torch.bfloat16, seed=10, dist="student_t3")
+    orig = [host(b) for b in bufs]
+    acc = torch.empty(count, dtype=torch.float32, device="cuda")
+    ctrl = B.ftar_ctrl_create()
+    p16 = B.ftar_plan(n, 0xFFFF, count, chunk, torch.bfloat16)
+    B.ftar_ring_persistent(p16, bufs, acc, ctrl, timeout_us=5_000_000)
+    ctrl.release(5)
+    assert _wait_progress(ctrl, 5)
+    ctrl.cancel()
+    torch.cuda.synchronize()
+    st, done = ctrl.result()
+    assert st == B.FTAR_ERR_STALE_PLAN and done == 5
+    for r in range(n):
+        assert_same(host(bufs[r]), orig[r], "buf %d untouched" % r)
+    new_mask = 0xFFFF & ~(1 << 9)
+    p15 = B.ftar_plan(n, new_mask, count, chunk, torch.bfloat16)
+    B.ftar_ring_persistent(p15, bufs, acc, ctrl, timeout_us=5_000_000)
+    ctrl.release(28)
+    torch.cuda.synchronize()
+    assert ctrl.result() == (B.FTAR_OK, 28)
+    fresh = oracle.ring_closed_form(orig, new_mask, count, chunk, 1)
+    for r in range(n):
+        assert_same(host(bufs[r]), orig[r] if r == 9 else fresh, "buf %d" % r)
+
+
+def test_argument_errors_and_ring_of_one(B):
+    plan = B.ftar_plan(4, 0b1111, 1000, 8, torch.float32)
+    bufs = [torch.zeros(1000, device="cuda") for _ in range(4)]
+    acc = torch.zeros(1000, device="cuda")
+    ctrl = B.ftar_ctrl_create()
+    say("persistent ring errors")
+    with pytest.raises(B.FtarError) as e:
+        B.ftar_ring_persistent(plan, bufs, acc, ctrl, timeout_us=0)
+    assert e.value.status == B.FTAR_ERR_INVALID_ARG
+    with pytest.raises(B.FtarError) as e:
+        B.ftar_ring_persistent(plan, bufs, None, ctrl)
+    assert e.value.status == B.FTAR_ERR_INVALID_ARG
+    with pytest.raises(B.FtarError) as e:
+        B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=5000)
+    assert e.value.status == B.FTAR_ERR_INVALID_ARG
+    one = B.ftar_plan(4, 0b0100, 1000, 8, torch.float32)
+    B.ftar_ring_persistent(one, bufs, acc, ctrl)       # nothing to do, nothing launched
+    torch.cuda.synchronize()
+    assert ctrl.result() == (B.FTAR_OK, 0)
