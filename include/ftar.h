@@ -180,19 +180,28 @@ ftar_status_t ftar_reduce_masked_bucketed(const void* const* bufs, int n_replica
  * the last ReduceScatter step (s = N-2) is released: a cancel or timeout before that leaves every
  * bufs[r] untouched and the caller re-plans and restarts.
  *
- * ctrl is a control block in coherent host-pinned memory made by ftar_ctrl_create() (a host
- * allocation at set-up, not on the hot path).  One control block serves one call at a time;
+ * ctrl is a control block made by ftar_ctrl_create(): coherent host-pinned memory plus a mirror
+ * of a few hundred bytes in device memory (both allocated at set-up, not on the hot path).  One control block serves one call at a time;
  * ftar_ring_persistent re-arms it (released = 0, no cancel) before launching.
- *   n_blocks    workgroups (= compute units used), 1..1024; 0 = one per compute unit
+ *   n_blocks    worker workgroups (= compute units used), 1..1024; 0 = one per compute unit;
+ *               one more workgroup relays the CPU's gate word to the workers
  *   timeout_us  per-wait limit in microseconds (> 0)
+ *   flags       FTAR_PERSIST_PUBLISH: a step counts as done (ftar_ctrl_progress) only after its
+ *               data has been written back from the GPU's L2, as a NIC reading the buffers on
+ *               the CPU's signal would need; without it progress means "computed", and the data
+ *               is guaranteed visible off the GPU once the stream has been synchronised.
+ *               FTAR_PERSIST_ALIGN: workgroups that ran ahead wait (bounded) for the others after
+ *               every step; a performance hint for long steps, never needed for correctness.
  * Returns at once like every other compute call.  After the stream has been synchronised,
  * ftar_ctrl_result tells how it ended: FTAR_OK (all steps done), or FTAR_ERR_STALE_PLAN
  * (retryable: cancelled or timed out); *steps_done = steps completed by every workgroup.
  */
+#define FTAR_PERSIST_PUBLISH 1u
+#define FTAR_PERSIST_ALIGN 2u
 void* ftar_ctrl_create(void);   /* NULL on failure */
 void ftar_ctrl_destroy(void* ctrl);
 ftar_status_t ftar_ring_persistent(const ftar_plan_t* plan, void* const* bufs, float* acc, void* ctrl,
-                                   int n_blocks, unsigned timeout_us, void* stream);
+                                   int n_blocks, unsigned timeout_us, unsigned flags, void* stream);
 /* CPU side of the handshake (plain host stores/loads on the control block; callable from any
  * thread while the kernel runs). */
 void ftar_ctrl_release(void* ctrl, int n_steps); /* steps [0, n_steps) may run */

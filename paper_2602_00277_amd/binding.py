@@ -27,6 +27,9 @@ FTAR_ERR_BAD_STEP = 4
 FTAR_ERR_STALE_PLAN = 16
 FTAR_ERR_DEVICE = 32
 
+FTAR_PERSIST_PUBLISH = 1
+FTAR_PERSIST_ALIGN = 2
+
 # every symbol include/ftar.h declares
 EXPORTS = [
     "ftar_plan", "ftar_plan_destroy", "ftar_plan_set_dtype", "ftar_plan_n_live",
@@ -98,7 +101,7 @@ def lib():
     L.ftar_ctrl_destroy.restype = None
     L.ftar_ctrl_destroy.argtypes = [vp]
     L.ftar_ring_persistent.restype = ci
-    L.ftar_ring_persistent.argtypes = [vp, vp, vp, vp, ci, ctypes.c_uint, vp]
+    L.ftar_ring_persistent.argtypes = [vp, vp, vp, vp, ci, ctypes.c_uint, ctypes.c_uint, vp]
     L.ftar_ctrl_release.restype = None
     L.ftar_ctrl_release.argtypes = [vp, ci]
     L.ftar_ctrl_cancel.restype = None
@@ -346,7 +349,7 @@ def ftar_ctrl_result(ctrl: Ctrl):
 
 def ftar_ring_persistent(plan: Plan, bufs: Sequence[Optional[torch.Tensor]],
                          acc: Optional[torch.Tensor], ctrl: Ctrl, n_blocks: int = 0,
-                         timeout_us: int = 2_000_000, stream=None) -> None:
+                         timeout_us: int = 2_000_000, flags: int = 0, stream=None) -> None:
     _check_bufs(bufs, plan.live_mask, plan.count, plan.dtype)
     if len(bufs) != plan.n_replicas:
         raise ValueError("bufs must have one entry per replica slot")
@@ -354,7 +357,7 @@ def ftar_ring_persistent(plan: Plan, bufs: Sequence[Optional[torch.Tensor]],
         raise ValueError("acc must be a GPU float32 tensor of at least count elements")
     st = lib().ftar_ring_persistent(plan.handle, _ptr_array(bufs),
                                     None if acc is None else acc.data_ptr(), ctrl.handle, n_blocks,
-                                    timeout_us, _stream_handle(stream))
+                                    timeout_us, flags, _stream_handle(stream))
     if st != FTAR_OK:
         raise FtarError(st, "ftar_ring_persistent")
 

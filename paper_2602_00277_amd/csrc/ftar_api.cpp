@@ -294,20 +294,30 @@ void* ftar_ctrl_create(void) {
     return nullptr;
   }
   std::memset(p, 0, sizeof(Ctrl));
+  void* mirror = nullptr;
+  if (hipMalloc(&mirror, sizeof(DevCtrl)) != hipSuccess || !mirror) {
+    (void)hipHostFree(p);
+    fail(FTAR_ERR_DEVICE);
+    return nullptr;
+  }
+  static_cast<Ctrl*>(p)->dev = static_cast<DevCtrl*>(mirror);
   return p;
 }
 
 void ftar_ctrl_destroy(void* ctrl) {
-  if (ctrl) (void)hipHostFree(ctrl);
+  if (!ctrl) return;
+  (void)hipFree(static_cast<Ctrl*>(ctrl)->dev);
+  (void)hipHostFree(ctrl);
 }
 
 ftar_status_t ftar_ring_persistent(const ftar_plan_t* plan, void* const* bufs, float* acc, void* ctrl,
-                                   int n_blocks, unsigned timeout_us, void* stream) {
+                                   int n_blocks, unsigned timeout_us, unsigned flags, void* stream) {
   if (!plan_ok(plan) || !bufs || !ctrl || timeout_us == 0 || n_blocks < 0 ||
-      n_blocks > kMaxPersistentBlocks)
+      n_blocks > kMaxPersistentBlocks || (flags & ~(FTAR_PERSIST_PUBLISH | FTAR_PERSIST_ALIGN)) != 0)
     return fail(FTAR_ERR_INVALID_ARG);
   const int N = plan->n_live;
   Ctrl* c = static_cast<Ctrl*>(ctrl);
+  if (!c->dev) return fail(FTAR_ERR_INVALID_ARG);
   PtrTable tab;
   std::memset(&tab, 0, sizeof(tab));
   bool vec = true;
@@ -320,46 +330,40 @@ ftar_status_t ftar_ring_persistent(const ftar_plan_t* plan, void* const* bufs, f
   unsigned blocks = n_blocks > 0 ? static_cast<unsigned>(n_blocks) : static_cast<unsigned>(device_cu_count());
   if (blocks > static_cast<unsigned>(kMaxPersistentBlocks)) blocks = kMaxPersistentBlocks;
   // re-arm the control block; the launch below orders these stores before the kernel's loads
-  c->released = 0;
-  c->cancel = 0;
+  c->gate = 0;
   c->status = 0;
   c->blocked_step = 0;
+  c->progress = 0;
   c->n_blocks = N >= 2 ? blocks : 0;
   c->n_steps = static_cast<unsigned>(2 * N - 2);
-  for (unsigned b = 0; b < blocks; ++b) c->block_step[b] = 0;
   std::atomic_thread_fence(std::memory_order_seq_cst);
   if (N < 2) return FTAR_OK;  // a ring of one has no steps: nothing to launch
   void* dev = nullptr;
   if (hipHostGetDevicePointer(&dev, ctrl, 0) != hipSuccess || !dev) return fail(FTAR_ERR_INVALID_ARG);
   hipError_t e = launch_ring_persistent(tab, N, plan->seg, plan->dtype, vec, acc, plan->scale,
-                                        static_cast<Ctrl*>(dev), blocks,
-                                        static_cast<unsigned long long>(timeout_us) * 100ull,
+                                        static_cast<Ctrl*>(dev), c->dev, blocks,
+                                        static_cast<unsigned long long>(timeout_us) * 100ull, flags,
                                         static_cast<hipStream_t>(stream));
   return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
 }
 
 void ftar_ctrl_release(void* ctrl, int n_steps) {
   if (!ctrl || n_steps < 0) return;
-  __atomic_store_n(&static_cast<Ctrl*>(ctrl)->released, static_cast<unsigned long long>(n_steps),
-                   __ATOMIC_RELEASE);
+  Ctrl* c = static_cast<Ctrl*>(ctrl);
+  const unsigned long long keep = __atomic_load_n(&c->gate, __ATOMIC_RELAXED) & kGateCancel;
+  __atomic_store_n(&c->gate, keep | static_cast<unsigned long long>(n_steps), __ATOMIC_RELEASE);
 }
 
 void ftar_ctrl_cancel(void* ctrl) {
   if (!ctrl) return;
-  __atomic_store_n(&static_cast<Ctrl*>(ctrl)->cancel, 1ull, __ATOMIC_RELEASE);
+  __atomic_fetch_or(&static_cast<Ctrl*>(ctrl)->gate, kGateCancel, __ATOMIC_RELEASE);
 }
 
 int ftar_ctrl_progress(const void* ctrl) {
   if (!ctrl) return 0;
   const Ctrl* c = static_cast<const Ctrl*>(ctrl);
-  const unsigned nb = c->n_blocks;
-  if (nb == 0) return static_cast<int>(c->n_steps);
-  unsigned lo = ~0u;
-  for (unsigned b = 0; b < nb; ++b) {
-    const unsigned v = __atomic_load_n(&c->block_step[b], __ATOMIC_ACQUIRE);
-    if (v < lo) lo = v;
-  }
-  return static_cast<int>(lo);
+  if (c->n_blocks == 0) return static_cast<int>(c->n_steps);
+  return static_cast<int>(__atomic_load_n(&c->progress, __ATOMIC_ACQUIRE));
 }
 
 ftar_status_t ftar_ctrl_result(const void* ctrl, int* steps_done) {

@@ -35,17 +35,29 @@ struct ScaleTable {
   float s[kMaxReplicas + 1];
 };
 
-// Control block of the persistent ring, in coherent host-pinned memory.  Each word the two sides
-// exchange sits on its own 64-byte line.
+// Control block of the persistent ring.  The CPU side lives in coherent host-pinned memory; each
+// word the two sides exchange sits on its own 64-byte line.  Only ONE workgroup (the relay) ever
+// reads it: 256 workgroups polling host memory over PCIe cost tens of microseconds per step.
+// The relay copies the gate into a small mirror in device memory, which the workers poll.
 constexpr int kMaxPersistentBlocks = 1024;
+constexpr int kMaxPersistentSteps = 2 * kMaxReplicas - 2;
+constexpr unsigned long long kGateCancel = 1ull << 63;
+
+struct DevCtrl {  // device memory, zeroed on the stream before every launch
+  unsigned long long gate;      // copy of Ctrl::gate, written by the relay
+  unsigned int verdict;         // 0 run, 1 a wait timed out, 2 cancelled: everybody leaves
+  unsigned int exited;          // workers that have left the kernel
+  unsigned int arrived[kMaxPersistentSteps + 2];  // workers that have finished step s
+};
+
 struct alignas(64) Ctrl {
-  alignas(64) unsigned long long released;  // CPU -> GPU: steps [0, released) may run
-  alignas(64) unsigned long long cancel;    // CPU -> GPU: non-zero = stop at the next wait
+  alignas(64) unsigned long long gate;      // CPU -> GPU: low 32 bits = steps released, bit 63 = cancel
   alignas(64) unsigned long long status;    // GPU -> CPU: 0 ok, 1 a wait timed out, 2 cancelled
-  alignas(64) unsigned long long blocked_step;  // GPU -> CPU: step a workgroup gave up at
-  alignas(64) unsigned int n_blocks;        // set by the launcher
-  unsigned int n_steps;                     // 2N-2, set by the launcher
-  alignas(64) unsigned int block_step[kMaxPersistentBlocks];  // GPU -> CPU: steps done by block b
+  unsigned long long blocked_step;          // GPU -> CPU: step a workgroup gave up at
+  alignas(64) unsigned long long progress;  // GPU -> CPU: steps finished by EVERY worker
+  alignas(64) unsigned int n_blocks;        // workers; set by the launcher
+  unsigned int n_steps;                     // 2N-2; set by the launcher
+  DevCtrl* dev;                             // the mirror, allocated with the control block
 };
 
 enum RingMode {
@@ -85,10 +97,11 @@ hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, con
                                  ftar_dtype_t dtype, bool vec, hipStream_t stream);
 
 // The whole ring in one kernel, gated by the control block (ctrl_dev = device view of it).
+// n_blocks workers plus one relay workgroup; clears *mirror on the stream first.
 hipError_t launch_ring_persistent(const PtrTable& ring, int n_live, const SegTable& seg,
                                   ftar_dtype_t dtype, bool vec, float* acc, float scale, Ctrl* ctrl_dev,
-                                  unsigned n_blocks, unsigned long long timeout_ticks,
-                                  hipStream_t stream);
+                                  DevCtrl* mirror, unsigned n_blocks, unsigned long long timeout_ticks,
+                                  unsigned flags, hipStream_t stream);
 
 }  // namespace ftar
 

@@ -395,16 +395,16 @@ __device__ __forceinline__ void stage_ring_tables(const PtrTable& ring, const Se
   __syncthreads();
 }
 
-// This block's share of one ReduceScatter step: tiles blockIdx.x, blockIdx.x + gridDim.x, ...
+// Block bx of gx's share of one ReduceScatter step: tiles bx, bx + gx, ...
 template <typename T, int VEC, int MODE, int U, int POL>
 __device__ __forceinline__ void ring_reduce_pass(T* const* s_tab, const unsigned long long* s_seg,
                                                  const unsigned long long* s_tile, int N, int step,
-                                                 float* acc, float scale) {
+                                                 float* acc, float scale, unsigned bx, unsigned gx) {
   constexpr size_t kTileElems = static_cast<size_t>(kThreads) * U * VEC;
   const size_t total = uniform_u64(s_tile[N]);
   int k = 0;
   size_t next = uniform_u64(s_tile[1]);
-  for (size_t g = blockIdx.x; g < total; g += gridDim.x) {
+  for (size_t g = bx; g < total; g += gx) {
     const RingTile t = ring_tile_of<kTileElems>(g, k, next, s_seg, s_tile);
     float* a = acc + t.begin;  // never dereferenced in the N == 2 mode
     if constexpr (MODE == kRsFirst) {
@@ -423,10 +423,11 @@ __device__ __forceinline__ void ring_reduce_pass(T* const* s_tab, const unsigned
   }
 }
 
-// This block's share of one AllGather step: bit copy from ring position k+t-1 to k+t.
+// Block bx of gx's share of one AllGather step: bit copy from ring position k+t-1 to k+t.
 template <typename T, int VEC, int U, int POL>
 __device__ __forceinline__ void ring_allgather_pass(T* const* s_tab, const unsigned long long* s_seg,
-                                                    const unsigned long long* s_tile, int N, int step) {
+                                                    const unsigned long long* s_tile, int N, int step,
+                                                    unsigned bx, unsigned gx) {
   typedef typename Raw<T, VEC>::type R;
   typedef typename Raw<T, 1>::type R1;
   constexpr size_t kTileElems = static_cast<size_t>(kThreads) * U * VEC;
@@ -434,7 +435,7 @@ __device__ __forceinline__ void ring_allgather_pass(T* const* s_tab, const unsig
   const size_t total = uniform_u64(s_tile[N]);
   int k = 0;
   size_t next = uniform_u64(s_tile[1]);
-  for (size_t g = blockIdx.x; g < total; g += gridDim.x) {
+  for (size_t g = bx; g < total; g += gx) {
     const RingTile t = ring_tile_of<kTileElems>(g, k, next, s_seg, s_tile);
     const T* from = uniform_ptr(s_tab[(t.k + step + N - 1) % N]) + t.begin;
     T* to = uniform_ptr(s_tab[(t.k + step) % N]) + t.begin;
@@ -463,7 +464,7 @@ k_ring_reduce(PtrTable ring, SegTable seg, SegTable tile0, int N, int step, floa
   __shared__ T* s_tab[kMaxReplicas];
   __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
   stage_ring_tables<T>(ring, seg, tile0, N, s_tab, s_seg, s_tile);
-  ring_reduce_pass<T, VEC, MODE, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale);
+  ring_reduce_pass<T, VEC, MODE, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale, blockIdx.x, gridDim.x);
 }
 
 // One AllGather step over all N portions.
@@ -473,17 +474,27 @@ k_ring_allgather(PtrTable ring, SegTable seg, SegTable tile0, int N, int step) {
   __shared__ T* s_tab[kMaxReplicas];
   __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
   stage_ring_tables<T>(ring, seg, tile0, N, s_tab, s_seg, s_tile);
-  ring_allgather_pass<T, VEC, U, POL>(s_tab, s_seg, s_tile, N, step);
+  ring_allgather_pass<T, VEC, U, POL>(s_tab, s_seg, s_tile, N, step, blockIdx.x, gridDim.x);
 }
 
 // ---- the whole ring as one CPU-gated persistent kernel ----------------------------
-// Element i of acc (and of every replica buffer) is only ever touched by the lane that owns
-// tile position i, and the tile -> block assignment is the same in every step, so consecutive
-// steps need no synchronisation between blocks: program order within a lane is enough.  What
-// the blocks do wait for is the CPU: before step s, lane 0 polls the control block in
-// host-pinned memory until the step is released, the call is cancelled, or the wait has lasted
-// longer than the timeout (wall clock, 100 MHz); in the last two cases the whole block records
-// why and leaves, so the kernel ends no matter what the CPU does.
+// Element i of acc (and of every replica buffer) is only ever touched by the block that owns
+// the tile holding i, and the tile -> block assignment is the same in every step, so consecutive
+// steps need no synchronisation between blocks: a block-wide barrier with workgroup-scope
+// release/acquire between two steps is enough (all waves of a block share one CU and its L1).
+// That also lets the AllGather steps copy 16 bytes per lane although the ReduceScatter steps
+// hand each lane 8 bytes of bf16.
+//
+// What the blocks do wait for is the CPU.  The grid is n workers plus one relay block.  The
+// relay is the only one that reads the gate word in host-pinned memory (every worker polling
+// it over PCIe costs tens of microseconds per step); it copies each new value into a mirror in
+// device memory.  Before step s a worker waits on the mirror until the step is released, the
+// call is cancelled, somebody else gave up, or its own wait has lasted longer than the timeout
+// (wall clock, 100 MHz, and a spin bound should the clock stand still): then it records why and
+// leaves.  A worker that has seen r steps released does not look again before step r.  After
+// a step each worker counts itself in; the last one to arrive publishes the progress to the
+// CPU.  The relay leaves when every step is released or every worker has left, so the kernel
+// ends no matter what the CPU does.
 __device__ __forceinline__ unsigned long long sys_load(const unsigned long long* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
@@ -491,60 +502,126 @@ template <typename V>
 __device__ __forceinline__ void sys_store(V* p, V v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
+template <typename V>
+__device__ __forceinline__ V dev_load(const V* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename V>
+__device__ __forceinline__ void dev_store(V* p, V v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
-constexpr int kPersistentUnroll = 4;
+constexpr int kPersistentUnroll = 8;
+
+__global__ void k_clear_mirror(DevCtrl* m) {
+  unsigned int* w = reinterpret_cast<unsigned int*>(m);
+  for (unsigned i = threadIdx.x; i < sizeof(DevCtrl) / 4; i += blockDim.x) w[i] = 0;
+}
+
+// The relay block: lane 0 only.
+__device__ __forceinline__ void relay_gate(Ctrl* ctrl, DevCtrl* mirror, unsigned n_workers,
+                                           unsigned n_steps, unsigned long long max_spins) {
+  if (threadIdx.x != 0) return;
+  unsigned long long last = 0;
+  // max_spins bounds one worker's wait; all workers leave within n_steps such waits plus their work,
+  // which the generous factor covers, so this loop ends even if the counters were never updated.
+  for (unsigned long long spin = 0; spin < max_spins * 4096ull; ++spin) {
+    const unsigned long long g = sys_load(&ctrl->gate);
+    if (g != last) {
+      dev_store(&mirror->gate, g);
+      last = g;
+    }
+    if ((g & kGateCancel) != 0 || (g & 0xffffffffull) >= n_steps) return;  // nothing left to relay
+    if (dev_load(&mirror->exited) >= n_workers) return;                    // nobody left to tell
+    __builtin_amdgcn_s_sleep(16);
+  }
+}
 
 template <typename T, int VEC, int POL>
 __global__ void __launch_bounds__(kThreads)
 k_ring_persistent(PtrTable ring, SegTable seg, SegTable tile0, int N, float* acc, float scale,
-                  Ctrl* ctrl, unsigned long long timeout_ticks, unsigned long long max_spins) {
+                  Ctrl* ctrl, DevCtrl* mirror, unsigned long long timeout_ticks,
+                  unsigned long long max_spins, unsigned flags) {
   __shared__ T* s_tab[kMaxReplicas];
   __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
-  __shared__ int s_verdict;  // 0 = run the step, 1 = timed out, 2 = cancelled
+  __shared__ unsigned long long s_gate;  // what lane 0 saw: released steps, or a verdict in bits 32..33
+  const int n_steps = 2 * N - 2;
+  const unsigned n_workers = gridDim.x - 1;
+  if (blockIdx.x == n_workers) {  // the last block is the relay
+    relay_gate(ctrl, mirror, n_workers, static_cast<unsigned>(n_steps), max_spins);
+    return;
+  }
   stage_ring_tables<T>(ring, seg, tile0, N, s_tab, s_seg, s_tile);
   constexpr int U = kPersistentUnroll;
-  const int n_steps = 2 * N - 2;
+  int released = 0;  // steps [0, released) are known to be released
   for (int step = 0; step < n_steps; ++step) {
-    if (threadIdx.x == 0) {
-      // Bounded twice over: by the wall clock and, should the clock ever stand still, by a
-      // spin count (one spin costs two reads of host memory, about a microsecond or more).
-      int verdict = 1;
-      const long long t0 = wall_clock64();
-      for (unsigned long long spin = 0; spin < max_spins; ++spin) {
-        if (sys_load(&ctrl->released) > static_cast<unsigned long long>(step)) { verdict = 0; break; }
-        if (sys_load(&ctrl->cancel) != 0) { verdict = 2; break; }
-        if (static_cast<unsigned long long>(wall_clock64() - t0) > timeout_ticks) break;
-        __builtin_amdgcn_s_sleep(8);
-      }
-      s_verdict = verdict;
-    }
-    __syncthreads();
-    const int verdict = s_verdict;
-    if (verdict != 0) {  // the same for every lane of the block: all leave together
+    if (step >= released) {  // same decision in every lane: `released` comes from shared memory
       if (threadIdx.x == 0) {
-        sys_store(&ctrl->blocked_step, static_cast<unsigned long long>(step));
-        sys_store(&ctrl->status, static_cast<unsigned long long>(verdict));
+        unsigned long long seen = 1ull << 32;  // verdict 1 (timed out) unless the loop says otherwise
+        const long long t0 = wall_clock64();
+        for (unsigned long long spin = 0; spin < max_spins; ++spin) {
+          const unsigned long long g = dev_load(&mirror->gate);
+          if ((g & kGateCancel) != 0) { seen = 2ull << 32; break; }
+          if ((g & 0xffffffffull) > static_cast<unsigned long long>(step)) { seen = g & 0xffffffffull; break; }
+          const unsigned v = dev_load(&mirror->verdict);
+          if (v != 0) { seen = static_cast<unsigned long long>(v) << 32; break; }
+          if (static_cast<unsigned long long>(wall_clock64() - t0) > timeout_ticks) break;
+          __builtin_amdgcn_s_sleep(4);
+        }
+        s_gate = seen;
       }
-      return;
+      __syncthreads();
+      const unsigned long long seen = s_gate;
+      const int verdict = static_cast<int>(seen >> 32);
+      if (verdict != 0) {  // the same for every lane of the block: all leave together
+        if (threadIdx.x == 0) {
+          dev_store(&mirror->verdict, static_cast<unsigned>(verdict));
+          sys_store(&ctrl->blocked_step, static_cast<unsigned long long>(step));
+          sys_store(&ctrl->status, static_cast<unsigned long long>(verdict));
+          __hip_atomic_fetch_add(&mirror->exited, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        return;
+      }
+      released = static_cast<int>(seen);
     }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // see this block's stores of the step before
     if (step < N - 1) {
-      if (N == 2) ring_reduce_pass<T, VEC, kRsOnly, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale);
-      else if (step == 0) ring_reduce_pass<T, VEC, kRsFirst, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale);
-      else if (step == N - 2) ring_reduce_pass<T, VEC, kRsLast, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale);
-      else ring_reduce_pass<T, VEC, kRsMid, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale);
+      if (N == 2) ring_reduce_pass<T, VEC, kRsOnly, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale, blockIdx.x, n_workers);
+      else if (step == 0) ring_reduce_pass<T, VEC, kRsFirst, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale, blockIdx.x, n_workers);
+      else if (step == N - 2) ring_reduce_pass<T, VEC, kRsLast, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale, blockIdx.x, n_workers);
+      else ring_reduce_pass<T, VEC, kRsMid, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale, blockIdx.x, n_workers);
     } else {
-      ring_allgather_pass<T, VEC, U, POL>(s_tab, s_seg, s_tile, N, step - (N - 1));
+      // same tiles, widest copy: kThreads*U*VEC == kThreads*(U*VEC/CV)*CV
+      constexpr int CV = VEC == 1 ? 1 : 16 / static_cast<int>(sizeof(T));
+      ring_allgather_pass<T, CV, U * VEC / CV, POL>(s_tab, s_seg, s_tile, N, step - (N - 1), blockIdx.x,
+                                                    n_workers);
     }
-    // Publish progress the way a NIC would need it: every lane's stores have left the CU
-    // (workgroup release + barrier), then one lane makes them visible system-wide (one L2
-    // write-back per block and step, not one per wave) and only then writes the progress word.
+    // Count this block in: every lane's stores have left the CU (workgroup release + barrier),
+    // then lane 0 arrives.  With FTAR_PERSIST_PUBLISH the arrival is a release at agent scope:
+    // the step's data is written back from this XCD's L2 before the count can be seen, which is
+    // what a NIC reading the buffers on the CPU's signal would need (it costs one L2 write-back
+    // per block and step: 18 % at 64 Mi elements).  The last block to arrive tells the CPU.
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();  // also: every lane has read s_verdict before lane 0 writes it again
+    __syncthreads();  // also: every lane has read s_gate before lane 0 writes it again
     if (threadIdx.x == 0) {
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");
-      sys_store(&ctrl->block_step[blockIdx.x], static_cast<unsigned int>(step + 1));
+      const unsigned before = (flags & FTAR_PERSIST_PUBLISH)
+          ? __hip_atomic_fetch_add(&mirror->arrived[step], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT)
+          : __hip_atomic_fetch_add(&mirror->arrived[step], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (before + 1 == n_workers) sys_store(&ctrl->progress, static_cast<unsigned long long>(step + 1));
+      if (flags & FTAR_PERSIST_ALIGN) {
+        // Soft barrier, a performance hint only (bounded, nobody depends on it): blocks that ran
+        // ahead wait for the stragglers, so all blocks stay in the same step and read the same
+        // few buffers.  Pays when a step is long (+7 % at 16 x 256 Mi), costs when it is short.
+        for (int spin = 0; spin < 4000; ++spin) {
+          if (dev_load(&mirror->arrived[step]) >= n_workers) break;
+          __builtin_amdgcn_s_sleep(2);
+        }
+      }
     }
+    if (flags & FTAR_PERSIST_ALIGN) __syncthreads();
   }
+  if (threadIdx.x == 0)
+    __hip_atomic_fetch_add(&mirror->exited, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---- launch geometry and access policy -----------------------------------------
@@ -768,12 +845,15 @@ struct RingAllgather {
 template <typename T, int VEC>
 struct RingPersistent {
   const PtrTable& ring; int N; const SegTable& seg; float* acc; float scale; Ctrl* ctrl;
-  unsigned n_blocks; unsigned long long timeout_ticks; hipStream_t stream;
+  DevCtrl* mirror; unsigned n_blocks; unsigned long long timeout_ticks; unsigned flags;
+  hipStream_t stream;
   template <int POL> hipError_t operator()(unsigned) const {
     const SegTable tiles = ring_tiles(seg, N, VEC, kPersistentUnroll);
-    const dim3 grid(n_blocks), block(kThreads);
+    hipLaunchKernelGGL(k_clear_mirror, dim3(1), dim3(64), 0, stream, mirror);
+    const dim3 grid(n_blocks + 1), block(kThreads);  // workers + the relay
+    // one spin of a wait is a sleep plus two loads from device memory: well over 0.1 us
     launch(k_ring_persistent<T, VEC, POL>, grid, block, stream, ring, seg, tiles, N, acc, scale, ctrl,
-           timeout_ticks, timeout_ticks / 10 + 100000);
+           mirror, timeout_ticks, timeout_ticks / 10 + 100000, flags);
     return hipGetLastError();
   }
 };
@@ -822,22 +902,22 @@ hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, con
 
 hipError_t launch_ring_persistent(const PtrTable& ring, int n_live, const SegTable& seg,
                                   ftar_dtype_t dtype, bool vec, float* acc, float scale, Ctrl* ctrl_dev,
-                                  unsigned n_blocks, unsigned long long timeout_ticks,
-                                  hipStream_t stream) {
+                                  DevCtrl* mirror, unsigned n_blocks, unsigned long long timeout_ticks,
+                                  unsigned flags, hipStream_t stream) {
   // same store policy as the middle ReduceScatter step: what a step writes, the next one reads
   const LaunchCfg cfg = launch_cfg(1, seg.begin[n_live] * 4 <= 256 * kMiB ? 1 : 3);
   if (dtype == FTAR_F32) {
     if (vec)
-      return with_policy(cfg, RingPersistent<float, 4>{ring, n_live, seg, acc, scale, ctrl_dev, n_blocks,
-                                                       timeout_ticks, stream});
-    return with_policy(cfg, RingPersistent<float, 1>{ring, n_live, seg, acc, scale, ctrl_dev, n_blocks,
-                                                     timeout_ticks, stream});
+      return with_policy(cfg, RingPersistent<float, 4>{ring, n_live, seg, acc, scale, ctrl_dev, mirror,
+                                                       n_blocks, timeout_ticks, flags, stream});
+    return with_policy(cfg, RingPersistent<float, 1>{ring, n_live, seg, acc, scale, ctrl_dev, mirror,
+                                                     n_blocks, timeout_ticks, flags, stream});
   }
   if (vec)
-    return with_policy(cfg, RingPersistent<bf16, 4>{ring, n_live, seg, acc, scale, ctrl_dev, n_blocks,
-                                                    timeout_ticks, stream});
-  return with_policy(cfg, RingPersistent<bf16, 1>{ring, n_live, seg, acc, scale, ctrl_dev, n_blocks,
-                                                  timeout_ticks, stream});
+    return with_policy(cfg, RingPersistent<bf16, 4>{ring, n_live, seg, acc, scale, ctrl_dev, mirror,
+                                                    n_blocks, timeout_ticks, flags, stream});
+  return with_policy(cfg, RingPersistent<bf16, 1>{ring, n_live, seg, acc, scale, ctrl_dev, mirror,
+                                                  n_blocks, timeout_ticks, flags, stream});
 }
 
 }  // namespace ftar

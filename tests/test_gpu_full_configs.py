@@ -101,6 +101,45 @@ def test_cfg3b_replica_leaves_before_step_five(B, oracle):
     _ring_slabs(B, oracle, w, [(0xFFFF, w.replan_before_step), (0xFFFF & ~(1 << w.replan_leaver), None)])
 
 
+def test_cfg3b_through_the_persistent_kernel(B, oracle):
+    # the same scenario driven the paper's way: one CPU-gated kernel; the CPU releases five steps,
+    # learns that replica 9 has left, cancels, re-plans for 15 and runs the new ring to the end
+    w = W.configs()[2]
+    say(w.name, "persistent kernel: 5 steps, cancel, re-plan for 15")
+    n, count, chunk = w.n_replicas, w.count, w.chunk_elems
+    new_mask = 0xFFFF & ~(1 << w.replan_leaver)
+    special = oracle.geometry(n, new_mask, count, chunk)[1:-1]
+    starts = _slab_starts(count, special, 12, seed=w.seed + 100)
+    bufs = W.draw_replicas(w, "cuda")
+    orig = {s: [host_slab(b, s, s + SLAB) for b in bufs] for s in starts}
+    acc = torch.empty(count, dtype=torch.float32, device="cuda")
+    ctrl = B.ftar_ctrl_create()
+    p16 = B.ftar_plan(n, 0xFFFF, count, chunk, w.dtype)
+    B.ftar_ring_persistent(p16, bufs, acc, ctrl, timeout_us=5_000_000)
+    ctrl.release(w.replan_before_step)
+    import time
+    t0 = time.time()
+    while ctrl.progress() < w.replan_before_step and time.time() - t0 < 20:
+        time.sleep(0.001)
+    ctrl.cancel()
+    torch.cuda.synchronize()
+    st, done = ctrl.result()
+    assert st == B.FTAR_ERR_STALE_PLAN and done == w.replan_before_step
+    p15 = B.ftar_plan(n, new_mask, count, chunk, w.dtype)
+    B.ftar_ring_persistent(p15, bufs, acc, ctrl, timeout_us=5_000_000, flags=B.FTAR_PERSIST_ALIGN)
+    ctrl.release(28)
+    torch.cuda.synchronize()
+    assert ctrl.result() == (B.FTAR_OK, 28)
+    for s in starts:
+        want = oracle.ring_closed_form(orig[s], new_mask, count, chunk, code(w.dtype), begin=s, length=SLAB)
+        for r in range(n):
+            assert_same(host_slab(bufs[r], s, s + SLAB), want if (new_mask >> r) & 1 else orig[s][r],
+                        "slab %d replica %d" % (s, r))
+    live = [r for r in range(n) if (new_mask >> r) & 1]
+    for r in live[1:]:
+        assert torch.equal(bufs[r].view(torch.int16), bufs[live[0]].view(torch.int16)), r
+
+
 def test_cfg4_two_billion_elements(B, oracle):
     w = W.configs()[3]
     say(w.name)

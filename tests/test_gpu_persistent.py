@@ -54,8 +54,9 @@ def test_all_steps_released_matches_oracle_and_step_kernels(B, oracle, dtype, n,
     ctrl.destroy()
 
 
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
 @pytest.mark.parametrize("n_blocks", [1, 2, 7, 64, 1024])
-def test_any_cu_budget_gives_the_same_bits(B, oracle, n_blocks):
+def test_any_cu_budget_gives_the_same_bits(B, oracle, n_blocks, flags):
     n, mask, chunk = 8, 0xFF, 512
     count = 8 * chunk * 13 + 77
     say("persistent ring blocks", n_blocks)
@@ -64,7 +65,7 @@ def test_any_cu_budget_gives_the_same_bits(B, oracle, n_blocks):
     plan = B.ftar_plan(n, mask, count, chunk, torch.bfloat16)
     acc = torch.empty(count, dtype=torch.float32, device="cuda")
     ctrl = B.ftar_ctrl_create()
-    B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=n_blocks, timeout_us=5_000_000)
+    B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=n_blocks, timeout_us=5_000_000, flags=flags)
     ctrl.release(14)
     torch.cuda.synchronize()
     assert ctrl.result() == (B.FTAR_OK, 14)
@@ -83,7 +84,7 @@ def test_cpu_gates_every_step(B, oracle):
     plan = B.ftar_plan(n, mask, count, chunk, torch.float32)
     acc = torch.empty(count, dtype=torch.float32, device="cuda")
     ctrl = B.ftar_ctrl_create()
-    B.ftar_ring_persistent(plan, bufs, acc, ctrl, timeout_us=5_000_000)
+    B.ftar_ring_persistent(plan, bufs, acc, ctrl, timeout_us=5_000_000, flags=B.FTAR_PERSIST_PUBLISH)
     for s in range(10):
         assert ctrl.progress() <= s
         ctrl.release(s + 1)
@@ -170,6 +171,9 @@ def test_argument_errors_and_ring_of_one(B):
     assert e.value.status == B.FTAR_ERR_INVALID_ARG
     with pytest.raises(B.FtarError) as e:
         B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=5000)
+    assert e.value.status == B.FTAR_ERR_INVALID_ARG
+    with pytest.raises(B.FtarError) as e:
+        B.ftar_ring_persistent(plan, bufs, acc, ctrl, flags=8)
     assert e.value.status == B.FTAR_ERR_INVALID_ARG
     one = B.ftar_plan(4, 0b0100, 1000, 8, torch.float32)
     B.ftar_ring_persistent(one, bufs, acc, ctrl)       # nothing to do, nothing launched
