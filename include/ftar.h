@@ -99,12 +99,35 @@ ftar_status_t ftar_plan_set_dtype(ftar_plan_t* plan, ftar_dtype_t dtype);
 
 int ftar_plan_n_live(const ftar_plan_t* plan);     /* N; 0 if plan is NULL */
 int ftar_plan_n_steps(const ftar_plan_t* plan);    /* N-1, the steps of each phase */
-size_t ftar_plan_acc_bytes(const ftar_plan_t* plan); /* count * 4: size of `acc` */
+size_t ftar_plan_acc_bytes(const ftar_plan_t* plan); /* size of `acc`: 4 bytes per element of one partition */
 float ftar_plan_scale(const ftar_plan_t* plan);    /* 1.0f/(float)N */
 /* Portion k in [0,N): element range [*begin,*end) and the replica that holds its
  * finished value after the ReduceScatter phase (the replica at ring position k-1). */
 ftar_status_t ftar_plan_segment(const ftar_plan_t* plan, int k, size_t* begin, size_t* end,
                                 int* owner_replica);
+
+/* ---------------------------------------------------------------------------
+ * ftar_plan_set_partition - split the data into partitions for ftar_ring_persistent.
+ * Paper: section 4.2 - the send and receive buffers are a fixed S x C bytes; the message is split
+ * into partitions of at most S x C x N bytes; each partition runs one whole round of the ring
+ * (2N-2 steps), then the next partition starts.
+ * Partition p covers elements [p*partition_elems, min((p+1)*partition_elems, count)) of every
+ * buffer and is split into N portions by the rule of ftar_plan applied to the partition's own
+ * length (so the result differs from the unpartitioned ring only in which rotation of the
+ * summation order an element gets).  `acc` then holds ONE partition (ftar_plan_acc_bytes) and is
+ * reused by the next one.  A "slot" is one step of one partition; slots run partition-major and
+ * are what the CPU releases and what progress counts: ftar_plan_n_slots = partitions * (2N-2).
+ * partition_elems == 0 or >= count restores the single partition.  A partitioned plan is only
+ * valid for ftar_ring_persistent; the per-step calls reject it (a caller who wants partitions
+ * with per-step kernels makes one plan per partition over offset pointers).
+ * A cancel or timeout leaves the partitions before the blocked one finished, the later ones
+ * untouched, and the blocked one untouched only if its last ReduceScatter slot was not released.
+ */
+ftar_status_t ftar_plan_set_partition(ftar_plan_t* plan, size_t partition_elems);
+int ftar_plan_n_partitions(const ftar_plan_t* plan);
+int ftar_plan_n_slots(const ftar_plan_t* plan);
+ftar_status_t ftar_plan_partition_segment(const ftar_plan_t* plan, int partition, int k, size_t* begin,
+                                          size_t* end, int* owner_replica);
 
 /* ---------------------------------------------------------------------------
  * ftar_reduce_step - one ReduceScatter step, for all N portions at once (each
@@ -172,9 +195,10 @@ ftar_status_t ftar_reduce_masked_bucketed(const void* const* bufs, int n_replica
  * cancelled and marked skipped).
  *
  * The kernel runs the 2N-2 steps of the plan in order (ReduceScatter 0..N-2, then AllGather
- * N-1..2N-3), with the arithmetic of ftar_reduce_step / ftar_allgather_step.  Before step s
- * every workgroup waits until the CPU has released it (ftar_ctrl_release(ctrl, r) with r > s);
- * after step s it publishes its progress.  A wait ends without the release when the CPU
+ * N-1..2N-3), partition after partition if the plan is partitioned, with the arithmetic of
+ * ftar_reduce_step / ftar_allgather_step.  Before slot s (one step of one partition) every
+ * workgroup waits until the CPU has released it (ftar_ctrl_release(ctrl, r) with r > s);
+ * after slot s it publishes its progress.  A wait ends without the release when the CPU
  * cancels (ftar_ctrl_cancel) or when timeout_us microseconds have passed: the workgroup then
  * records why and exits, so the kernel always terminates.  No user buffer is written before
  * the last ReduceScatter step (s = N-2) is released: a cancel or timeout before that leaves every

@@ -39,6 +39,8 @@ EXPORTS = [
     "ftar_status_str", "ftar_set_tuning", "ftar_time_next_launch",
     "ftar_ctrl_create", "ftar_ctrl_destroy", "ftar_ring_persistent", "ftar_ctrl_release",
     "ftar_ctrl_cancel", "ftar_ctrl_progress", "ftar_ctrl_result",
+    "ftar_plan_set_partition", "ftar_plan_n_partitions", "ftar_plan_n_slots",
+    "ftar_plan_partition_segment",
 ]
 
 _lib = None
@@ -96,6 +98,15 @@ def lib():
     L.ftar_set_tuning.argtypes = [ci, ci]
     L.ftar_time_next_launch.restype = None
     L.ftar_time_next_launch.argtypes = [vp, vp]
+    L.ftar_plan_set_partition.restype = ci
+    L.ftar_plan_set_partition.argtypes = [vp, sz]
+    L.ftar_plan_n_partitions.restype = ci
+    L.ftar_plan_n_partitions.argtypes = [vp]
+    L.ftar_plan_n_slots.restype = ci
+    L.ftar_plan_n_slots.argtypes = [vp]
+    L.ftar_plan_partition_segment.restype = ci
+    L.ftar_plan_partition_segment.argtypes = [vp, ci, ci, ctypes.POINTER(sz), ctypes.POINTER(sz),
+                                              ctypes.POINTER(ci)]
     L.ftar_ctrl_create.restype = vp
     L.ftar_ctrl_create.argtypes = []
     L.ftar_ctrl_destroy.restype = None
@@ -182,6 +193,28 @@ class Plan:
             raise FtarError(st, "ftar_plan_segment")
         return b.value, e.value, o.value
 
+    @property
+    def n_partitions(self) -> int:
+        return lib().ftar_plan_n_partitions(self.handle)
+
+    @property
+    def n_slots(self) -> int:
+        return lib().ftar_plan_n_slots(self.handle)
+
+    def set_partition(self, partition_elems: int) -> None:
+        st = lib().ftar_plan_set_partition(self.handle, partition_elems)
+        if st != FTAR_OK:
+            raise FtarError(st, "ftar_plan_set_partition")
+        self.partition_elems = partition_elems
+
+    def partition_segment(self, partition: int, k: int):
+        b, e, o = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_int()
+        st = lib().ftar_plan_partition_segment(self.handle, partition, k, ctypes.byref(b),
+                                               ctypes.byref(e), ctypes.byref(o))
+        if st != FTAR_OK:
+            raise FtarError(st, "ftar_plan_partition_segment")
+        return b.value, e.value, o.value
+
     def destroy(self):
         if self.handle:
             lib().ftar_plan_destroy(self.handle)
@@ -207,6 +240,10 @@ def ftar_plan(n_replicas: int, live_mask: int, count: int, chunk_elems: int,
 
 def ftar_plan_destroy(plan: Plan) -> None:
     plan.destroy()
+
+
+def ftar_plan_set_partition(plan: Plan, partition_elems: int) -> None:
+    plan.set_partition(partition_elems)
 
 
 def ftar_plan_set_dtype(plan: Plan, dtype: torch.dtype) -> None:
@@ -353,8 +390,8 @@ def ftar_ring_persistent(plan: Plan, bufs: Sequence[Optional[torch.Tensor]],
     _check_bufs(bufs, plan.live_mask, plan.count, plan.dtype)
     if len(bufs) != plan.n_replicas:
         raise ValueError("bufs must have one entry per replica slot")
-    if acc is not None and (acc.dtype != torch.float32 or acc.numel() < plan.count or not acc.is_cuda):
-        raise ValueError("acc must be a GPU float32 tensor of at least count elements")
+    if acc is not None and (acc.dtype != torch.float32 or acc.numel() * 4 < plan.acc_bytes or not acc.is_cuda):
+        raise ValueError("acc must be a GPU float32 tensor of at least one partition")
     st = lib().ftar_ring_persistent(plan.handle, _ptr_array(bufs),
                                     None if acc is None else acc.data_ptr(), ctrl.handle, n_blocks,
                                     timeout_us, flags, _stream_handle(stream))

@@ -96,8 +96,25 @@ struct ftar_plan_s {
   int ring[kMaxReplicas];  // ring position -> replica id
   float scale;             // 1.0f/(float)n_live
   ftar_dtype_t dtype;
-  SegTable seg;            // portion boundaries, n_live+1 entries
+  SegTable seg;            // portion boundaries, n_live+1 entries (of the whole buffer)
+  // partitioned ring (persistent kernel only); part_elems == 0: one partition = the whole buffer
+  size_t part_elems;
+  size_t n_parts;
+  SegTable part_seg_full;  // portions of a full partition, relative to its first element
+  SegTable part_seg_last;  // portions of the last partition
 };
+
+// Portions are whole chunks, as even as whole chunks allow: portion k starts at chunk
+// floor(k * n_chunks / N).  Only the very last chunk can be short.
+static void portions(size_t len, size_t chunk_elems, int N, SegTable* seg) {
+  const size_t n_chunks = len / chunk_elems + (len % chunk_elems ? 1 : 0);
+  for (int k = 0; k < N; ++k) {
+    const unsigned __int128 first_chunk = static_cast<unsigned __int128>(n_chunks) * k / N;
+    const unsigned __int128 b = first_chunk * chunk_elems;
+    seg->begin[k] = b < len ? static_cast<unsigned long long>(b) : len;
+  }
+  for (int k = N; k <= kMaxReplicas; ++k) seg->begin[k] = len;
+}
 
 extern "C" {
 
@@ -119,15 +136,11 @@ ftar_plan_t* ftar_plan(int n_replicas, uint64_t live_mask, size_t count, size_t 
   std::memcpy(p->ring, ring, sizeof(int) * N);
   p->scale = 1.0f / static_cast<float>(N);
   p->dtype = FTAR_BF16;
-  // Portions are whole chunks, as even as whole chunks allow: portion k starts at chunk
-  // floor(k * n_chunks / N).  Only the very last chunk can be short.
-  const size_t n_chunks = count / chunk_elems + (count % chunk_elems ? 1 : 0);
-  for (int k = 0; k < N; ++k) {
-    const unsigned __int128 first_chunk = static_cast<unsigned __int128>(n_chunks) * k / N;
-    const unsigned __int128 b = first_chunk * chunk_elems;
-    p->seg.begin[k] = b < count ? static_cast<unsigned long long>(b) : count;
-  }
-  p->seg.begin[N] = count;
+  portions(count, chunk_elems, N, &p->seg);
+  p->part_elems = 0;
+  p->n_parts = 1;
+  p->part_seg_full = p->seg;
+  p->part_seg_last = p->seg;
   return p;
 }
 
@@ -145,16 +158,59 @@ ftar_status_t ftar_plan_set_dtype(ftar_plan_t* plan, ftar_dtype_t dtype) {
   return FTAR_OK;
 }
 
+ftar_status_t ftar_plan_set_partition(ftar_plan_t* plan, size_t partition_elems) {
+  if (!plan_ok(plan)) return fail(FTAR_ERR_INVALID_ARG);
+  if (partition_elems == 0 || partition_elems >= plan->count) {
+    plan->part_elems = 0;
+    plan->n_parts = 1;
+    plan->part_seg_full = plan->seg;
+    plan->part_seg_last = plan->seg;
+    return FTAR_OK;
+  }
+  const size_t n_parts = plan->count / partition_elems + (plan->count % partition_elems ? 1 : 0);
+  if (n_parts * static_cast<size_t>(2 * plan->n_live - 2) > 0x7fffffffull) return fail(FTAR_ERR_INVALID_ARG);
+  plan->part_elems = partition_elems;
+  plan->n_parts = n_parts;
+  portions(partition_elems, plan->chunk_elems, plan->n_live, &plan->part_seg_full);
+  portions(plan->count - (n_parts - 1) * partition_elems, plan->chunk_elems, plan->n_live,
+           &plan->part_seg_last);
+  return FTAR_OK;
+}
+
 int ftar_plan_n_live(const ftar_plan_t* plan) { return plan_ok(plan) ? plan->n_live : 0; }
 int ftar_plan_n_steps(const ftar_plan_t* plan) { return plan_ok(plan) ? plan->n_live - 1 : 0; }
-size_t ftar_plan_acc_bytes(const ftar_plan_t* plan) { return plan_ok(plan) ? plan->count * 4 : 0; }
+int ftar_plan_n_partitions(const ftar_plan_t* plan) {
+  return plan_ok(plan) ? static_cast<int>(plan->n_parts) : 0;
+}
+int ftar_plan_n_slots(const ftar_plan_t* plan) {
+  return plan_ok(plan) ? static_cast<int>(plan->n_parts) * (2 * plan->n_live - 2) : 0;
+}
+size_t ftar_plan_acc_bytes(const ftar_plan_t* plan) {
+  if (!plan_ok(plan)) return 0;
+  return (plan->part_elems ? plan->part_elems : plan->count) * 4;
+}
 float ftar_plan_scale(const ftar_plan_t* plan) { return plan_ok(plan) ? plan->scale : 0.0f; }
 
 ftar_status_t ftar_plan_segment(const ftar_plan_t* plan, int k, size_t* begin, size_t* end,
                                 int* owner_replica) {
-  if (!plan_ok(plan) || k < 0 || k >= plan->n_live) return fail(FTAR_ERR_INVALID_ARG);
+  if (!plan_ok(plan) || k < 0 || k >= plan->n_live || plan->part_elems != 0)
+    return fail(FTAR_ERR_INVALID_ARG);
   if (begin) *begin = plan->seg.begin[k];
   if (end) *end = plan->seg.begin[k + 1];
+  if (owner_replica) *owner_replica = plan->ring[(k + plan->n_live - 1) % plan->n_live];
+  return FTAR_OK;
+}
+
+ftar_status_t ftar_plan_partition_segment(const ftar_plan_t* plan, int partition, int k, size_t* begin,
+                                          size_t* end, int* owner_replica) {
+  if (!plan_ok(plan) || k < 0 || k >= plan->n_live || partition < 0 ||
+      static_cast<size_t>(partition) >= plan->n_parts)
+    return fail(FTAR_ERR_INVALID_ARG);
+  const SegTable& seg = static_cast<size_t>(partition) + 1 == plan->n_parts ? plan->part_seg_last
+                                                                             : plan->part_seg_full;
+  const size_t base = static_cast<size_t>(partition) * plan->part_elems;
+  if (begin) *begin = base + seg.begin[k];
+  if (end) *end = base + seg.begin[k + 1];
   if (owner_replica) *owner_replica = plan->ring[(k + plan->n_live - 1) % plan->n_live];
   return FTAR_OK;
 }
@@ -171,15 +227,20 @@ static ftar_status_t ring_table(const ftar_plan_t* plan, void* const* bufs, PtrT
     if (!aligned(b, 16)) v = false;
     tab->p[p] = b;
   }
-  for (int k = 1; k < plan->n_live; ++k)
-    if (plan->seg.begin[k] % 8 != 0 && plan->seg.begin[k] != plan->count) v = false;
+  for (int k = 1; k < plan->n_live; ++k) {
+    if (plan->part_seg_full.begin[k] % 8 != 0 && plan->part_seg_full.begin[k] != plan->part_seg_full.begin[plan->n_live])
+      v = false;
+    if (plan->part_seg_last.begin[k] % 8 != 0 && plan->part_seg_last.begin[k] != plan->part_seg_last.begin[plan->n_live])
+      v = false;
+  }
+  if (plan->part_elems % 8 != 0) v = false;
   *vec = v;
   return FTAR_OK;
 }
 
 ftar_status_t ftar_reduce_step(const ftar_plan_t* plan, int step, void* const* bufs, float* acc,
                                void* stream) {
-  if (!plan_ok(plan) || !bufs) return fail(FTAR_ERR_INVALID_ARG);
+  if (!plan_ok(plan) || !bufs || plan->part_elems != 0) return fail(FTAR_ERR_INVALID_ARG);
   const int N = plan->n_live;
   if (step < 0 || step > N - 2) return fail(FTAR_ERR_BAD_STEP);
   PtrTable tab;
@@ -203,7 +264,7 @@ ftar_status_t ftar_reduce_step(const ftar_plan_t* plan, int step, void* const* b
 
 ftar_status_t ftar_allgather_step(const ftar_plan_t* plan, int step, void* const* bufs,
                                   void* stream) {
-  if (!plan_ok(plan) || !bufs) return fail(FTAR_ERR_INVALID_ARG);
+  if (!plan_ok(plan) || !bufs || plan->part_elems != 0) return fail(FTAR_ERR_INVALID_ARG);
   const int N = plan->n_live;
   if (step < 0 || step > N - 2) return fail(FTAR_ERR_BAD_STEP);
   PtrTable tab;
@@ -335,12 +396,17 @@ ftar_status_t ftar_ring_persistent(const ftar_plan_t* plan, void* const* bufs, f
   c->blocked_step = 0;
   c->progress = 0;
   c->n_blocks = N >= 2 ? blocks : 0;
-  c->n_steps = static_cast<unsigned>(2 * N - 2);
+  c->n_steps = static_cast<unsigned>(plan->n_parts) * static_cast<unsigned>(2 * N - 2);
   std::atomic_thread_fence(std::memory_order_seq_cst);
   if (N < 2) return FTAR_OK;  // a ring of one has no steps: nothing to launch
   void* dev = nullptr;
   if (hipHostGetDevicePointer(&dev, ctrl, 0) != hipSuccess || !dev) return fail(FTAR_ERR_INVALID_ARG);
-  hipError_t e = launch_ring_persistent(tab, N, plan->seg, plan->dtype, vec, acc, plan->scale,
+  PartGeom geom;
+  geom.n_parts = static_cast<unsigned>(plan->n_parts);
+  geom.part_elems = plan->part_elems;
+  geom.seg_full = plan->part_seg_full;
+  geom.seg_last = plan->part_seg_last;
+  hipError_t e = launch_ring_persistent(tab, N, geom, plan->dtype, vec, acc, plan->scale,
                                         static_cast<Ctrl*>(dev), c->dev, blocks,
                                         static_cast<unsigned long long>(timeout_us) * 100ull, flags,
                                         static_cast<hipStream_t>(stream));

@@ -40,23 +40,23 @@ struct ScaleTable {
 // reads it: 256 workgroups polling host memory over PCIe cost tens of microseconds per step.
 // The relay copies the gate into a small mirror in device memory, which the workers poll.
 constexpr int kMaxPersistentBlocks = 1024;
-constexpr int kMaxPersistentSteps = 2 * kMaxReplicas - 2;
 constexpr unsigned long long kGateCancel = 1ull << 63;
 
 struct DevCtrl {  // device memory, zeroed on the stream before every launch
   unsigned long long gate;      // copy of Ctrl::gate, written by the relay
   unsigned int verdict;         // 0 run, 1 a wait timed out, 2 cancelled: everybody leaves
   unsigned int exited;          // workers that have left the kernel
-  unsigned int arrived[kMaxPersistentSteps + 2];  // workers that have finished step s
+  unsigned int min_slot;        // slots finished by EVERY worker, maintained by the relay
+  unsigned int worker_slot[kMaxPersistentBlocks];  // slots finished by worker b
 };
 
 struct alignas(64) Ctrl {
   alignas(64) unsigned long long gate;      // CPU -> GPU: low 32 bits = steps released, bit 63 = cancel
   alignas(64) unsigned long long status;    // GPU -> CPU: 0 ok, 1 a wait timed out, 2 cancelled
   unsigned long long blocked_step;          // GPU -> CPU: step a workgroup gave up at
-  alignas(64) unsigned long long progress;  // GPU -> CPU: steps finished by EVERY worker
+  alignas(64) unsigned long long progress;  // GPU -> CPU: slots finished by EVERY worker
   alignas(64) unsigned int n_blocks;        // workers; set by the launcher
-  unsigned int n_steps;                     // 2N-2; set by the launcher
+  unsigned int n_steps;                     // slots = partitions * (2N-2); set by the launcher
   DevCtrl* dev;                             // the mirror, allocated with the control block
 };
 
@@ -97,8 +97,17 @@ hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, con
                                  ftar_dtype_t dtype, bool vec, hipStream_t stream);
 
 // The whole ring in one kernel, gated by the control block (ctrl_dev = device view of it).
+// Geometry of a partitioned ring: n_parts partitions of part_elems elements (the last one may be
+// shorter); portion boundaries are relative to the partition's first element.
+struct PartGeom {
+  unsigned n_parts;
+  unsigned long long part_elems;
+  SegTable seg_full;  // portions of a full partition
+  SegTable seg_last;  // portions of the last partition
+};
+
 // n_blocks workers plus one relay workgroup; clears *mirror on the stream first.
-hipError_t launch_ring_persistent(const PtrTable& ring, int n_live, const SegTable& seg,
+hipError_t launch_ring_persistent(const PtrTable& ring, int n_live, const PartGeom& geom,
                                   ftar_dtype_t dtype, bool vec, float* acc, float scale, Ctrl* ctrl_dev,
                                   DevCtrl* mirror, unsigned n_blocks, unsigned long long timeout_ticks,
                                   unsigned flags, hipStream_t stream);

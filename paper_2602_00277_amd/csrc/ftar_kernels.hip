@@ -399,7 +399,9 @@ __device__ __forceinline__ void stage_ring_tables(const PtrTable& ring, const Se
 template <typename T, int VEC, int MODE, int U, int POL>
 __device__ __forceinline__ void ring_reduce_pass(T* const* s_tab, const unsigned long long* s_seg,
                                                  const unsigned long long* s_tile, int N, int step,
-                                                 float* acc, float scale, unsigned bx, unsigned gx) {
+                                                 float* acc, float scale, unsigned bx, unsigned gx,
+                                                 size_t buf_off = 0) {
+  // buf_off: first element of the partition in the replica buffers (acc is partition-relative)
   constexpr size_t kTileElems = static_cast<size_t>(kThreads) * U * VEC;
   const size_t total = uniform_u64(s_tile[N]);
   int k = 0;
@@ -407,17 +409,18 @@ __device__ __forceinline__ void ring_reduce_pass(T* const* s_tab, const unsigned
   for (size_t g = bx; g < total; g += gx) {
     const RingTile t = ring_tile_of<kTileElems>(g, k, next, s_seg, s_tile);
     float* a = acc + t.begin;  // never dereferenced in the N == 2 mode
+    const size_t b0 = buf_off + t.begin;
     if constexpr (MODE == kRsFirst) {
-      T* src[2] = {uniform_ptr(s_tab[t.k]) + t.begin, uniform_ptr(s_tab[(t.k + 1) % N]) + t.begin};
+      T* src[2] = {uniform_ptr(s_tab[t.k]) + b0, uniform_ptr(s_tab[(t.k + 1) % N]) + b0};
       sum_block_tile<T, VEC, 2, false, true, U, POL>(src, nullptr, a, nullptr, scale, t.rem);
     } else if constexpr (MODE == kRsMid) {
-      T* src[1] = {uniform_ptr(s_tab[(t.k + step + 1) % N]) + t.begin};
+      T* src[1] = {uniform_ptr(s_tab[(t.k + step + 1) % N]) + b0};
       sum_block_tile<T, VEC, 1, true, true, U, POL>(src, a, a, nullptr, scale, t.rem);
     } else if constexpr (MODE == kRsLast) {
-      T* src[1] = {uniform_ptr(s_tab[(t.k + N - 1) % N]) + t.begin};
+      T* src[1] = {uniform_ptr(s_tab[(t.k + N - 1) % N]) + b0};
       sum_block_tile<T, VEC, 1, true, false, U, POL>(src, a, nullptr, src[0], scale, t.rem);
     } else {  // kRsOnly, N == 2
-      T* src[2] = {uniform_ptr(s_tab[t.k]) + t.begin, uniform_ptr(s_tab[(t.k + 1) % N]) + t.begin};
+      T* src[2] = {uniform_ptr(s_tab[t.k]) + b0, uniform_ptr(s_tab[(t.k + 1) % N]) + b0};
       sum_block_tile<T, VEC, 2, false, false, U, POL>(src, nullptr, nullptr, src[1], scale, t.rem);
     }
   }
@@ -427,7 +430,7 @@ __device__ __forceinline__ void ring_reduce_pass(T* const* s_tab, const unsigned
 template <typename T, int VEC, int U, int POL>
 __device__ __forceinline__ void ring_allgather_pass(T* const* s_tab, const unsigned long long* s_seg,
                                                     const unsigned long long* s_tile, int N, int step,
-                                                    unsigned bx, unsigned gx) {
+                                                    unsigned bx, unsigned gx, size_t buf_off = 0) {
   typedef typename Raw<T, VEC>::type R;
   typedef typename Raw<T, 1>::type R1;
   constexpr size_t kTileElems = static_cast<size_t>(kThreads) * U * VEC;
@@ -437,8 +440,8 @@ __device__ __forceinline__ void ring_allgather_pass(T* const* s_tab, const unsig
   size_t next = uniform_u64(s_tile[1]);
   for (size_t g = bx; g < total; g += gx) {
     const RingTile t = ring_tile_of<kTileElems>(g, k, next, s_seg, s_tile);
-    const T* from = uniform_ptr(s_tab[(t.k + step + N - 1) % N]) + t.begin;
-    T* to = uniform_ptr(s_tab[(t.k + step) % N]) + t.begin;
+    const T* from = uniform_ptr(s_tab[(t.k + step + N - 1) % N]) + buf_off + t.begin;
+    T* to = uniform_ptr(s_tab[(t.k + step) % N]) + buf_off + t.begin;
     if (t.rem >= kTileElems) {
       R raw[U];
 #pragma unroll
@@ -478,23 +481,29 @@ k_ring_allgather(PtrTable ring, SegTable seg, SegTable tile0, int N, int step) {
 }
 
 // ---- the whole ring as one CPU-gated persistent kernel ----------------------------
+// The data is handled in partitions (paper section 4.2: the message is split into partitions of
+// at most S x C x N bytes; each partition runs one full round of the ring, then the next one
+// starts).  A "slot" is one step of one partition; slots run in order, partition-major.  `acc`
+// holds one partition and is reused by the next, so with partitions of a few tens of MiB the
+// in-flight partial sums never leave the caches.
+//
 // Element i of acc (and of every replica buffer) is only ever touched by the block that owns
-// the tile holding i, and the tile -> block assignment is the same in every step, so consecutive
-// steps need no synchronisation between blocks: a block-wide barrier with workgroup-scope
-// release/acquire between two steps is enough (all waves of a block share one CU and its L1).
+// the tile holding i, and the tile -> block assignment is the same in every slot, so consecutive
+// slots need no synchronisation between blocks: a block-wide barrier with workgroup-scope
+// release/acquire between two slots is enough (all waves of a block share one CU and its L1).
 // That also lets the AllGather steps copy 16 bytes per lane although the ReduceScatter steps
 // hand each lane 8 bytes of bf16.
 //
-// What the blocks do wait for is the CPU.  The grid is n workers plus one relay block.  The
-// relay is the only one that reads the gate word in host-pinned memory (every worker polling
-// it over PCIe costs tens of microseconds per step); it copies each new value into a mirror in
-// device memory.  Before step s a worker waits on the mirror until the step is released, the
-// call is cancelled, somebody else gave up, or its own wait has lasted longer than the timeout
-// (wall clock, 100 MHz, and a spin bound should the clock stand still): then it records why and
-// leaves.  A worker that has seen r steps released does not look again before step r.  After
-// a step each worker counts itself in; the last one to arrive publishes the progress to the
-// CPU.  The relay leaves when every step is released or every worker has left, so the kernel
-// ends no matter what the CPU does.
+// What the blocks do wait for is the CPU.  The grid is n workers plus one relay block, and the
+// relay is the only one that talks to the CPU: it copies the gate word from host-pinned memory
+// into a mirror in device memory whenever it changes (every worker polling host memory over
+// PCIe costs tens of microseconds per step), and it publishes the minimum over the workers'
+// progress words back to the CPU.  Before slot s a worker waits on the mirror until the slot is
+// released, the call is cancelled, somebody else gave up, or its own wait has lasted longer than
+// the timeout (wall clock, 100 MHz, and a spin bound should the clock stand still): then it
+// records why and leaves.  A worker that has seen r slots released does not look again before
+// slot r.  The relay leaves when every worker has left, so the kernel ends no matter what the
+// CPU does.
 __device__ __forceinline__ unsigned long long sys_load(const unsigned long long* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
@@ -518,51 +527,91 @@ __global__ void k_clear_mirror(DevCtrl* m) {
   for (unsigned i = threadIdx.x; i < sizeof(DevCtrl) / 4; i += blockDim.x) w[i] = 0;
 }
 
-// The relay block: lane 0 only.
-__device__ __forceinline__ void relay_gate(Ctrl* ctrl, DevCtrl* mirror, unsigned n_workers,
-                                           unsigned n_steps, unsigned long long max_spins) {
-  if (threadIdx.x != 0) return;
-  unsigned long long last = 0;
-  // max_spins bounds one worker's wait; all workers leave within n_steps such waits plus their work,
-  // which the generous factor covers, so this loop ends even if the counters were never updated.
-  for (unsigned long long spin = 0; spin < max_spins * 4096ull; ++spin) {
-    const unsigned long long g = sys_load(&ctrl->gate);
-    if (g != last) {
-      dev_store(&mirror->gate, g);
-      last = g;
+// The relay block (all its lanes take part in the scan of the workers' progress words).
+__device__ __forceinline__ void relay_loop(Ctrl* ctrl, DevCtrl* mirror, unsigned n_workers,
+                                           unsigned long long max_spins, unsigned flags) {
+  __shared__ unsigned s_min;
+  __shared__ int s_last_round;
+  unsigned long long last_gate = 0;
+  unsigned last_min = 0;
+  // max_spins bounds one wait of one worker; every worker leaves after at most n_slots such waits
+  // plus its work, so the factor below is never reached: it only guarantees termination.
+  for (unsigned long long spin = 0; spin < max_spins * 65536ull; ++spin) {
+    if (threadIdx.x == 0) {
+      // decide first whether this is the last round, then scan: a worker writes its progress word
+      // before it counts itself out, so the scan of the last round sees every final value
+      s_last_round = __hip_atomic_load(&mirror->exited, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= n_workers;
+      s_min = 0xffffffffu;
+      const unsigned long long g = sys_load(&ctrl->gate);
+      if (g != last_gate) {
+        dev_store(&mirror->gate, g);
+        last_gate = g;
+      }
     }
-    if ((g & kGateCancel) != 0 || (g & 0xffffffffull) >= n_steps) return;  // nothing left to relay
-    if (dev_load(&mirror->exited) >= n_workers) return;                    // nobody left to tell
-    __builtin_amdgcn_s_sleep(16);
+    __syncthreads();
+    unsigned lo = 0xffffffffu;
+    for (unsigned b = threadIdx.x; b < n_workers; b += kThreads) {
+      const unsigned v = dev_load(&mirror->worker_slot[b]);
+      lo = v < lo ? v : lo;
+    }
+    atomicMin(&s_min, lo);
+    __syncthreads();
+    const int last_round = s_last_round;
+    if (threadIdx.x == 0) {
+      const unsigned m = s_min;
+      if (m != last_min) {
+        if (flags & FTAR_PERSIST_PUBLISH) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        dev_store(&mirror->min_slot, m);
+        sys_store(&ctrl->progress, static_cast<unsigned long long>(m));
+        last_min = m;
+      }
+    }
+    if (last_round) return;  // the same for every lane
+    __builtin_amdgcn_s_sleep(8);
+    __syncthreads();  // everybody has read s_last_round before lane 0 writes it again
   }
 }
 
 template <typename T, int VEC, int POL>
 __global__ void __launch_bounds__(kThreads)
-k_ring_persistent(PtrTable ring, SegTable seg, SegTable tile0, int N, float* acc, float scale,
-                  Ctrl* ctrl, DevCtrl* mirror, unsigned long long timeout_ticks,
+k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable tile_last, int N, float* acc,
+                  float scale, Ctrl* ctrl, DevCtrl* mirror, unsigned long long timeout_ticks,
                   unsigned long long max_spins, unsigned flags) {
   __shared__ T* s_tab[kMaxReplicas];
-  __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
-  __shared__ unsigned long long s_gate;  // what lane 0 saw: released steps, or a verdict in bits 32..33
-  const int n_steps = 2 * N - 2;
+  __shared__ unsigned long long s_seg[2][kMaxReplicas + 1], s_tile[2][kMaxReplicas + 1];
+  __shared__ unsigned long long s_gate;  // what lane 0 saw: released slots, or a verdict in bits 32..33
   const unsigned n_workers = gridDim.x - 1;
   if (blockIdx.x == n_workers) {  // the last block is the relay
-    relay_gate(ctrl, mirror, n_workers, static_cast<unsigned>(n_steps), max_spins);
+    relay_loop(ctrl, mirror, n_workers, max_spins, flags);
     return;
   }
-  stage_ring_tables<T>(ring, seg, tile0, N, s_tab, s_seg, s_tile);
+  const unsigned tid = threadIdx.x;
+  if (tid < static_cast<unsigned>(N)) s_tab[tid] = static_cast<T*>(ring.p[tid]);
+  if (tid <= static_cast<unsigned>(N)) {
+    s_seg[0][tid] = geom.seg_full.begin[tid];
+    s_tile[0][tid] = tile_full.begin[tid];
+    s_seg[1][tid] = geom.seg_last.begin[tid];
+    s_tile[1][tid] = tile_last.begin[tid];
+  }
+  __syncthreads();
   constexpr int U = kPersistentUnroll;
-  int released = 0;  // steps [0, released) are known to be released
-  for (int step = 0; step < n_steps; ++step) {
-    if (step >= released) {  // same decision in every lane: `released` comes from shared memory
-      if (threadIdx.x == 0) {
+  const unsigned n_steps = static_cast<unsigned>(2 * N - 2);
+  const unsigned n_slots = geom.n_parts * n_steps;
+  unsigned released = 0;  // slots [0, released) are known to be released
+  unsigned part = 0, ustep = 0;
+  for (unsigned slot = 0; slot < n_slots; ++slot, ++ustep) {
+    if (ustep == n_steps) {
+      ustep = 0;
+      ++part;
+    }
+    if (slot >= released) {  // same decision in every lane: `released` comes from shared memory
+      if (tid == 0) {
         unsigned long long seen = 1ull << 32;  // verdict 1 (timed out) unless the loop says otherwise
         const long long t0 = wall_clock64();
         for (unsigned long long spin = 0; spin < max_spins; ++spin) {
           const unsigned long long g = dev_load(&mirror->gate);
           if ((g & kGateCancel) != 0) { seen = 2ull << 32; break; }
-          if ((g & 0xffffffffull) > static_cast<unsigned long long>(step)) { seen = g & 0xffffffffull; break; }
+          if ((g & 0xffffffffull) > slot) { seen = g & 0xffffffffull; break; }
           const unsigned v = dev_load(&mirror->verdict);
           if (v != 0) { seen = static_cast<unsigned long long>(v) << 32; break; }
           if (static_cast<unsigned long long>(wall_clock64() - t0) > timeout_ticks) break;
@@ -572,56 +621,59 @@ k_ring_persistent(PtrTable ring, SegTable seg, SegTable tile0, int N, float* acc
       }
       __syncthreads();
       const unsigned long long seen = s_gate;
-      const int verdict = static_cast<int>(seen >> 32);
+      const unsigned verdict = static_cast<unsigned>(seen >> 32);
       if (verdict != 0) {  // the same for every lane of the block: all leave together
-        if (threadIdx.x == 0) {
-          dev_store(&mirror->verdict, static_cast<unsigned>(verdict));
-          sys_store(&ctrl->blocked_step, static_cast<unsigned long long>(step));
+        if (tid == 0) {
+          dev_store(&mirror->verdict, verdict);
+          sys_store(&ctrl->blocked_step, static_cast<unsigned long long>(slot));
           sys_store(&ctrl->status, static_cast<unsigned long long>(verdict));
-          __hip_atomic_fetch_add(&mirror->exited, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_fetch_add(&mirror->exited, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         }
         return;
       }
-      released = static_cast<int>(seen);
+      released = static_cast<unsigned>(seen);
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // see this block's stores of the step before
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // see this block's stores of the slot before
+    const int step = static_cast<int>(ustep);
+    const int sel = part + 1 == geom.n_parts ? 1 : 0;
+    const unsigned long long* seg = s_seg[sel];
+    const unsigned long long* til = s_tile[sel];
+    const size_t off = static_cast<size_t>(part) * geom.part_elems;
     if (step < N - 1) {
-      if (N == 2) ring_reduce_pass<T, VEC, kRsOnly, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale, blockIdx.x, n_workers);
-      else if (step == 0) ring_reduce_pass<T, VEC, kRsFirst, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale, blockIdx.x, n_workers);
-      else if (step == N - 2) ring_reduce_pass<T, VEC, kRsLast, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale, blockIdx.x, n_workers);
-      else ring_reduce_pass<T, VEC, kRsMid, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale, blockIdx.x, n_workers);
+      if (N == 2) ring_reduce_pass<T, VEC, kRsOnly, U, POL>(s_tab, seg, til, N, step, acc, scale, blockIdx.x, n_workers, off);
+      else if (step == 0) ring_reduce_pass<T, VEC, kRsFirst, U, POL>(s_tab, seg, til, N, step, acc, scale, blockIdx.x, n_workers, off);
+      else if (step == N - 2) ring_reduce_pass<T, VEC, kRsLast, U, POL>(s_tab, seg, til, N, step, acc, scale, blockIdx.x, n_workers, off);
+      else ring_reduce_pass<T, VEC, kRsMid, U, POL>(s_tab, seg, til, N, step, acc, scale, blockIdx.x, n_workers, off);
     } else {
       // same tiles, widest copy: kThreads*U*VEC == kThreads*(U*VEC/CV)*CV
       constexpr int CV = VEC == 1 ? 1 : 16 / static_cast<int>(sizeof(T));
-      ring_allgather_pass<T, CV, U * VEC / CV, POL>(s_tab, s_seg, s_tile, N, step - (N - 1), blockIdx.x,
-                                                    n_workers);
+      ring_allgather_pass<T, CV, U * VEC / CV, POL>(s_tab, seg, til, N, step - (N - 1), blockIdx.x, n_workers, off);
     }
-    // Count this block in: every lane's stores have left the CU (workgroup release + barrier),
-    // then lane 0 arrives.  With FTAR_PERSIST_PUBLISH the arrival is a release at agent scope:
-    // the step's data is written back from this XCD's L2 before the count can be seen, which is
-    // what a NIC reading the buffers on the CPU's signal would need (it costs one L2 write-back
-    // per block and step: 18 % at 64 Mi elements).  The last block to arrive tells the CPU.
+    // Report the slot: every lane's stores have left the CU (workgroup release + barrier), then
+    // lane 0 writes this worker's progress word.  With FTAR_PERSIST_PUBLISH that store is a
+    // release at agent scope: the slot's data is written back from this XCD's L2 before the
+    // progress can be seen, which is what a NIC reading the buffers on the CPU's signal would
+    // need (one L2 write-back per block and slot: 18 % at 64 Mi elements).
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();  // also: every lane has read s_gate before lane 0 writes it again
-    if (threadIdx.x == 0) {
-      const unsigned before = (flags & FTAR_PERSIST_PUBLISH)
-          ? __hip_atomic_fetch_add(&mirror->arrived[step], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT)
-          : __hip_atomic_fetch_add(&mirror->arrived[step], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (before + 1 == n_workers) sys_store(&ctrl->progress, static_cast<unsigned long long>(step + 1));
+    if (tid == 0) {
+      if (flags & FTAR_PERSIST_PUBLISH)
+        __hip_atomic_store(&mirror->worker_slot[blockIdx.x], slot + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+      else
+        dev_store(&mirror->worker_slot[blockIdx.x], slot + 1);
       if (flags & FTAR_PERSIST_ALIGN) {
         // Soft barrier, a performance hint only (bounded, nobody depends on it): blocks that ran
-        // ahead wait for the stragglers, so all blocks stay in the same step and read the same
+        // ahead wait for the stragglers, so all blocks stay in the same slot and read the same
         // few buffers.  Pays when a step is long (+7 % at 16 x 256 Mi), costs when it is short.
         for (int spin = 0; spin < 4000; ++spin) {
-          if (dev_load(&mirror->arrived[step]) >= n_workers) break;
+          if (dev_load(&mirror->min_slot) > slot) break;
           __builtin_amdgcn_s_sleep(2);
         }
       }
     }
     if (flags & FTAR_PERSIST_ALIGN) __syncthreads();
   }
-  if (threadIdx.x == 0)
-    __hip_atomic_fetch_add(&mirror->exited, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (tid == 0) __hip_atomic_fetch_add(&mirror->exited, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---- launch geometry and access policy -----------------------------------------
@@ -844,16 +896,17 @@ struct RingAllgather {
 
 template <typename T, int VEC>
 struct RingPersistent {
-  const PtrTable& ring; int N; const SegTable& seg; float* acc; float scale; Ctrl* ctrl;
+  const PtrTable& ring; int N; const PartGeom& geom; float* acc; float scale; Ctrl* ctrl;
   DevCtrl* mirror; unsigned n_blocks; unsigned long long timeout_ticks; unsigned flags;
   hipStream_t stream;
   template <int POL> hipError_t operator()(unsigned) const {
-    const SegTable tiles = ring_tiles(seg, N, VEC, kPersistentUnroll);
-    hipLaunchKernelGGL(k_clear_mirror, dim3(1), dim3(64), 0, stream, mirror);
+    const SegTable tile_full = ring_tiles(geom.seg_full, N, VEC, kPersistentUnroll);
+    const SegTable tile_last = ring_tiles(geom.seg_last, N, VEC, kPersistentUnroll);
+    hipLaunchKernelGGL(k_clear_mirror, dim3(1), dim3(256), 0, stream, mirror);
     const dim3 grid(n_blocks + 1), block(kThreads);  // workers + the relay
     // one spin of a wait is a sleep plus two loads from device memory: well over 0.1 us
-    launch(k_ring_persistent<T, VEC, POL>, grid, block, stream, ring, seg, tiles, N, acc, scale, ctrl,
-           mirror, timeout_ticks, timeout_ticks / 10 + 100000, flags);
+    launch(k_ring_persistent<T, VEC, POL>, grid, block, stream, ring, geom, tile_full, tile_last, N, acc,
+           scale, ctrl, mirror, timeout_ticks, timeout_ticks / 10 + 100000, flags);
     return hipGetLastError();
   }
 };
@@ -900,23 +953,25 @@ hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, con
   return with_policy(ring_allgather_cfg(seg.begin[n_live], 2), RingAllgather<bf16, 1>{ring, n_live, step, seg, stream});
 }
 
-hipError_t launch_ring_persistent(const PtrTable& ring, int n_live, const SegTable& seg,
+hipError_t launch_ring_persistent(const PtrTable& ring, int n_live, const PartGeom& geom,
                                   ftar_dtype_t dtype, bool vec, float* acc, float scale, Ctrl* ctrl_dev,
                                   DevCtrl* mirror, unsigned n_blocks, unsigned long long timeout_ticks,
                                   unsigned flags, hipStream_t stream) {
-  // same store policy as the middle ReduceScatter step: what a step writes, the next one reads
-  const LaunchCfg cfg = launch_cfg(1, seg.begin[n_live] * 4 <= 256 * kMiB ? 1 : 3);
+  // Stores as in the middle ReduceScatter step: what a slot writes, the next one reads.  The
+  // partials of one partition are what must fit the Infinity Cache.
+  const size_t acc_bytes = (geom.n_parts > 1 ? geom.part_elems : geom.seg_full.begin[n_live]) * 4;
+  const LaunchCfg cfg = launch_cfg(1, acc_bytes <= 256 * kMiB ? 1 : 3);
   if (dtype == FTAR_F32) {
     if (vec)
-      return with_policy(cfg, RingPersistent<float, 4>{ring, n_live, seg, acc, scale, ctrl_dev, mirror,
+      return with_policy(cfg, RingPersistent<float, 4>{ring, n_live, geom, acc, scale, ctrl_dev, mirror,
                                                        n_blocks, timeout_ticks, flags, stream});
-    return with_policy(cfg, RingPersistent<float, 1>{ring, n_live, seg, acc, scale, ctrl_dev, mirror,
+    return with_policy(cfg, RingPersistent<float, 1>{ring, n_live, geom, acc, scale, ctrl_dev, mirror,
                                                      n_blocks, timeout_ticks, flags, stream});
   }
   if (vec)
-    return with_policy(cfg, RingPersistent<bf16, 4>{ring, n_live, seg, acc, scale, ctrl_dev, mirror,
+    return with_policy(cfg, RingPersistent<bf16, 4>{ring, n_live, geom, acc, scale, ctrl_dev, mirror,
                                                     n_blocks, timeout_ticks, flags, stream});
-  return with_policy(cfg, RingPersistent<bf16, 1>{ring, n_live, seg, acc, scale, ctrl_dev, mirror,
+  return with_policy(cfg, RingPersistent<bf16, 1>{ring, n_live, geom, acc, scale, ctrl_dev, mirror,
                                                   n_blocks, timeout_ticks, flags, stream});
 }
 

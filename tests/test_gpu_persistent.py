@@ -179,3 +179,82 @@ def test_argument_errors_and_ring_of_one(B):
     B.ftar_ring_persistent(one, bufs, acc, ctrl)       # nothing to do, nothing launched
     torch.cuda.synchronize()
     assert ctrl.result() == (B.FTAR_OK, 0)
+
+
+def _partitioned_reference(oracle, orig, n, mask, count, chunk, part, d):
+    """The partitioned ring by definition: an independent ring all-reduce per partition."""
+    want = np.empty_like(orig[[r for r in range(n) if (mask >> r) & 1][0]])
+    for lo in range(0, count, part):
+        hi = min(count, lo + part)
+        sl = [None if o is None else o[lo:hi].copy() for o in orig]
+        want[lo:hi] = oracle.ring_closed_form(sl, mask, hi - lo, chunk, d)
+    return want
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("part", [4096, 8192 * 3, 100000, 50000 - 8])
+def test_partitioned_ring_matches_a_ring_per_partition(B, oracle, dtype, part):
+    n, mask, chunk = 8, 0b11110111, 512
+    count = 7 * chunk * 40 + 1111
+    say("persistent partitioned", dtype, part, count)
+    bufs = rand_bufs(n, count, dtype, seed=part % 97, dist="student_t3", mask=mask)
+    orig = [host(b) for b in bufs]
+    plan = B.ftar_plan(n, mask, count, chunk, dtype)
+    plan.set_partition(part)
+    n_parts = (count + part - 1) // part
+    assert plan.n_partitions == n_parts and plan.n_slots == n_parts * 12 and plan.acc_bytes == part * 4
+    # geometry of every partition against the oracle's independent rule
+    for p in (0, n_parts - 1):
+        lo, hi = p * part, min(count, (p + 1) * part)
+        sb = oracle.geometry(n, mask, hi - lo, chunk)
+        for k in range(7):
+            b, e, _ = plan.partition_segment(p, k)
+            assert (b, e) == (lo + sb[k], lo + sb[k + 1])
+    acc = torch.full((part,), float("nan"), dtype=torch.float32, device="cuda")
+    ctrl = B.ftar_ctrl_create()
+    B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=5, timeout_us=5_000_000)
+    ctrl.release(plan.n_slots)
+    torch.cuda.synchronize()
+    assert ctrl.result() == (B.FTAR_OK, plan.n_slots)
+    want = _partitioned_reference(oracle, orig, n, mask, count, chunk, part, code(dtype))
+    for r in range(n):
+        assert_same(host(bufs[r]), want if (mask >> r) & 1 else orig[r], "buf %d" % r)
+    # the per-step kernels on one plan per partition over offset views give the same bits
+    ref = [torch.from_numpy(o.view(np.int16 if dtype == torch.bfloat16 else np.float32).copy()).cuda().view(dtype)
+           for o in orig]
+    for lo in range(0, count, part):
+        hi = min(count, lo + part)
+        sub = B.ftar_plan(n, mask, hi - lo, chunk, dtype)
+        B.ring_allreduce(sub, [x[lo:hi] for x in ref], acc)
+    torch.cuda.synchronize()
+    for r in range(n):
+        assert torch.equal(ref[r].view(torch.uint8), bufs[r].view(torch.uint8)), r
+    # the per-step calls refuse a partitioned plan
+    with pytest.raises(B.FtarError) as e:
+        B.ftar_reduce_step(plan, 0, bufs, torch.empty(count, dtype=torch.float32, device="cuda"))
+    assert e.value.status == B.FTAR_ERR_INVALID_ARG
+
+
+def test_partitioned_cancel_leaves_earlier_partitions_done_and_later_ones_untouched(B, oracle):
+    n, mask, chunk, part = 4, 0xF, 256, 8192
+    count = part * 5
+    say("persistent partitioned cancel")
+    bufs = rand_bufs(n, count, torch.float32, seed=12)
+    orig = [host(b) for b in bufs]
+    plan = B.ftar_plan(n, mask, count, chunk, torch.float32)
+    plan.set_partition(part)
+    assert plan.n_slots == 5 * 6
+    acc = torch.empty(part, dtype=torch.float32, device="cuda")
+    ctrl = B.ftar_ctrl_create()
+    B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=3, timeout_us=5_000_000)
+    ctrl.release(2 * 6 + 2)                  # two partitions and two ReduceScatter steps of the third
+    assert _wait_progress(ctrl, 14)
+    ctrl.cancel()
+    torch.cuda.synchronize()
+    st, done = ctrl.result()
+    assert st == B.FTAR_ERR_STALE_PLAN and done == 14
+    want = _partitioned_reference(oracle, orig, n, mask, count, chunk, part, 0)
+    for r in range(n):
+        got = host(bufs[r])
+        assert_same(got[:2 * part], want[:2 * part], "finished partitions, buf %d" % r)
+        assert_same(got[2 * part:], orig[r][2 * part:], "untouched partitions, buf %d" % r)
