@@ -186,6 +186,18 @@ ftar_status_t ftar_reduce_masked_bucketed(const void* const* bufs, int n_replica
                                           void* out, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * ftar_allreduce_onepass - what the whole schedule of the plan (N-1 ftar_reduce_step calls, then
+ * N-1 ftar_allgather_step calls) leaves in the replica buffers, computed in ONE pass: every
+ * element's N contributions are added in a register in the ring's order (portion k: ring
+ * positions k, k+1, ..., k+N-1 mod N; paper section 4.2, "Ring algorithm") and the rounded mean
+ * is written into all N live buffers.  Bit-identical to the step schedule; `acc` is not needed.
+ * The ring's steps exist for the network between the replicas; with all replicas' buffers on one
+ * device this is the bandwidth-optimal form: 2*N*E bytes per element.
+ * Dead replicas' buffers are neither read nor written.  N == 1: nothing to do.
+ */
+ftar_status_t ftar_allreduce_onepass(const ftar_plan_t* plan, void* const* bufs, void* stream);
+
+/* ---------------------------------------------------------------------------
  * CPU-driven persistent ring: the whole ring all-reduce as ONE kernel whose progress the CPU
  * gates through flags in host-pinned memory.
  * Paper: section 4.2, "Optimizations" (one kernel per AllReduce that busy-polls a flag in

@@ -40,7 +40,7 @@ EXPORTS = [
     "ftar_ctrl_create", "ftar_ctrl_destroy", "ftar_ring_persistent", "ftar_ctrl_release",
     "ftar_ctrl_cancel", "ftar_ctrl_progress", "ftar_ctrl_result",
     "ftar_plan_set_partition", "ftar_plan_n_partitions", "ftar_plan_n_slots",
-    "ftar_plan_partition_segment",
+    "ftar_plan_partition_segment", "ftar_allreduce_onepass",
 ]
 
 _lib = None
@@ -107,6 +107,8 @@ def lib():
     L.ftar_plan_partition_segment.restype = ci
     L.ftar_plan_partition_segment.argtypes = [vp, ci, ci, ctypes.POINTER(sz), ctypes.POINTER(sz),
                                               ctypes.POINTER(ci)]
+    L.ftar_allreduce_onepass.restype = ci
+    L.ftar_allreduce_onepass.argtypes = [vp, vp, vp]
     L.ftar_ctrl_create.restype = vp
     L.ftar_ctrl_create.argtypes = []
     L.ftar_ctrl_destroy.restype = None
@@ -323,6 +325,15 @@ def ftar_status_str(status: int) -> str:
 
 def ftar_last_error() -> int:
     return lib().ftar_last_error()
+
+
+def ftar_allreduce_onepass(plan: Plan, bufs: Sequence[Optional[torch.Tensor]], stream=None) -> None:
+    _check_bufs(bufs, plan.live_mask, plan.count, plan.dtype)
+    if len(bufs) != plan.n_replicas:
+        raise ValueError("bufs must have one entry per replica slot")
+    st = lib().ftar_allreduce_onepass(plan.handle, _ptr_array(bufs), _stream_handle(stream))
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_allreduce_onepass")
 
 
 class Ctrl:

@@ -348,6 +348,20 @@ ftar_status_t ftar_reduce_masked_bucketed(const void* const* bufs, int n_replica
   return FTAR_OK;
 }
 
+ftar_status_t ftar_allreduce_onepass(const ftar_plan_t* plan, void* const* bufs, void* stream) {
+  if (!plan_ok(plan) || !bufs || plan->part_elems != 0) return fail(FTAR_ERR_INVALID_ARG);
+  const int N = plan->n_live;
+  PtrTable tab;
+  std::memset(&tab, 0, sizeof(tab));
+  bool vec = true;
+  ftar_status_t s = ring_table(plan, bufs, &tab, &vec);
+  if (s != FTAR_OK) return fail(s);
+  if (N < 2) return FTAR_OK;  // a ring of one exchanges nothing: the buffer stays as it is
+  hipError_t e = launch_ring_onepass(tab, N, plan->seg, plan->dtype, vec, plan->scale,
+                                     static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
+}
+
 void* ftar_ctrl_create(void) {
   void* p = nullptr;
   if (hipHostMalloc(&p, sizeof(Ctrl), hipHostMallocCoherent | hipHostMallocMapped) != hipSuccess || !p) {

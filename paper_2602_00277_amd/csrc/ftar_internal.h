@@ -97,6 +97,10 @@ hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, con
                                  ftar_dtype_t dtype, bool vec, hipStream_t stream);
 
 // The whole ring in one kernel, gated by the control block (ctrl_dev = device view of it).
+// What the whole ring schedule leaves in the buffers, in one pass (N reads, N writes per element).
+hipError_t launch_ring_onepass(const PtrTable& ring, int n_live, const SegTable& seg,
+                               ftar_dtype_t dtype, bool vec, float scale, hipStream_t stream);
+
 // Geometry of a partitioned ring: n_parts partitions of part_elems elements (the last one may be
 // shorter); portion boundaries are relative to the partition's first element.
 struct PartGeom {

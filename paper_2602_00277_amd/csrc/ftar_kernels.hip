@@ -480,6 +480,111 @@ k_ring_allgather(PtrTable ring, SegTable seg, SegTable tile0, int N, int step) {
   ring_allgather_pass<T, VEC, U, POL>(s_tab, s_seg, s_tile, N, step, blockIdx.x, gridDim.x);
 }
 
+// ---- the ring's result in one pass ------------------------------------------------
+// On one device nothing forces the 2N-2 steps to be separate passes over memory: the partial sum
+// of an element can stay in a register while its N contributions are added in the ring's order
+// (portion k: positions k, k+1, ..., k+N-1 mod N), and the rounded mean can be written straight
+// into all N replica buffers.  Same bits as the step schedule, 2*N*E bytes per element instead
+// of 4*N*E + 10*N - 20 (N = 16, bf16: 64 instead of 206).
+template <typename T, int VEC, int N, int U, int POL>
+__device__ __forceinline__ void onepass_tile(T* const (&buf)[N], float scale, size_t v) {
+  typedef typename Raw<T, VEC>::type R;
+  R raw[U][N];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+#pragma unroll
+    for (int j = 0; j < N; ++j) raw[u][j] = ld<POL>(reinterpret_cast<const R*>(buf[j]) + v + u * kThreads);
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    float a[VEC], x[VEC];
+    widen(raw[u][0], a);
+#pragma unroll
+    for (int j = 1; j < N; ++j) {
+      widen(raw[u][j], x);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) a[e] = a[e] + x[e];
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) a[e] = a[e] * scale;
+    const R r = narrow<R, VEC>(a);
+#pragma unroll
+    for (int j = 0; j < N; ++j) st<POL>(reinterpret_cast<R*>(buf[j]) + v + u * kThreads, r);
+  }
+}
+
+// Any N (runtime): loads in groups of 8 in ring order starting at position k, then N stores.
+template <typename T, int VEC, int POL>
+__device__ __forceinline__ void onepass_any_one(T* const* s_tab, int N, int k, size_t base, float scale,
+                                                size_t v) {
+  typedef typename Raw<T, VEC>::type R;
+  float a[VEC];
+  for (int j0 = 0; j0 < N; j0 += 8) {
+    R raw[8];
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj)
+      if (j0 + jj < N)
+        raw[jj] = ld<POL>(reinterpret_cast<const R*>(uniform_ptr(s_tab[(k + j0 + jj) % N]) + base) + v);
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) {
+      if (j0 + jj < N) {
+        float x[VEC];
+        widen(raw[jj], x);
+        if (j0 + jj == 0) {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) a[e] = x[e];
+        } else {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) a[e] = a[e] + x[e];
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) a[e] = a[e] * scale;
+  const R r = narrow<R, VEC>(a);
+  for (int j = 0; j < N; ++j) st<POL>(reinterpret_cast<R*>(uniform_ptr(s_tab[j]) + base) + v, r);
+}
+
+template <typename T, int VEC, int POL>
+__device__ __forceinline__ void onepass_any_range(T* const* s_tab, int N, int k, size_t base, float scale,
+                                                  size_t len) {
+  const size_t n_vec = len / VEC;
+  for (size_t v = threadIdx.x; v < n_vec; v += kThreads) onepass_any_one<T, VEC, POL>(s_tab, N, k, base, scale, v);
+  if constexpr (VEC > 1) {
+    const size_t e = n_vec * VEC + threadIdx.x;
+    if (e < len) onepass_any_one<T, 1, POL>(s_tab, N, k, base, scale, e);
+  }
+}
+
+// NT = compile-time N for the unrolled tile (1..16), or 0: any N through the grouped loop.
+template <typename T, int VEC, int NT, int POL>
+__global__ void __launch_bounds__(kThreads)
+k_ring_onepass(PtrTable ring, SegTable seg, SegTable tile0, int N, float scale) {
+  __shared__ T* s_tab[kMaxReplicas];
+  __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
+  stage_ring_tables<T>(ring, seg, tile0, N, s_tab, s_seg, s_tile);
+  constexpr int U = NT == 0 ? 1 : unroll_narrow(NT);
+  constexpr size_t kTileElems = static_cast<size_t>(kThreads) * U * VEC;
+  const size_t total = uniform_u64(s_tile[N]);
+  int k = 0;
+  size_t next = uniform_u64(s_tile[1]);
+  for (size_t g = blockIdx.x; g < total; g += gridDim.x) {
+    const RingTile t = ring_tile_of<kTileElems>(g, k, next, s_seg, s_tile);
+    if constexpr (NT > 0) {
+      if (t.rem >= kTileElems) {
+        T* buf[NT];
+#pragma unroll
+        for (int m = 0; m < NT; ++m) buf[m] = uniform_ptr(s_tab[(t.k + m) % NT]) + t.begin;
+        onepass_tile<T, VEC, NT, U, POL>(buf, scale, threadIdx.x);
+        continue;
+      }
+    }
+    if (t.rem >= kTileElems) onepass_any_range<T, VEC, POL>(s_tab, N, t.k, t.begin, scale, kTileElems);
+    else onepass_any_range<T, VEC, POL>(s_tab, N, t.k, t.begin, scale, t.rem);
+  }
+}
+
 // ---- the whole ring as one CPU-gated persistent kernel ----------------------------
 // The data is handled in partitions (paper section 4.2: the message is split into partitions of
 // at most S x C x N bytes; each partition runs one full round of the ring, then the next one
@@ -895,6 +1000,30 @@ struct RingAllgather {
 };
 
 template <typename T, int VEC>
+struct RingOnepass {
+  const PtrTable& ring; int N; const SegTable& seg; float scale; hipStream_t stream;
+  template <int POL> hipError_t operator()(unsigned blocks) const {
+    const int U = (VEC == 1 || N > 16) ? 1 : unroll_narrow(N);  // must match the kernel's tile
+    const SegTable tiles = ring_tiles(seg, N, VEC, U);
+    const dim3 grid(grid_x_for(tiles.begin[N], blocks)), block(kThreads);
+    if (VEC == 1 || N > 16) {
+      launch(k_ring_onepass<T, VEC, 0, POL>, grid, block, stream, ring, seg, tiles, N, scale);
+      return hipGetLastError();
+    }
+    switch (N) {
+#define FTAR_CASE(n) \
+  case n: launch(k_ring_onepass<T, VEC, (VEC == 1 ? 0 : n), POL>, grid, block, stream, ring, seg, tiles, N, scale); break;
+      FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7) FTAR_CASE(8)
+      FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13) FTAR_CASE(14)
+      FTAR_CASE(15) FTAR_CASE(16)
+#undef FTAR_CASE
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
+};
+
+template <typename T, int VEC>
 struct RingPersistent {
   const PtrTable& ring; int N; const PartGeom& geom; float* acc; float scale; Ctrl* ctrl;
   DevCtrl* mirror; unsigned n_blocks; unsigned long long timeout_ticks; unsigned flags;
@@ -951,6 +1080,19 @@ hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, con
   }
   if (vec) return with_policy(ring_allgather_cfg(seg.begin[n_live], 2), RingAllgather<bf16, 8>{ring, n_live, step, seg, stream});
   return with_policy(ring_allgather_cfg(seg.begin[n_live], 2), RingAllgather<bf16, 1>{ring, n_live, step, seg, stream});
+}
+
+hipError_t launch_ring_onepass(const PtrTable& ring, int n_live, const SegTable& seg,
+                               ftar_dtype_t dtype, bool vec, float scale, hipStream_t stream) {
+  // N reads and N writes per element: as many write streams as read streams
+  const size_t bytes = seg.begin[n_live] * (dtype == FTAR_F32 ? 4 : 2);
+  const LaunchCfg cfg = launch_cfg(1, bytes * n_live <= 192 * kMiB ? 1 : 3);
+  if (dtype == FTAR_F32) {
+    if (vec) return with_policy(cfg, RingOnepass<float, 4>{ring, n_live, seg, scale, stream});
+    return with_policy(cfg, RingOnepass<float, 1>{ring, n_live, seg, scale, stream});
+  }
+  if (vec) return with_policy(cfg, RingOnepass<bf16, 8>{ring, n_live, seg, scale, stream});
+  return with_policy(cfg, RingOnepass<bf16, 1>{ring, n_live, seg, scale, stream});
 }
 
 hipError_t launch_ring_persistent(const PtrTable& ring, int n_live, const PartGeom& geom,
