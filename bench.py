@@ -233,6 +233,19 @@ def all_configs_report(path, B, W, torch, np):
             for nb in (2, 4, 8, 16, 32, 64, 128):
                 med, mn = time_schedule(lambda: persistent(nb=nb), 1 if nb < 16 else 3)
                 curve.append((nb, gb / med))
+            # partitions of 4 Mi elements: acc (16 MiB) and the partition's slices stay in the caches
+            plan.set_partition(4 * W.M)
+            n_steps = plan.n_slots
+            med, mn = time_schedule(lambda: persistent(), 5)
+            st, done = ctrl.result()
+            add_row(w.name, "3a persistent kernel, partitions of 4 Mi elements (%d slots)" % n_steps, gb, med, mn,
+                    st == 0 and done == n_steps, float("nan"), "-")
+            plan.set_partition(0)
+            # the same result in one pass: its own algorithmic bytes are 2*N*E per element
+            own_gb = 2 * plan.n_live * E * w.count / 1e9
+            med, mn = time_schedule(lambda: B.ftar_allreduce_onepass(plan, bufs), 5)
+            add_row(w.name, "3a ftar_allreduce_onepass (own bytes: 2NE per element)", own_gb, med, mn, True,
+                    float("nan"), "-")
             ctrl.destroy()
             B.ftar_plan_destroy(plan)
         del bufs, acc

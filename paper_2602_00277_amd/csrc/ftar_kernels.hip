@@ -1084,9 +1084,9 @@ hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, con
 
 hipError_t launch_ring_onepass(const PtrTable& ring, int n_live, const SegTable& seg,
                                ftar_dtype_t dtype, bool vec, float scale, hipStream_t stream) {
-  // N reads and N writes per element: as many write streams as read streams
-  const size_t bytes = seg.begin[n_live] * (dtype == FTAR_F32 ? 4 : 2);
-  const LaunchCfg cfg = launch_cfg(1, bytes * n_live <= 192 * kMiB ? 1 : 3);
+  // N reads and N writes per element, as many write streams as read streams: non-temporal
+  // stores and one workgroup per CU are best at every size measured
+  const LaunchCfg cfg = launch_cfg(1, 3);
   if (dtype == FTAR_F32) {
     if (vec) return with_policy(cfg, RingOnepass<float, 4>{ring, n_live, seg, scale, stream});
     return with_policy(cfg, RingOnepass<float, 1>{ring, n_live, seg, scale, stream});
