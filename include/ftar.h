@@ -219,8 +219,8 @@ ftar_status_t ftar_allreduce_onepass(const ftar_plan_t* plan, void* const* bufs,
  * ctrl is a control block made by ftar_ctrl_create(): coherent host-pinned memory plus a mirror
  * of a few hundred bytes in device memory (both allocated at set-up, not on the hot path).  One control block serves one call at a time;
  * ftar_ring_persistent re-arms it (released = 0, no cancel) before launching.
- *   n_blocks    worker workgroups (= compute units used), 1..1024; 0 = one per compute unit;
- *               one more workgroup relays the CPU's gate word to the workers
+ *   n_blocks    worker workgroups (= compute units used), 1..1024; 0 = one per compute unit
+ *               (two with a partitioned plan); one more workgroup relays the CPU's gate word
  *   timeout_us  per-wait limit in microseconds (> 0)
  *   flags       FTAR_PERSIST_PUBLISH: a step counts as done (ftar_ctrl_progress) only after its
  *               data has been written back from the GPU's L2, as a NIC reading the buffers on
@@ -242,7 +242,9 @@ ftar_status_t ftar_ring_persistent(const ftar_plan_t* plan, void* const* bufs, f
  * thread while the kernel runs). */
 void ftar_ctrl_release(void* ctrl, int n_steps); /* steps [0, n_steps) may run */
 void ftar_ctrl_cancel(void* ctrl);               /* stop at the next wait */
-int ftar_ctrl_progress(const void* ctrl);        /* steps completed by EVERY workgroup so far */
+int ftar_ctrl_progress(const void* ctrl);        /* slots completed by EVERY workgroup: a lower bound
+                                                    while the kernel runs ahead of it, exact
+                                                    whenever the kernel waits for a release */
 ftar_status_t ftar_ctrl_result(const void* ctrl, int* steps_done);
 
 /* --------------------------------------------------------------------------- */

@@ -402,7 +402,9 @@ ftar_status_t ftar_ring_persistent(const ftar_plan_t* plan, void* const* bufs, f
     if (!acc || !aligned(acc, 4)) return fail(FTAR_ERR_INVALID_ARG);
     if (!aligned(acc, 16)) vec = false;
   }
-  unsigned blocks = n_blocks > 0 ? static_cast<unsigned>(n_blocks) : static_cast<unsigned>(device_cu_count());
+  // default: one worker per compute unit; two when the slots are short (partitioned)
+  unsigned blocks = n_blocks > 0 ? static_cast<unsigned>(n_blocks)
+                                 : static_cast<unsigned>(device_cu_count()) * (plan->n_parts > 1 ? 2u : 1u);
   if (blocks > static_cast<unsigned>(kMaxPersistentBlocks)) blocks = kMaxPersistentBlocks;
   // re-arm the control block; the launch below orders these stores before the kernel's loads
   c->gate = 0;

@@ -738,8 +738,8 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
       }
       released = static_cast<unsigned>(seen);
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // see this block's stores of the slot before
     const int step = static_cast<int>(ustep);
+    if (step == N - 1) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // first AllGather step: see the block's stores
     const int sel = part + 1 == geom.n_parts ? 1 : 0;
     const unsigned long long* seg = s_seg[sel];
     const unsigned long long* til = s_tile[sel];
@@ -754,14 +754,23 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
       constexpr int CV = VEC == 1 ? 1 : 16 / static_cast<int>(sizeof(T));
       ring_allgather_pass<T, CV, U * VEC / CV, POL>(s_tab, seg, til, N, step - (N - 1), blockIdx.x, n_workers, off);
     }
-    // Report the slot: every lane's stores have left the CU (workgroup release + barrier), then
-    // lane 0 writes this worker's progress word.  With FTAR_PERSIST_PUBLISH that store is a
-    // release at agent scope: the slot's data is written back from this XCD's L2 before the
-    // progress can be seen, which is what a NIC reading the buffers on the CPU's signal would
-    // need (one L2 write-back per block and slot: 18 % at 64 Mi elements).
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();  // also: every lane has read s_gate before lane 0 writes it again
-    if (tid == 0) {
+    // A block-wide barrier with workgroup release/acquire is needed (a) before the first
+    // AllGather step, whose 16-byte lanes read what other lanes of the block wrote in the last
+    // ReduceScatter step, and (b) whenever the slot is reported or the next slot needs a wait
+    // (lane 0 then rewrites s_gate).  Between two ReduceScatter steps, or two AllGather steps,
+    // every lane only re-reads its own stores, so slots that are already released run back to
+    // back.  Reporting is skipped while the next slot is already released: the progress the CPU
+    // sees is then a lower bound, exact whenever the kernel waits.
+    const bool report = slot + 1 >= released || slot + 1 == n_slots || (flags & FTAR_PERSIST_ALIGN) != 0;
+    if (report || step == N - 2) {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      __syncthreads();
+    }
+    // With FTAR_PERSIST_PUBLISH the progress store is a release at agent scope: the data of the
+    // slots reported is written back from this XCD's L2 before the progress can be seen, which
+    // is what a NIC reading the buffers on the CPU's signal would need (one L2 write-back per
+    // block and report: 18 % at 64 Mi elements when every slot is reported).
+    if (report && tid == 0) {
       if (flags & FTAR_PERSIST_PUBLISH)
         __hip_atomic_store(&mirror->worker_slot[blockIdx.x], slot + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
       else
