@@ -107,6 +107,27 @@ ftar_status_t ftar_plan_segment(const ftar_plan_t* plan, int k, size_t* begin, s
                                 int* owner_replica);
 
 /* ---------------------------------------------------------------------------
+ * Zero-gradient participants.
+ * Paper: section 4.3, "Non-blocking Catch Up" - a replica that has fallen behind fetches a
+ * checkpoint while the others train, takes part in the gradient exchange at the end of the step
+ * and sends a ZERO gradient; the exchange brings all replicas to the same state.
+ * Replicas in zero_mask (a subset of live_mask) are participants: they count among the N ring
+ * members, and in the ring calls their buffers RECEIVE the result; but they contribute +0.0 and
+ * their buffers are never read (N_zero * E bytes per element are not moved).  The result is
+ * bit-identical to running with buffers that hold +0.0 everywhere.
+ * The divisor is N (a catching-up replica is a participant); with contributors_only != 0 it is
+ * N - N_zero.  FTAR_ERR_BAD_MASK if zero_mask has a bit outside live_mask; FTAR_ERR_NO_LIVE if
+ * contributors_only leaves nobody.
+ * ftar_plan_set_zero_mask applies to every ring call made with the plan afterwards (step calls,
+ * one-pass, persistent); ftar_reduce_masked_zero is the one-shot form, where a zero
+ * participant's entry in bufs may be NULL.
+ */
+ftar_status_t ftar_plan_set_zero_mask(ftar_plan_t* plan, uint64_t zero_mask, int contributors_only);
+ftar_status_t ftar_reduce_masked_zero(const void* const* bufs, int n_replicas, uint64_t live_mask,
+                                      uint64_t zero_mask, int contributors_only, size_t count,
+                                      ftar_dtype_t dtype, void* out, void* stream);
+
+/* ---------------------------------------------------------------------------
  * ftar_plan_set_partition - split the data into partitions for ftar_ring_persistent.
  * Paper: section 4.2 - the send and receive buffers are a fixed S x C bytes; the message is split
  * into partitions of at most S x C x N bytes; each partition runs one whole round of the ring
@@ -220,7 +241,9 @@ ftar_status_t ftar_allreduce_onepass(const ftar_plan_t* plan, void* const* bufs,
  * of a few hundred bytes in device memory (both allocated at set-up, not on the hot path).  One control block serves one call at a time;
  * ftar_ring_persistent re-arms it (released = 0, no cancel) before launching.
  *   n_blocks    worker workgroups (= compute units used), 1..1024; 0 = one per compute unit
- *               (two with a partitioned plan); one more workgroup relays the CPU's gate word
+ *               (two with a partitioned plan); one more workgroup relays the CPU's gate word;
+ *               clamped to what the GPU can keep resident at once (a waiting workgroup keeps
+ *               its place, so all of them must fit)
  *   timeout_us  per-wait limit in microseconds (> 0)
  *   flags       FTAR_PERSIST_PUBLISH: a step counts as done (ftar_ctrl_progress) only after its
  *               data has been written back from the GPU's L2, as a NIC reading the buffers on

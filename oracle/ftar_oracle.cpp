@@ -188,6 +188,66 @@ int oracle_reduce_masked(const void* const* bufs, int n, uint64_t mask, size_t c
     return N;
 }
 
+// Zero-gradient participants (section 4.3, "Non-blocking Catch Up": a replica that is catching
+// up takes part in the exchange and sends a zero gradient).  Replicas in zero_mask (a subset of
+// live_mask) take part - they count among the N participants and, in a ring, receive the result -
+// but contribute +0.0 and their buffers are never read.  The divisor is the number of
+// participants, or with contributors_only the number of replicas that really contribute.
+// By definition this is oracle_reduce_masked over buffers in which the zero participants hold
+// +0.0 everywhere (tests pin exactly that), with the other divisor if asked.
+int oracle_reduce_masked_zero(const void* const* bufs, int n, uint64_t live_mask, uint64_t zero_mask,
+                              int contributors_only, size_t count, int dtype, void* out) {
+  int ring[64];
+  int N = live_ring(n, live_mask, ring);
+  if (N < 0) return N;
+  if ((zero_mask & ~live_mask) != 0) return -3;
+  int Z = 0;
+  for (int j = 0; j < N; ++j) Z += (zero_mask >> ring[j]) & 1u;
+  const int divisor = contributors_only ? N - Z : N;
+  if (divisor <= 0) return -2;
+  const float scale = 1.0f / static_cast<float>(divisor);
+  for (size_t i = 0; i < count; ++i) {
+    float a = ((zero_mask >> ring[0]) & 1u) ? 0.0f : load_f32(bufs[ring[0]], i, dtype);
+    for (int j = 1; j < N; ++j)
+      a = a + (((zero_mask >> ring[j]) & 1u) ? 0.0f : load_f32(bufs[ring[j]], i, dtype));
+    a = a * scale;
+    store_cvt(out, i, dtype, a);
+  }
+  return N;
+}
+
+// Ring all-reduce with zero-gradient participants, closed form for the element range
+// [begin, begin+len): as oracle_ring_closed_form with +0.0 in place of the zero participants'
+// values.  Every participant, the zero ones included, ends with this value.
+int oracle_ring_closed_form_zero(const void* const* bufs, int n, uint64_t live_mask, uint64_t zero_mask,
+                                 int contributors_only, size_t count, size_t chunk_elems, int dtype,
+                                 size_t begin, size_t len, void* out) {
+  int ring[64];
+  int N = live_ring(n, live_mask, ring);
+  if (N < 0) return N;
+  if ((zero_mask & ~live_mask) != 0) return -3;
+  if (count == 0 || chunk_elems == 0 || begin > count || len > count - begin) return -1;
+  int Z = 0;
+  for (int j = 0; j < N; ++j) Z += (zero_mask >> ring[j]) & 1u;
+  const int divisor = contributors_only ? N - Z : N;
+  if (divisor <= 0) return -2;
+  const float scale = 1.0f / static_cast<float>(divisor);
+  std::vector<size_t> sb(N + 1);
+  segment_bounds(N, count, chunk_elems, sb.data());
+  for (size_t j = 0; j < len; ++j) {
+    int k = segment_of(sb.data(), N, begin + j);
+    int r0 = ring[k];
+    float a = ((zero_mask >> r0) & 1u) ? 0.0f : load_f32(bufs[r0], j, dtype);
+    for (int m = 1; m < N; ++m) {
+      int r = ring[(k + m) % N];
+      a = a + (((zero_mask >> r) & 1u) ? 0.0f : load_f32(bufs[r], j, dtype));
+    }
+    if (N > 1) a = a * scale;
+    store_cvt(out, j, dtype, a);
+  }
+  return N;
+}
+
 // The same sum carried in binary64 with a binary64 1/N: the "exact" value
 // the error bounds are stated against.  out: count doubles.
 int oracle_reduce_f64(const void* const* bufs, int n, uint64_t mask, size_t count,

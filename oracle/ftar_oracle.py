@@ -56,6 +56,10 @@ def lib():
         L.oracle_geometry.argtypes = [ci, u64, sz, sz, vp]
         L.oracle_reduce_masked.restype = ci
         L.oracle_reduce_masked.argtypes = [vp, ci, u64, sz, ci, ci, vp]
+        L.oracle_reduce_masked_zero.restype = ci
+        L.oracle_reduce_masked_zero.argtypes = [vp, ci, u64, u64, ci, sz, ci, vp]
+        L.oracle_ring_closed_form_zero.restype = ci
+        L.oracle_ring_closed_form_zero.argtypes = [vp, ci, u64, u64, ci, sz, sz, ci, sz, sz, vp]
         L.oracle_reduce_f64.restype = ci
         L.oracle_reduce_f64.argtypes = [vp, ci, u64, sz, ci, ci, vp, vp]
         L.oracle_ring_per_rank.restype = ci
@@ -137,6 +141,30 @@ def reduce_masked(bufs, mask, dtype, sum_only=False, count=None):
     out = np.empty(count, dtype=_np_dtype(dtype))
     tab = _ptr_table(bufs, dtype, mask)
     _check(lib().oracle_reduce_masked(tab, n, mask, count, dtype, int(sum_only), out.ctypes.data))
+    return out
+
+
+def reduce_masked_zero(bufs, live_mask, zero_mask, dtype, contributors_only=False):
+    """Zero participants' buffers are never read and may be None."""
+    n = len(bufs)
+    count = [b for r, b in enumerate(bufs) if b is not None and not (zero_mask >> r) & 1][0].size \
+        if any(b is not None and not (zero_mask >> r) & 1 for r, b in enumerate(bufs)) \
+        else [b for b in bufs if b is not None][0].size
+    out = np.empty(count, dtype=_np_dtype(dtype))
+    tab = _ptr_table(bufs, dtype, live_mask & ~zero_mask)
+    _check(lib().oracle_reduce_masked_zero(tab, n, live_mask, zero_mask, int(contributors_only), count,
+                                           dtype, out.ctypes.data))
+    return out
+
+
+def ring_closed_form_zero(bufs, live_mask, zero_mask, count, chunk_elems, dtype, contributors_only=False,
+                          begin=0, length=None):
+    n = len(bufs)
+    length = [b for b in bufs if b is not None][0].size if length is None else length
+    out = np.empty(length, dtype=_np_dtype(dtype))
+    tab = _ptr_table(bufs, dtype, live_mask & ~zero_mask)
+    _check(lib().oracle_ring_closed_form_zero(tab, n, live_mask, zero_mask, int(contributors_only), count,
+                                              chunk_elems, dtype, begin, length, out.ctypes.data))
     return out
 
 

@@ -40,7 +40,8 @@ EXPORTS = [
     "ftar_ctrl_create", "ftar_ctrl_destroy", "ftar_ring_persistent", "ftar_ctrl_release",
     "ftar_ctrl_cancel", "ftar_ctrl_progress", "ftar_ctrl_result",
     "ftar_plan_set_partition", "ftar_plan_n_partitions", "ftar_plan_n_slots",
-    "ftar_plan_partition_segment", "ftar_allreduce_onepass",
+    "ftar_plan_partition_segment", "ftar_allreduce_onepass", "ftar_plan_set_zero_mask",
+    "ftar_reduce_masked_zero",
 ]
 
 _lib = None
@@ -107,6 +108,10 @@ def lib():
     L.ftar_plan_partition_segment.restype = ci
     L.ftar_plan_partition_segment.argtypes = [vp, ci, ci, ctypes.POINTER(sz), ctypes.POINTER(sz),
                                               ctypes.POINTER(ci)]
+    L.ftar_plan_set_zero_mask.restype = ci
+    L.ftar_plan_set_zero_mask.argtypes = [vp, u64, ci]
+    L.ftar_reduce_masked_zero.restype = ci
+    L.ftar_reduce_masked_zero.argtypes = [vp, ci, u64, u64, ci, sz, ci, vp, vp]
     L.ftar_allreduce_onepass.restype = ci
     L.ftar_allreduce_onepass.argtypes = [vp, vp, vp]
     L.ftar_ctrl_create.restype = vp
@@ -287,6 +292,25 @@ def ftar_reduce_masked(bufs: Sequence[Optional[torch.Tensor]], live_mask: int, o
     if st != FTAR_OK:
         raise FtarError(st, "ftar_reduce_masked")
     return out
+
+
+def ftar_reduce_masked_zero(bufs: Sequence[Optional[torch.Tensor]], live_mask: int, zero_mask: int,
+                            out: torch.Tensor, contributors_only: bool = False,
+                            count: Optional[int] = None, stream=None) -> torch.Tensor:
+    count = out.numel() if count is None else count
+    _check_bufs(list(bufs) + [out], (live_mask & ~zero_mask) | (1 << len(bufs)), count, out.dtype)
+    st = lib().ftar_reduce_masked_zero(_ptr_array(bufs), len(bufs), live_mask, zero_mask,
+                                       int(contributors_only), count, dtype_code(out.dtype),
+                                       out.data_ptr(), _stream_handle(stream))
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_reduce_masked_zero")
+    return out
+
+
+def ftar_plan_set_zero_mask(plan: "Plan", zero_mask: int, contributors_only: bool = False) -> None:
+    st = lib().ftar_plan_set_zero_mask(plan.handle, zero_mask, int(contributors_only))
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_plan_set_zero_mask")
 
 
 def ftar_reduce_masked_bucketed(bufs: Sequence[Optional[torch.Tensor]], masks: Sequence[int],

@@ -98,6 +98,7 @@ struct ftar_plan_s {
   ftar_dtype_t dtype;
   SegTable seg;            // portion boundaries, n_live+1 entries (of the whole buffer)
   // partitioned ring (persistent kernel only); part_elems == 0: one partition = the whole buffer
+  unsigned long long zero_pos;  // bit p: ring position p is a zero-gradient participant
   size_t part_elems;
   size_t n_parts;
   SegTable part_seg_full;  // portions of a full partition, relative to its first element
@@ -155,6 +156,24 @@ static bool plan_ok(const ftar_plan_t* p) { return p && p->magic == kPlanMagic; 
 ftar_status_t ftar_plan_set_dtype(ftar_plan_t* plan, ftar_dtype_t dtype) {
   if (!plan_ok(plan) || (dtype != FTAR_F32 && dtype != FTAR_BF16)) return fail(FTAR_ERR_INVALID_ARG);
   plan->dtype = dtype;
+  return FTAR_OK;
+}
+
+ftar_status_t ftar_plan_set_zero_mask(ftar_plan_t* plan, uint64_t zero_mask, int contributors_only) {
+  if (!plan_ok(plan)) return fail(FTAR_ERR_INVALID_ARG);
+  if ((zero_mask & ~plan->live_mask) != 0) return fail(FTAR_ERR_BAD_MASK);
+  unsigned long long zpos = 0;
+  int Z = 0;
+  for (int p = 0; p < plan->n_live; ++p) {
+    if ((zero_mask >> plan->ring[p]) & 1ull) {
+      zpos |= 1ull << p;
+      ++Z;
+    }
+  }
+  const int divisor = contributors_only ? plan->n_live - Z : plan->n_live;
+  if (divisor <= 0) return fail(FTAR_ERR_NO_LIVE);
+  plan->zero_pos = zpos;
+  plan->scale = 1.0f / static_cast<float>(divisor);
   return FTAR_OK;
 }
 
@@ -258,7 +277,7 @@ ftar_status_t ftar_reduce_step(const ftar_plan_t* plan, int step, void* const* b
     if (!aligned(acc, 16)) vec = false;
   }
   hipError_t e = launch_ring_reduce(mode, tab, N, step, plan->seg, plan->dtype, vec, acc, plan->scale,
-                                    static_cast<hipStream_t>(stream));
+                                    plan->zero_pos, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
 }
 
@@ -277,28 +296,47 @@ ftar_status_t ftar_allgather_step(const ftar_plan_t* plan, int step, void* const
   return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
 }
 
-ftar_status_t ftar_reduce_masked(const void* const* bufs, int n_replicas, uint64_t live_mask,
-                                 size_t count, ftar_dtype_t dtype, void* out, void* stream) {
+static ftar_status_t reduce_masked_common(const void* const* bufs, int n_replicas, uint64_t live_mask,
+                                          uint64_t zero_mask, int contributors_only, size_t count,
+                                          ftar_dtype_t dtype, void* out, void* stream) {
   if (!bufs || !out || count == 0 || (dtype != FTAR_F32 && dtype != FTAR_BF16))
     return fail(FTAR_ERR_INVALID_ARG);
   int ring[kMaxReplicas];
   int N = 0;
   ftar_status_t s = resolve_mask(n_replicas, live_mask, ring, &N);
   if (s != FTAR_OK) return fail(s);
+  if ((zero_mask & ~live_mask) != 0) return fail(FTAR_ERR_BAD_MASK);
   const size_t es = elem_size(dtype);
   if (!aligned(out, es)) return fail(FTAR_ERR_INVALID_ARG);
   bool vec = aligned(out, 16);
   PtrTable tab;
   std::memset(&tab, 0, sizeof(tab));
+  int n_src = 0;
   for (int j = 0; j < N; ++j) {
+    if ((zero_mask >> ring[j]) & 1ull) continue;  // takes part, contributes +0.0, is never read
     const void* b = bufs[ring[j]];
     if (!b || !aligned(b, es)) return fail(FTAR_ERR_INVALID_ARG);
     if (!aligned(b, 16)) vec = false;
-    tab.p[j] = const_cast<void*>(b);
+    tab.p[n_src++] = const_cast<void*>(b);
   }
-  hipError_t e = launch_reduce_masked(tab, N, count, dtype, vec, out, 1.0f / static_cast<float>(N),
+  const int divisor = contributors_only ? n_src : N;
+  if (divisor <= 0) return fail(FTAR_ERR_NO_LIVE);
+  hipError_t e = launch_reduce_masked(tab, n_src, count, dtype, vec, out,
+                                      1.0f / static_cast<float>(divisor), n_src != N,
                                       static_cast<hipStream_t>(stream));
   return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
+}
+
+ftar_status_t ftar_reduce_masked(const void* const* bufs, int n_replicas, uint64_t live_mask,
+                                 size_t count, ftar_dtype_t dtype, void* out, void* stream) {
+  return reduce_masked_common(bufs, n_replicas, live_mask, 0, 0, count, dtype, out, stream);
+}
+
+ftar_status_t ftar_reduce_masked_zero(const void* const* bufs, int n_replicas, uint64_t live_mask,
+                                      uint64_t zero_mask, int contributors_only, size_t count,
+                                      ftar_dtype_t dtype, void* out, void* stream) {
+  return reduce_masked_common(bufs, n_replicas, live_mask, zero_mask, contributors_only, count, dtype,
+                              out, stream);
 }
 
 ftar_status_t ftar_reduce_masked_bucketed(const void* const* bufs, int n_replicas,
@@ -357,7 +395,7 @@ ftar_status_t ftar_allreduce_onepass(const ftar_plan_t* plan, void* const* bufs,
   ftar_status_t s = ring_table(plan, bufs, &tab, &vec);
   if (s != FTAR_OK) return fail(s);
   if (N < 2) return FTAR_OK;  // a ring of one exchanges nothing: the buffer stays as it is
-  hipError_t e = launch_ring_onepass(tab, N, plan->seg, plan->dtype, vec, plan->scale,
+  hipError_t e = launch_ring_onepass(tab, N, plan->seg, plan->dtype, vec, plan->scale, plan->zero_pos,
                                      static_cast<hipStream_t>(stream));
   return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
 }
@@ -425,7 +463,7 @@ ftar_status_t ftar_ring_persistent(const ftar_plan_t* plan, void* const* bufs, f
   hipError_t e = launch_ring_persistent(tab, N, geom, plan->dtype, vec, acc, plan->scale,
                                         static_cast<Ctrl*>(dev), c->dev, blocks,
                                         static_cast<unsigned long long>(timeout_us) * 100ull, flags,
-                                        static_cast<hipStream_t>(stream));
+                                        plan->zero_pos, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
 }
 

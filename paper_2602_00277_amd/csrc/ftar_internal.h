@@ -80,8 +80,13 @@ int device_cu_count();  // of the current device; cached
 
 // All launchers enqueue on `stream` and return hipGetLastError().
 // `vec` selects the 128-bit vector kernels (caller has checked alignment).
-hipError_t launch_reduce_masked(const PtrTable& live, int n_live, size_t count, ftar_dtype_t dtype,
-                                bool vec, void* out, float scale, hipStream_t stream);
+// zero_pos / zpos below: bit p set = the p-th live replica (ring position p) is a zero-gradient
+// participant: it contributes +0.0 and its buffer is never read.
+// live: the n_src buffers that are read, in summation order (zero-gradient participants already
+// left out: zero_participants says whether there were any; n_src may then be 0).
+hipError_t launch_reduce_masked(const PtrTable& live, int n_src, size_t count, ftar_dtype_t dtype,
+                                bool vec, void* out, float scale, bool zero_participants,
+                                hipStream_t stream);
 
 hipError_t launch_reduce_bucketed(const PtrTable& all, int n_replicas, const BucketTable& masks,
                                   int n_buckets, size_t first_elem, size_t bucket_elems,
@@ -91,7 +96,7 @@ hipError_t launch_reduce_bucketed(const PtrTable& all, int n_replicas, const Buc
 // ring: table of the N live buffers in ring order
 hipError_t launch_ring_reduce(RingMode mode, const PtrTable& ring, int n_live, int step,
                               const SegTable& seg, ftar_dtype_t dtype, bool vec, float* acc,
-                              float scale, hipStream_t stream);
+                              float scale, unsigned long long zpos, hipStream_t stream);
 
 hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, const SegTable& seg,
                                  ftar_dtype_t dtype, bool vec, hipStream_t stream);
@@ -99,7 +104,8 @@ hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, con
 // The whole ring in one kernel, gated by the control block (ctrl_dev = device view of it).
 // What the whole ring schedule leaves in the buffers, in one pass (N reads, N writes per element).
 hipError_t launch_ring_onepass(const PtrTable& ring, int n_live, const SegTable& seg,
-                               ftar_dtype_t dtype, bool vec, float scale, hipStream_t stream);
+                               ftar_dtype_t dtype, bool vec, float scale, unsigned long long zpos,
+                               hipStream_t stream);
 
 // Geometry of a partitioned ring: n_parts partitions of part_elems elements (the last one may be
 // shorter); portion boundaries are relative to the partition's first element.
@@ -114,7 +120,7 @@ struct PartGeom {
 hipError_t launch_ring_persistent(const PtrTable& ring, int n_live, const PartGeom& geom,
                                   ftar_dtype_t dtype, bool vec, float* acc, float scale, Ctrl* ctrl_dev,
                                   DevCtrl* mirror, unsigned n_blocks, unsigned long long timeout_ticks,
-                                  unsigned flags, hipStream_t stream);
+                                  unsigned flags, unsigned long long zpos, hipStream_t stream);
 
 }  // namespace ftar
 

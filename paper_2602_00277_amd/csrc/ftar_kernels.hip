@@ -124,9 +124,18 @@ __device__ __forceinline__ P* uniform_ptr(P* p) {
 // Every load of the tile is issued before the first use.  `out` may alias
 // src[NSRC-1] (the in-place last ReduceScatter step): a lane only ever writes
 // the elements it has itself already loaded.
-template <typename T, int VEC, int NSRC, bool ACC_IN, bool ACC_OUT, int U, int POL>
+// zm: bit j set = source j is a zero-gradient participant: it contributes +0.0 and its buffer is
+// not read (the pointer may be anything).  The bits are the same for the whole wave.
+// ZM = false compiles the loads without the tests (zm is then ignored): callers pick it when zm == 0.
+// ZT = true adds `zterm` to the finished sum before it is scaled: +0.0 when zero-gradient
+// participants were left out of src altogether, -0.0 (the identity of IEEE addition) otherwise.
+// x_1 + ... + x_n with +0.0 terms anywhere in between equals (x_1 + ... + x_n) + 0.0 bit for bit:
+// a +0.0 term only ever changes a running sum of -0.0, and that happens iff every x_i is -0.0.
+template <typename T, int VEC, int NSRC, bool ACC_IN, bool ACC_OUT, int U, int POL, bool ZM = false,
+          bool ZT = false>
 __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc_in, float* acc_out,
-                                         T* out, float scale, size_t v) {
+                                         T* out, float scale, size_t v, unsigned long long zm = 0,
+                                         float zterm = 0.0f) {
   static_assert(!(ACC_IN || ACC_OUT) || VEC <= 4, "fp32 partials are moved 4 at a time");
   typedef typename Raw<T, VEC>::type R;
   typedef typename Raw<float, (VEC == 1 ? 1 : 4)>::type A;
@@ -135,8 +144,10 @@ __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc
 #pragma unroll
   for (int u = 0; u < U; ++u) {
 #pragma unroll
-    for (int j = 0; j < NSRC; ++j)
-      raw[u][j] = ld<POL>(reinterpret_cast<const R*>(src[j]) + v + u * kThreads);
+    for (int j = 0; j < NSRC; ++j) {
+      if (ZM && ((zm >> j) & 1ull)) raw[u][j] = R{};  // all-zero bits are +0.0 in both element types
+      else raw[u][j] = ld<POL>(reinterpret_cast<const R*>(src[j]) + v + u * kThreads);
+    }
   }
   if constexpr (ACC_IN) {
 #pragma unroll
@@ -156,6 +167,10 @@ __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc
     if constexpr (ACC_OUT) {
       st<POL>(reinterpret_cast<A*>(acc_out) + v + u * kThreads, narrow<A, VEC>(a));
     } else {
+      if constexpr (ZT) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) a[e] = a[e] + zterm;
+      }
 #pragma unroll
       for (int e = 0; e < VEC; ++e) a[e] = a[e] * scale;
       st<POL>(reinterpret_cast<R*>(out) + v + u * kThreads, narrow<R, VEC>(a));
@@ -166,24 +181,33 @@ __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc
 // Persistent loop of block bx of gx over the `len` elements that start at the
 // given pointers: full tiles grid-strided, then one block finishes the whole
 // vectors past the last full tile and the last len % VEC single elements.
-template <typename T, int VEC, int NSRC, bool ACC_IN, bool ACC_OUT, int U, int POL>
-__device__ __forceinline__ void sum_range(T* const (&src)[NSRC], const float* acc_in, float* acc_out,
-                                          T* out, float scale, size_t len, unsigned bx,
-                                          unsigned gx) {
+template <typename T, int VEC, int NSRC, bool ACC_IN, bool ACC_OUT, int U, int POL, bool ZM,
+          bool ZT = false>
+__device__ __forceinline__ void sum_range_z(T* const (&src)[NSRC], const float* acc_in, float* acc_out,
+                                            T* out, float scale, size_t len, unsigned bx,
+                                            unsigned gx, unsigned long long zm, float zterm = 0.0f) {
   const unsigned tid = threadIdx.x;
   const size_t n_vec = len / VEC;
   constexpr size_t kTile = static_cast<size_t>(kThreads) * U;
   const size_t n_tiles = n_vec / kTile;
   for (size_t t = bx; t < n_tiles; t += gx)
-    sum_tile<T, VEC, NSRC, ACC_IN, ACC_OUT, U, POL>(src, acc_in, acc_out, out, scale, t * kTile + tid);
+    sum_tile<T, VEC, NSRC, ACC_IN, ACC_OUT, U, POL, ZM, ZT>(src, acc_in, acc_out, out, scale, t * kTile + tid, zm, zterm);
   if (bx == n_tiles % gx) {
     for (size_t v = n_tiles * kTile + tid; v < n_vec; v += kThreads)
-      sum_tile<T, VEC, NSRC, ACC_IN, ACC_OUT, 1, POL>(src, acc_in, acc_out, out, scale, v);
+      sum_tile<T, VEC, NSRC, ACC_IN, ACC_OUT, 1, POL, ZM, ZT>(src, acc_in, acc_out, out, scale, v, zm, zterm);
     if constexpr (VEC > 1) {
       const size_t e = n_vec * VEC + tid;
-      if (e < len) sum_tile<T, 1, NSRC, ACC_IN, ACC_OUT, 1, POL>(src, acc_in, acc_out, out, scale, e);
+      if (e < len) sum_tile<T, 1, NSRC, ACC_IN, ACC_OUT, 1, POL, ZM, ZT>(src, acc_in, acc_out, out, scale, e, zm, zterm);
     }
   }
+}
+
+template <typename T, int VEC, int NSRC, bool ACC_IN, bool ACC_OUT, int U, int POL>
+__device__ __forceinline__ void sum_range(T* const (&src)[NSRC], const float* acc_in, float* acc_out,
+                                          T* out, float scale, size_t len, unsigned bx,
+                                          unsigned gx, unsigned long long zm = 0) {
+  if (zm == 0) sum_range_z<T, VEC, NSRC, ACC_IN, ACC_OUT, U, POL, false>(src, acc_in, acc_out, out, scale, len, bx, gx, 0);
+  else sum_range_z<T, VEC, NSRC, ACC_IN, ACC_OUT, U, POL, true>(src, acc_in, acc_out, out, scale, len, bx, gx, zm);
 }
 
 // Vectors per lane per tile for an N-source sum.  Two choices per N are compiled: "wide"
@@ -198,15 +222,14 @@ __host__ __device__ constexpr int unroll_narrow(int n_src) {
 // ---- any number of sources (runtime N): loads in groups of 8 ---------------
 template <typename T, int VEC, int POL>
 __device__ __forceinline__ void sum_any_one(T* const* s_tab, size_t base, int N, T* out, float scale,
-                                            size_t v) {
+                                            size_t v, float zterm) {
   typedef typename Raw<T, VEC>::type R;
   float a[VEC];
   for (int j0 = 0; j0 < N; j0 += 8) {
     R raw[8];
 #pragma unroll
     for (int jj = 0; jj < 8; ++jj)
-      if (j0 + jj < N)
-        raw[jj] = ld<POL>(reinterpret_cast<const R*>(uniform_ptr(s_tab[j0 + jj]) + base) + v);
+      if (j0 + jj < N) raw[jj] = ld<POL>(reinterpret_cast<const R*>(uniform_ptr(s_tab[j0 + jj]) + base) + v);
 #pragma unroll
     for (int jj = 0; jj < 8; ++jj) {
       if (j0 + jj < N) {
@@ -223,21 +246,21 @@ __device__ __forceinline__ void sum_any_one(T* const* s_tab, size_t base, int N,
     }
   }
 #pragma unroll
-  for (int e = 0; e < VEC; ++e) a[e] = a[e] * scale;
+  for (int e = 0; e < VEC; ++e) a[e] = (a[e] + zterm) * scale;
   st<POL>(reinterpret_cast<R*>(out) + v, narrow<R, VEC>(a));
 }
 
 template <typename T, int VEC, int POL>
 __device__ __forceinline__ void sum_any_range(T* const* s_tab, size_t base, int N, T* out, float scale,
-                                              size_t len, unsigned bx, unsigned gx) {
+                                              size_t len, unsigned bx, unsigned gx, float zterm) {
   const size_t n_vec = len / VEC;
   for (size_t v = static_cast<size_t>(bx) * kThreads + threadIdx.x; v < n_vec;
        v += static_cast<size_t>(gx) * kThreads)
-    sum_any_one<T, VEC, POL>(s_tab, base, N, out, scale, v);
+    sum_any_one<T, VEC, POL>(s_tab, base, N, out, scale, v, zterm);
   if constexpr (VEC > 1) {
     if (bx == 0) {
       const size_t e = n_vec * VEC + threadIdx.x;
-      if (e < len) sum_any_one<T, 1, POL>(s_tab, base, N, out, scale, e);
+      if (e < len) sum_any_one<T, 1, POL>(s_tab, base, N, out, scale, e, zterm);
     }
   }
 }
@@ -247,25 +270,37 @@ __device__ __forceinline__ void sum_any_range(T* const* s_tab, size_t base, int 
 // One-shot masked mean over N live buffers (N fixed at compile time, 1..16).
 template <typename T, int VEC, int N, int U, int POL>
 __global__ void __launch_bounds__(kThreads)
-k_reduce_masked(PtrTable live, T* out, float scale, size_t count) {
+k_reduce_masked(PtrTable live, T* out, float scale, size_t count, float zterm) {
   __shared__ T* s_tab[kMaxReplicas];
   if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<T*>(live.p[threadIdx.x]);
   __syncthreads();
   T* src[N];
 #pragma unroll
   for (int j = 0; j < N; ++j) src[j] = uniform_ptr(s_tab[j]);
-  sum_range<T, VEC, N, false, false, U, POL>(src, nullptr, nullptr, out, scale, count, blockIdx.x,
-                                             gridDim.x);
+  sum_range_z<T, VEC, N, false, false, U, POL, false, true>(src, nullptr, nullptr, out, scale, count,
+                                                            blockIdx.x, gridDim.x, 0, zterm);
 }
 
 // One-shot masked mean, any N up to 64 (also the element-wise path for unaligned buffers).
 template <typename T, int VEC, int POL>
 __global__ void __launch_bounds__(kThreads)
-k_reduce_masked_any(PtrTable live, int N, T* out, float scale, size_t count) {
+k_reduce_masked_any(PtrTable live, int N, T* out, float scale, size_t count, float zterm) {
   __shared__ T* s_tab[kMaxReplicas];
   if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<T*>(live.p[threadIdx.x]);
   __syncthreads();
-  sum_any_range<T, VEC, POL>(s_tab, 0, N, out, scale, count, blockIdx.x, gridDim.x);
+  sum_any_range<T, VEC, POL>(s_tab, 0, N, out, scale, count, blockIdx.x, gridDim.x, zterm);
+}
+
+// Every participant is a zero-gradient one: the mean is +0.0 (all-zero bits in both element types).
+__global__ void __launch_bounds__(kThreads)
+k_fill_zero(uint16_t* head16, uint32_t* out32, size_t n32, uint16_t* tail16) {
+  for (size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x; i < n32;
+       i += static_cast<size_t>(gridDim.x) * kThreads)
+    out32[i] = 0u;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (head16 != nullptr) *head16 = 0;
+    if (tail16 != nullptr) *tail16 = 0;
+  }
 }
 
 __device__ __forceinline__ unsigned long long uniform_u64(unsigned long long x) {
@@ -280,11 +315,14 @@ __device__ __forceinline__ unsigned long long uniform_u64(unsigned long long x) 
 // wave-uniform 64-bit unsigned compare here, reading a stale SCC.)
 template <typename T, int VEC, int NSRC, bool ACC_IN, bool ACC_OUT, int U, int POL>
 __device__ __forceinline__ void sum_block_tile(T* const (&src)[NSRC], const float* acc_in,
-                                               float* acc_out, T* out, float scale, size_t rem) {
-  if (rem >= static_cast<size_t>(kThreads) * U * VEC)
-    sum_tile<T, VEC, NSRC, ACC_IN, ACC_OUT, U, POL>(src, acc_in, acc_out, out, scale, threadIdx.x);
-  else
-    sum_range<T, VEC, NSRC, ACC_IN, ACC_OUT, 1, POL>(src, acc_in, acc_out, out, scale, rem, 0u, 1u);
+                                               float* acc_out, T* out, float scale, size_t rem,
+                                               unsigned long long zm = 0) {
+  if (rem >= static_cast<size_t>(kThreads) * U * VEC) {
+    if (zm == 0) sum_tile<T, VEC, NSRC, ACC_IN, ACC_OUT, U, POL, false>(src, acc_in, acc_out, out, scale, threadIdx.x, 0);
+    else sum_tile<T, VEC, NSRC, ACC_IN, ACC_OUT, U, POL, true>(src, acc_in, acc_out, out, scale, threadIdx.x, zm);
+  } else {
+    sum_range<T, VEC, NSRC, ACC_IN, ACC_OUT, 1, POL>(src, acc_in, acc_out, out, scale, rem, 0u, 1u, zm);
+  }
 }
 
 // The kernels below walk the whole element range as ONE sequence of tiles, grid-strided, and
@@ -355,8 +393,8 @@ k_reduce_bucketed(PtrTable all, int n_replicas, BucketTable masks, ScaleTable sc
       }
     }
     if (!done) {
-      if (rem >= kTileElems) sum_any_range<T, VEC, POL>(s_tab, begin, N, out + begin, scale, kTileElems, 0u, 1u);
-      else sum_any_range<T, VEC, POL>(s_tab, begin, N, out + begin, scale, rem, 0u, 1u);
+      if (rem >= kTileElems) sum_any_range<T, VEC, POL>(s_tab, begin, N, out + begin, scale, kTileElems, 0u, 1u, -0.0f);
+      else sum_any_range<T, VEC, POL>(s_tab, begin, N, out + begin, scale, rem, 0u, 1u, -0.0f);
     }
   }
 }
@@ -400,7 +438,8 @@ template <typename T, int VEC, int MODE, int U, int POL>
 __device__ __forceinline__ void ring_reduce_pass(T* const* s_tab, const unsigned long long* s_seg,
                                                  const unsigned long long* s_tile, int N, int step,
                                                  float* acc, float scale, unsigned bx, unsigned gx,
-                                                 size_t buf_off = 0) {
+                                                 size_t buf_off = 0, unsigned long long zpos = 0) {
+  // zpos: bit p set = the replica at ring position p is a zero-gradient participant
   // buf_off: first element of the partition in the replica buffers (acc is partition-relative)
   constexpr size_t kTileElems = static_cast<size_t>(kThreads) * U * VEC;
   const size_t total = uniform_u64(s_tile[N]);
@@ -411,17 +450,23 @@ __device__ __forceinline__ void ring_reduce_pass(T* const* s_tab, const unsigned
     float* a = acc + t.begin;  // never dereferenced in the N == 2 mode
     const size_t b0 = buf_off + t.begin;
     if constexpr (MODE == kRsFirst) {
-      T* src[2] = {uniform_ptr(s_tab[t.k]) + b0, uniform_ptr(s_tab[(t.k + 1) % N]) + b0};
-      sum_block_tile<T, VEC, 2, false, true, U, POL>(src, nullptr, a, nullptr, scale, t.rem);
+      const int p1 = (t.k + 1) % N;
+      T* src[2] = {uniform_ptr(s_tab[t.k]) + b0, uniform_ptr(s_tab[p1]) + b0};
+      const unsigned long long zm = ((zpos >> t.k) & 1ull) | (((zpos >> p1) & 1ull) << 1);
+      sum_block_tile<T, VEC, 2, false, true, U, POL>(src, nullptr, a, nullptr, scale, t.rem, zm);
     } else if constexpr (MODE == kRsMid) {
-      T* src[1] = {uniform_ptr(s_tab[(t.k + step + 1) % N]) + b0};
-      sum_block_tile<T, VEC, 1, true, true, U, POL>(src, a, a, nullptr, scale, t.rem);
+      const int p = (t.k + step + 1) % N;
+      T* src[1] = {uniform_ptr(s_tab[p]) + b0};
+      sum_block_tile<T, VEC, 1, true, true, U, POL>(src, a, a, nullptr, scale, t.rem, (zpos >> p) & 1ull);
     } else if constexpr (MODE == kRsLast) {
-      T* src[1] = {uniform_ptr(s_tab[(t.k + N - 1) % N]) + b0};
-      sum_block_tile<T, VEC, 1, true, false, U, POL>(src, a, nullptr, src[0], scale, t.rem);
+      const int p = (t.k + N - 1) % N;
+      T* src[1] = {uniform_ptr(s_tab[p]) + b0};
+      sum_block_tile<T, VEC, 1, true, false, U, POL>(src, a, nullptr, src[0], scale, t.rem, (zpos >> p) & 1ull);
     } else {  // kRsOnly, N == 2
-      T* src[2] = {uniform_ptr(s_tab[t.k]) + b0, uniform_ptr(s_tab[(t.k + 1) % N]) + b0};
-      sum_block_tile<T, VEC, 2, false, false, U, POL>(src, nullptr, nullptr, src[1], scale, t.rem);
+      const int p1 = (t.k + 1) % N;
+      T* src[2] = {uniform_ptr(s_tab[t.k]) + b0, uniform_ptr(s_tab[p1]) + b0};
+      const unsigned long long zm = ((zpos >> t.k) & 1ull) | (((zpos >> p1) & 1ull) << 1);
+      sum_block_tile<T, VEC, 2, false, false, U, POL>(src, nullptr, nullptr, src[1], scale, t.rem, zm);
     }
   }
 }
@@ -463,11 +508,13 @@ __device__ __forceinline__ void ring_allgather_pass(T* const* s_tab, const unsig
 // One ReduceScatter step over all N portions.
 template <typename T, int VEC, int MODE, int U, int POL>
 __global__ void __launch_bounds__(kThreads)
-k_ring_reduce(PtrTable ring, SegTable seg, SegTable tile0, int N, int step, float* acc, float scale) {
+k_ring_reduce(PtrTable ring, SegTable seg, SegTable tile0, int N, int step, float* acc, float scale,
+              unsigned long long zpos) {
   __shared__ T* s_tab[kMaxReplicas];
   __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
   stage_ring_tables<T>(ring, seg, tile0, N, s_tab, s_seg, s_tile);
-  ring_reduce_pass<T, VEC, MODE, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale, blockIdx.x, gridDim.x);
+  ring_reduce_pass<T, VEC, MODE, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale, blockIdx.x, gridDim.x, 0,
+                                         zpos);
 }
 
 // One AllGather step over all N portions.
@@ -486,14 +533,18 @@ k_ring_allgather(PtrTable ring, SegTable seg, SegTable tile0, int N, int step) {
 // (portion k: positions k, k+1, ..., k+N-1 mod N), and the rounded mean can be written straight
 // into all N replica buffers.  Same bits as the step schedule, 2*N*E bytes per element instead
 // of 4*N*E + 10*N - 20 (N = 16, bf16: 64 instead of 206).
-template <typename T, int VEC, int N, int U, int POL>
-__device__ __forceinline__ void onepass_tile(T* const (&buf)[N], float scale, size_t v) {
+template <typename T, int VEC, int N, int U, int POL, bool ZM>
+__device__ __forceinline__ void onepass_tile(T* const (&buf)[N], float scale, size_t v,
+                                             unsigned long long zm) {
   typedef typename Raw<T, VEC>::type R;
   R raw[U][N];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
 #pragma unroll
-    for (int j = 0; j < N; ++j) raw[u][j] = ld<POL>(reinterpret_cast<const R*>(buf[j]) + v + u * kThreads);
+    for (int j = 0; j < N; ++j) {
+      if (ZM && ((zm >> j) & 1ull)) raw[u][j] = R{};
+      else raw[u][j] = ld<POL>(reinterpret_cast<const R*>(buf[j]) + v + u * kThreads);
+    }
   }
 #pragma unroll
   for (int u = 0; u < U; ++u) {
@@ -516,15 +567,18 @@ __device__ __forceinline__ void onepass_tile(T* const (&buf)[N], float scale, si
 // Any N (runtime): loads in groups of 8 in ring order starting at position k, then N stores.
 template <typename T, int VEC, int POL>
 __device__ __forceinline__ void onepass_any_one(T* const* s_tab, int N, int k, size_t base, float scale,
-                                                size_t v) {
+                                                size_t v, unsigned long long zpos) {
   typedef typename Raw<T, VEC>::type R;
   float a[VEC];
   for (int j0 = 0; j0 < N; j0 += 8) {
     R raw[8];
 #pragma unroll
     for (int jj = 0; jj < 8; ++jj)
-      if (j0 + jj < N)
-        raw[jj] = ld<POL>(reinterpret_cast<const R*>(uniform_ptr(s_tab[(k + j0 + jj) % N]) + base) + v);
+      if (j0 + jj < N) {
+        const int p = (k + j0 + jj) % N;
+        if ((zpos >> p) & 1ull) raw[jj] = R{};
+        else raw[jj] = ld<POL>(reinterpret_cast<const R*>(uniform_ptr(s_tab[p]) + base) + v);
+      }
 #pragma unroll
     for (int jj = 0; jj < 8; ++jj) {
       if (j0 + jj < N) {
@@ -548,19 +602,20 @@ __device__ __forceinline__ void onepass_any_one(T* const* s_tab, int N, int k, s
 
 template <typename T, int VEC, int POL>
 __device__ __forceinline__ void onepass_any_range(T* const* s_tab, int N, int k, size_t base, float scale,
-                                                  size_t len) {
+                                                  size_t len, unsigned long long zpos) {
   const size_t n_vec = len / VEC;
-  for (size_t v = threadIdx.x; v < n_vec; v += kThreads) onepass_any_one<T, VEC, POL>(s_tab, N, k, base, scale, v);
+  for (size_t v = threadIdx.x; v < n_vec; v += kThreads)
+    onepass_any_one<T, VEC, POL>(s_tab, N, k, base, scale, v, zpos);
   if constexpr (VEC > 1) {
     const size_t e = n_vec * VEC + threadIdx.x;
-    if (e < len) onepass_any_one<T, 1, POL>(s_tab, N, k, base, scale, e);
+    if (e < len) onepass_any_one<T, 1, POL>(s_tab, N, k, base, scale, e, zpos);
   }
 }
 
 // NT = compile-time N for the unrolled tile (1..16), or 0: any N through the grouped loop.
 template <typename T, int VEC, int NT, int POL>
 __global__ void __launch_bounds__(kThreads)
-k_ring_onepass(PtrTable ring, SegTable seg, SegTable tile0, int N, float scale) {
+k_ring_onepass(PtrTable ring, SegTable seg, SegTable tile0, int N, float scale, unsigned long long zpos) {
   __shared__ T* s_tab[kMaxReplicas];
   __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
   stage_ring_tables<T>(ring, seg, tile0, N, s_tab, s_seg, s_tile);
@@ -574,14 +629,20 @@ k_ring_onepass(PtrTable ring, SegTable seg, SegTable tile0, int N, float scale) 
     if constexpr (NT > 0) {
       if (t.rem >= kTileElems) {
         T* buf[NT];
+        unsigned long long zm = 0;
 #pragma unroll
-        for (int m = 0; m < NT; ++m) buf[m] = uniform_ptr(s_tab[(t.k + m) % NT]) + t.begin;
-        onepass_tile<T, VEC, NT, U, POL>(buf, scale, threadIdx.x);
+        for (int m = 0; m < NT; ++m) {
+          const int p = (t.k + m) % NT;
+          buf[m] = uniform_ptr(s_tab[p]) + t.begin;
+          zm |= ((zpos >> p) & 1ull) << m;
+        }
+        if (zm == 0) onepass_tile<T, VEC, NT, U, POL, false>(buf, scale, threadIdx.x, 0);
+        else onepass_tile<T, VEC, NT, U, POL, true>(buf, scale, threadIdx.x, zm);
         continue;
       }
     }
-    if (t.rem >= kTileElems) onepass_any_range<T, VEC, POL>(s_tab, N, t.k, t.begin, scale, kTileElems);
-    else onepass_any_range<T, VEC, POL>(s_tab, N, t.k, t.begin, scale, t.rem);
+    if (t.rem >= kTileElems) onepass_any_range<T, VEC, POL>(s_tab, N, t.k, t.begin, scale, kTileElems, zpos);
+    else onepass_any_range<T, VEC, POL>(s_tab, N, t.k, t.begin, scale, t.rem, zpos);
   }
 }
 
@@ -681,15 +742,16 @@ template <typename T, int VEC, int POL>
 __global__ void __launch_bounds__(kThreads)
 k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable tile_last, int N, float* acc,
                   float scale, Ctrl* ctrl, DevCtrl* mirror, unsigned long long timeout_ticks,
-                  unsigned long long max_spins, unsigned flags) {
+                  unsigned long long max_spins, unsigned flags, unsigned long long zpos) {
   __shared__ T* s_tab[kMaxReplicas];
   __shared__ unsigned long long s_seg[2][kMaxReplicas + 1], s_tile[2][kMaxReplicas + 1];
   __shared__ unsigned long long s_gate;  // what lane 0 saw: released slots, or a verdict in bits 32..33
   const unsigned n_workers = gridDim.x - 1;
-  if (blockIdx.x == n_workers) {  // the last block is the relay
+  if (blockIdx.x == 0) {  // the first block (dispatched first, so always resident) is the relay
     relay_loop(ctrl, mirror, n_workers, max_spins, flags);
     return;
   }
+  const unsigned worker = blockIdx.x - 1;
   const unsigned tid = threadIdx.x;
   if (tid < static_cast<unsigned>(N)) s_tab[tid] = static_cast<T*>(ring.p[tid]);
   if (tid <= static_cast<unsigned>(N)) {
@@ -745,14 +807,14 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
     const unsigned long long* til = s_tile[sel];
     const size_t off = static_cast<size_t>(part) * geom.part_elems;
     if (step < N - 1) {
-      if (N == 2) ring_reduce_pass<T, VEC, kRsOnly, U, POL>(s_tab, seg, til, N, step, acc, scale, blockIdx.x, n_workers, off);
-      else if (step == 0) ring_reduce_pass<T, VEC, kRsFirst, U, POL>(s_tab, seg, til, N, step, acc, scale, blockIdx.x, n_workers, off);
-      else if (step == N - 2) ring_reduce_pass<T, VEC, kRsLast, U, POL>(s_tab, seg, til, N, step, acc, scale, blockIdx.x, n_workers, off);
-      else ring_reduce_pass<T, VEC, kRsMid, U, POL>(s_tab, seg, til, N, step, acc, scale, blockIdx.x, n_workers, off);
+      if (N == 2) ring_reduce_pass<T, VEC, kRsOnly, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off, zpos);
+      else if (step == 0) ring_reduce_pass<T, VEC, kRsFirst, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off, zpos);
+      else if (step == N - 2) ring_reduce_pass<T, VEC, kRsLast, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off, zpos);
+      else ring_reduce_pass<T, VEC, kRsMid, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off, zpos);
     } else {
       // same tiles, widest copy: kThreads*U*VEC == kThreads*(U*VEC/CV)*CV
       constexpr int CV = VEC == 1 ? 1 : 16 / static_cast<int>(sizeof(T));
-      ring_allgather_pass<T, CV, U * VEC / CV, POL>(s_tab, seg, til, N, step - (N - 1), blockIdx.x, n_workers, off);
+      ring_allgather_pass<T, CV, U * VEC / CV, POL>(s_tab, seg, til, N, step - (N - 1), worker, n_workers, off);
     }
     // A block-wide barrier with workgroup release/acquire is needed (a) before the first
     // AllGather step, whose 16-byte lanes read what other lanes of the block wrote in the last
@@ -772,9 +834,9 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
     // block and report: 18 % at 64 Mi elements when every slot is reported).
     if (report && tid == 0) {
       if (flags & FTAR_PERSIST_PUBLISH)
-        __hip_atomic_store(&mirror->worker_slot[blockIdx.x], slot + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&mirror->worker_slot[worker], slot + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
       else
-        dev_store(&mirror->worker_slot[blockIdx.x], slot + 1);
+        dev_store(&mirror->worker_slot[worker], slot + 1);
       if (flags & FTAR_PERSIST_ALIGN) {
         // Soft barrier, a performance hint only (bounded, nobody depends on it): blocks that ran
         // ahead wait for the stragglers, so all blocks stay in the same slot and read the same
@@ -871,7 +933,7 @@ bool wide_tiles() { return (current_tuning().flags & 0x20) != 0; }
 
 template <typename T, int VEC>
 struct ReduceFixed {
-  const PtrTable& live; int N; size_t count; T* out; float scale; hipStream_t stream;
+  const PtrTable& live; int N; size_t count; T* out; float scale; float zterm; hipStream_t stream;
   template <int POL> hipError_t operator()(unsigned blocks) const {
     const bool wide = wide_tiles();
     const int U = wide ? unroll_wide(N) : unroll_narrow(N);
@@ -882,10 +944,10 @@ struct ReduceFixed {
   case n:                                                                                         \
     if (wide)                                                                                     \
       launch(k_reduce_masked<T, VEC, n, unroll_wide(n), POL>, grid, block, stream, live, out, scale, \
-                                                                                  count);         \
+                                                                                  count, zterm);  \
     else                                                                                          \
       launch(k_reduce_masked<T, VEC, n, unroll_narrow(n), POL>, grid, block, stream, live, out,    \
-                                                                                    scale, count); \
+                                                                                    scale, count, zterm); \
     break;
       FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
       FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
@@ -899,22 +961,23 @@ struct ReduceFixed {
 
 template <typename T, int VEC>
 struct ReduceAny {
-  const PtrTable& live; int N; size_t count; T* out; float scale; hipStream_t stream;
+  const PtrTable& live; int N; size_t count; T* out; float scale; float zterm; hipStream_t stream;
   template <int POL> hipError_t operator()(unsigned blocks) const {
     const size_t tiles = (count / VEC + kThreads - 1) / kThreads;
     const dim3 grid(grid_x_for(tiles, blocks)), block(kThreads);
-    launch(k_reduce_masked_any<T, VEC, POL>, grid, block, stream, live, N, out, scale, count);
+    launch(k_reduce_masked_any<T, VEC, POL>, grid, block, stream, live, N, out, scale, count, zterm);
     return hipGetLastError();
   }
 };
 
 template <typename T, int VECW>
 hipError_t reduce_masked_typed(const PtrTable& live, int N, size_t count, bool vec, void* out,
-                               float scale, hipStream_t stream) {
+                               float scale, float zterm, hipStream_t stream) {
   T* o = static_cast<T*>(out);
-  if (vec && N <= 16) return with_policy(reduce_cfg(N, count * sizeof(T)), ReduceFixed<T, VECW>{live, N, count, o, scale, stream});
-  if (vec) return with_policy(reduce_cfg(N, count * sizeof(T)), ReduceAny<T, VECW>{live, N, count, o, scale, stream});
-  return with_policy(reduce_cfg(N, count * sizeof(T)), ReduceAny<T, 1>{live, N, count, o, scale, stream});
+  const LaunchCfg cfg = reduce_cfg(N, count * sizeof(T));
+  if (vec && N <= 16) return with_policy(cfg, ReduceFixed<T, VECW>{live, N, count, o, scale, zterm, stream});
+  if (vec) return with_policy(cfg, ReduceAny<T, VECW>{live, N, count, o, scale, zterm, stream});
+  return with_policy(cfg, ReduceAny<T, 1>{live, N, count, o, scale, zterm, stream});
 }
 
 template <typename T, int VEC>
@@ -968,11 +1031,11 @@ SegTable ring_tiles(const SegTable& seg, int N, int vec, int U) {
 template <typename T, int VEC>
 struct RingReduce {
   RingMode mode; const PtrTable& ring; int N; int step; const SegTable& seg; float* acc; float scale;
-  hipStream_t stream;
+  unsigned long long zpos; hipStream_t stream;
   template <int MODE, int U, int POL> void go(unsigned blocks) const {
     const SegTable tiles = ring_tiles(seg, N, VEC, U);
     const dim3 grid(grid_x_for(tiles.begin[N], blocks)), block(kThreads);
-    launch(k_ring_reduce<T, VEC, MODE, U, POL>, grid, block, stream, ring, seg, tiles, N, step, acc, scale);
+    launch(k_ring_reduce<T, VEC, MODE, U, POL>, grid, block, stream, ring, seg, tiles, N, step, acc, scale, zpos);
   }
   template <int MODE, int POL> void pick_unroll(unsigned blocks) const {
     const int U = ring_unroll();
@@ -1010,18 +1073,18 @@ struct RingAllgather {
 
 template <typename T, int VEC>
 struct RingOnepass {
-  const PtrTable& ring; int N; const SegTable& seg; float scale; hipStream_t stream;
+  const PtrTable& ring; int N; const SegTable& seg; float scale; unsigned long long zpos; hipStream_t stream;
   template <int POL> hipError_t operator()(unsigned blocks) const {
     const int U = (VEC == 1 || N > 16) ? 1 : unroll_narrow(N);  // must match the kernel's tile
     const SegTable tiles = ring_tiles(seg, N, VEC, U);
     const dim3 grid(grid_x_for(tiles.begin[N], blocks)), block(kThreads);
     if (VEC == 1 || N > 16) {
-      launch(k_ring_onepass<T, VEC, 0, POL>, grid, block, stream, ring, seg, tiles, N, scale);
+      launch(k_ring_onepass<T, VEC, 0, POL>, grid, block, stream, ring, seg, tiles, N, scale, zpos);
       return hipGetLastError();
     }
     switch (N) {
 #define FTAR_CASE(n) \
-  case n: launch(k_ring_onepass<T, VEC, (VEC == 1 ? 0 : n), POL>, grid, block, stream, ring, seg, tiles, N, scale); break;
+  case n: launch(k_ring_onepass<T, VEC, (VEC == 1 ? 0 : n), POL>, grid, block, stream, ring, seg, tiles, N, scale, zpos); break;
       FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7) FTAR_CASE(8)
       FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13) FTAR_CASE(14)
       FTAR_CASE(15) FTAR_CASE(16)
@@ -1036,15 +1099,23 @@ template <typename T, int VEC>
 struct RingPersistent {
   const PtrTable& ring; int N; const PartGeom& geom; float* acc; float scale; Ctrl* ctrl;
   DevCtrl* mirror; unsigned n_blocks; unsigned long long timeout_ticks; unsigned flags;
-  hipStream_t stream;
+  unsigned long long zpos; hipStream_t stream;
   template <int POL> hipError_t operator()(unsigned) const {
     const SegTable tile_full = ring_tiles(geom.seg_full, N, VEC, kPersistentUnroll);
     const SegTable tile_last = ring_tiles(geom.seg_last, N, VEC, kPersistentUnroll);
+    // Every workgroup must be resident at once: a worker that waits for the CPU keeps its place,
+    // and the CPU may be waiting for a worker that has not started.  Clamp to what fits.
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_ring_persistent<T, VEC, POL>, kThreads, 0) !=
+            hipSuccess || per_cu < 1)
+      per_cu = 1;
+    const unsigned capacity = static_cast<unsigned>(per_cu) * static_cast<unsigned>(device_cu_count());
+    const unsigned workers = n_blocks + 1 > capacity ? capacity - 1 : n_blocks;
     hipLaunchKernelGGL(k_clear_mirror, dim3(1), dim3(256), 0, stream, mirror);
-    const dim3 grid(n_blocks + 1), block(kThreads);  // workers + the relay
+    const dim3 grid(workers + 1), block(kThreads);  // the relay + the workers
     // one spin of a wait is a sleep plus two loads from device memory: well over 0.1 us
     launch(k_ring_persistent<T, VEC, POL>, grid, block, stream, ring, geom, tile_full, tile_last, N, acc,
-           scale, ctrl, mirror, timeout_ticks, timeout_ticks / 10 + 100000, flags);
+           scale, ctrl, mirror, timeout_ticks, timeout_ticks / 10 + 100000, flags, zpos);
     return hipGetLastError();
   }
 };
@@ -1053,10 +1124,31 @@ struct RingPersistent {
 
 // ---- exported launchers ----------------------------------------------------
 
-hipError_t launch_reduce_masked(const PtrTable& live, int n_live, size_t count, ftar_dtype_t dtype,
-                                bool vec, void* out, float scale, hipStream_t stream) {
-  if (dtype == FTAR_F32) return reduce_masked_typed<float, 4>(live, n_live, count, vec, out, scale, stream);
-  return reduce_masked_typed<bf16, 8>(live, n_live, count, vec, out, scale, stream);
+hipError_t launch_reduce_masked(const PtrTable& live, int n_src, size_t count, ftar_dtype_t dtype,
+                                bool vec, void* out, float scale, bool zero_participants,
+                                hipStream_t stream) {
+  if (n_src == 0) {  // nothing to read; bf16 buffers are only 2-byte aligned: head/tail by halves
+    if (!zero_participants) return hipErrorInvalidValue;
+    const size_t bytes = count * (dtype == FTAR_F32 ? 4 : 2);
+    char* o = static_cast<char*>(out);
+    uint16_t *head = nullptr, *odd = nullptr;
+    size_t left = bytes;
+    if (reinterpret_cast<uintptr_t>(o) % 4 != 0) {  // 2-byte aligned bf16: first half alone
+      head = reinterpret_cast<uint16_t*>(o);
+      o += 2;
+      left -= 2;
+    }
+    const size_t n32 = left / 4;
+    if (left % 4) odd = reinterpret_cast<uint16_t*>(o + n32 * 4);
+    const unsigned blocks = static_cast<unsigned>(std::min<size_t>((n32 + kThreads - 1) / kThreads + 1,
+                                                                  static_cast<size_t>(device_cu_count()) * 8));
+    launch(k_fill_zero, dim3(blocks), dim3(kThreads), stream, head, reinterpret_cast<uint32_t*>(o), n32, odd);
+    return hipGetLastError();
+  }
+  const float zterm = zero_participants ? 0.0f : -0.0f;
+  if (dtype == FTAR_F32)
+    return reduce_masked_typed<float, 4>(live, n_src, count, vec, out, scale, zterm, stream);
+  return reduce_masked_typed<bf16, 8>(live, n_src, count, vec, out, scale, zterm, stream);
 }
 
 hipError_t launch_reduce_bucketed(const PtrTable& all, int n_replicas, const BucketTable& masks,
@@ -1072,13 +1164,13 @@ hipError_t launch_reduce_bucketed(const PtrTable& all, int n_replicas, const Buc
 
 hipError_t launch_ring_reduce(RingMode mode, const PtrTable& ring, int n_live, int step,
                               const SegTable& seg, ftar_dtype_t dtype, bool vec, float* acc,
-                              float scale, hipStream_t stream) {
+                              float scale, unsigned long long zpos, hipStream_t stream) {
   if (dtype == FTAR_F32) {
-    if (vec) return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<float, 4>{mode, ring, n_live, step, seg, acc, scale, stream});
-    return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<float, 1>{mode, ring, n_live, step, seg, acc, scale, stream});
+    if (vec) return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<float, 4>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
+    return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<float, 1>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
   }
-  if (vec) return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<bf16, 4>{mode, ring, n_live, step, seg, acc, scale, stream});
-  return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<bf16, 1>{mode, ring, n_live, step, seg, acc, scale, stream});
+  if (vec) return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<bf16, 4>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
+  return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<bf16, 1>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
 }
 
 hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, const SegTable& seg,
@@ -1092,22 +1184,23 @@ hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, con
 }
 
 hipError_t launch_ring_onepass(const PtrTable& ring, int n_live, const SegTable& seg,
-                               ftar_dtype_t dtype, bool vec, float scale, hipStream_t stream) {
+                               ftar_dtype_t dtype, bool vec, float scale, unsigned long long zpos,
+                               hipStream_t stream) {
   // N reads and N writes per element, as many write streams as read streams: non-temporal
   // stores and one workgroup per CU are best at every size measured
   const LaunchCfg cfg = launch_cfg(1, 3);
   if (dtype == FTAR_F32) {
-    if (vec) return with_policy(cfg, RingOnepass<float, 4>{ring, n_live, seg, scale, stream});
-    return with_policy(cfg, RingOnepass<float, 1>{ring, n_live, seg, scale, stream});
+    if (vec) return with_policy(cfg, RingOnepass<float, 4>{ring, n_live, seg, scale, zpos, stream});
+    return with_policy(cfg, RingOnepass<float, 1>{ring, n_live, seg, scale, zpos, stream});
   }
-  if (vec) return with_policy(cfg, RingOnepass<bf16, 8>{ring, n_live, seg, scale, stream});
-  return with_policy(cfg, RingOnepass<bf16, 1>{ring, n_live, seg, scale, stream});
+  if (vec) return with_policy(cfg, RingOnepass<bf16, 8>{ring, n_live, seg, scale, zpos, stream});
+  return with_policy(cfg, RingOnepass<bf16, 1>{ring, n_live, seg, scale, zpos, stream});
 }
 
 hipError_t launch_ring_persistent(const PtrTable& ring, int n_live, const PartGeom& geom,
                                   ftar_dtype_t dtype, bool vec, float* acc, float scale, Ctrl* ctrl_dev,
                                   DevCtrl* mirror, unsigned n_blocks, unsigned long long timeout_ticks,
-                                  unsigned flags, hipStream_t stream) {
+                                  unsigned flags, unsigned long long zpos, hipStream_t stream) {
   // Stores as in the middle ReduceScatter step: what a slot writes, the next one reads.  The
   // partials of one partition are what must fit the Infinity Cache.
   const size_t acc_bytes = (geom.n_parts > 1 ? geom.part_elems : geom.seg_full.begin[n_live]) * 4;
@@ -1115,15 +1208,15 @@ hipError_t launch_ring_persistent(const PtrTable& ring, int n_live, const PartGe
   if (dtype == FTAR_F32) {
     if (vec)
       return with_policy(cfg, RingPersistent<float, 4>{ring, n_live, geom, acc, scale, ctrl_dev, mirror,
-                                                       n_blocks, timeout_ticks, flags, stream});
+                                                       n_blocks, timeout_ticks, flags, zpos, stream});
     return with_policy(cfg, RingPersistent<float, 1>{ring, n_live, geom, acc, scale, ctrl_dev, mirror,
-                                                     n_blocks, timeout_ticks, flags, stream});
+                                                     n_blocks, timeout_ticks, flags, zpos, stream});
   }
   if (vec)
     return with_policy(cfg, RingPersistent<bf16, 4>{ring, n_live, geom, acc, scale, ctrl_dev, mirror,
-                                                    n_blocks, timeout_ticks, flags, stream});
+                                                    n_blocks, timeout_ticks, flags, zpos, stream});
   return with_policy(cfg, RingPersistent<bf16, 1>{ring, n_live, geom, acc, scale, ctrl_dev, mirror,
-                                                  n_blocks, timeout_ticks, flags, stream});
+                                                  n_blocks, timeout_ticks, flags, zpos, stream});
 }
 
 }  // namespace ftar
