@@ -100,7 +100,7 @@ ftar_status_t ftar_plan_set_dtype(ftar_plan_t* plan, ftar_dtype_t dtype);
 int ftar_plan_n_live(const ftar_plan_t* plan);     /* N; 0 if plan is NULL */
 int ftar_plan_n_steps(const ftar_plan_t* plan);    /* N-1, the steps of each phase */
 size_t ftar_plan_acc_bytes(const ftar_plan_t* plan); /* size of `acc`: 4 bytes per element of one partition */
-float ftar_plan_scale(const ftar_plan_t* plan);    /* 1.0f/(float)N */
+float ftar_plan_scale(const ftar_plan_t* plan);    /* 1.0f/(float)N unless changed by set_zero_mask / set_op */
 /* Portion k in [0,N): element range [*begin,*end) and the replica that holds its
  * finished value after the ReduceScatter phase (the replica at ring position k-1). */
 ftar_status_t ftar_plan_segment(const ftar_plan_t* plan, int k, size_t* begin, size_t* end,
@@ -190,6 +190,34 @@ ftar_status_t ftar_allgather_step(const ftar_plan_t* plan, int step, void* const
  */
 ftar_status_t ftar_reduce_masked(const void* const* bufs, int n_replicas, uint64_t live_mask,
                                  size_t count, ftar_dtype_t dtype, void* out, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Delivery variants.
+ * Paper: section 4.1 states the exchange as the SUM of the participants' gradients (the mean is
+ * this build's default reading); FTAR_SUM gives exactly that: the scale factor is 1.0f, all else
+ * is unchanged.  ftar_plan_set_op applies to every ring call made with the plan afterwards;
+ * ftar_plan_scale reports the factor in force.
+ * ftar_reduce_masked_ex is the one-shot reduce with everything selectable: zero-gradient
+ * participants (as ftar_reduce_masked_zero), the operation, and the result type, which is
+ * in_dtype or FTAR_F32 from FTAR_BF16 inputs (the fp32 sum/mean is then stored unrounded:
+ * 2N read + 4 written bytes per element).  Other type pairs: FTAR_ERR_INVALID_ARG.
+ */
+typedef enum { FTAR_MEAN = 0, FTAR_SUM = 1 } ftar_op_t;
+ftar_status_t ftar_plan_set_op(ftar_plan_t* plan, ftar_op_t op);
+ftar_status_t ftar_reduce_masked_ex(const void* const* bufs, int n_replicas, uint64_t live_mask,
+                                    uint64_t zero_mask, int contributors_only, size_t count,
+                                    ftar_dtype_t in_dtype, ftar_dtype_t out_dtype, ftar_op_t op,
+                                    void* out, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Learning-rate intervention factors.
+ * Paper: section 6.2 - with fewer healthy replicas a step trains on less data; the "linear"
+ * strategy scales the learning rate by healthy/total replicas, the "sqrt" strategy by the
+ * square root of that ratio.  Healthy = live and not a zero-gradient participant of the plan;
+ * total = n_replicas.  Host-only: *linear = (float)healthy / (float)n_replicas,
+ * *root = (float)sqrt((double)healthy / (double)n_replicas).  Either pointer may be NULL.
+ */
+ftar_status_t ftar_plan_lr_factors(const ftar_plan_t* plan, float* linear, float* root);
 
 /* ---------------------------------------------------------------------------
  * ftar_reduce_masked_bucketed - ftar_reduce_masked with a live mask of its own

@@ -47,6 +47,7 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <cmath>
 #include <cstring>
 #include <vector>
 
@@ -213,6 +214,48 @@ int oracle_reduce_masked_zero(const void* const* bufs, int n, uint64_t live_mask
     a = a * scale;
     store_cvt(out, i, dtype, a);
   }
+  return N;
+}
+
+// Delivery variants of the one-shot reduction: the result type may be fp32 although the inputs
+// are bf16 (the one rounding to the output type is then the identity), and the operation may be
+// the plain sum of section 4.1 instead of this build's mean.  Otherwise as
+// oracle_reduce_masked_zero.
+int oracle_reduce_masked_ex(const void* const* bufs, int n, uint64_t live_mask, uint64_t zero_mask,
+                            int contributors_only, size_t count, int in_dtype, int out_dtype,
+                            int sum_only, void* out) {
+  int ring[64];
+  int N = live_ring(n, live_mask, ring);
+  if (N < 0) return N;
+  if ((zero_mask & ~live_mask) != 0) return -3;
+  int Z = 0;
+  for (int j = 0; j < N; ++j) Z += (zero_mask >> ring[j]) & 1u;
+  const int divisor = contributors_only ? N - Z : N;
+  if (divisor <= 0) return -2;
+  const float scale = sum_only ? 1.0f : 1.0f / static_cast<float>(divisor);
+  for (size_t i = 0; i < count; ++i) {
+    float a = ((zero_mask >> ring[0]) & 1u) ? 0.0f : load_f32(bufs[ring[0]], i, in_dtype);
+    for (int j = 1; j < N; ++j)
+      a = a + (((zero_mask >> ring[j]) & 1u) ? 0.0f : load_f32(bufs[ring[j]], i, in_dtype));
+    a = a * scale;
+    store_cvt(out, i, out_dtype, a);
+  }
+  return N;
+}
+
+// Learning-rate intervention factors of section 6.2: "linear" = healthy replicas / all replicas,
+// "sqrt" = the square root of that ratio.  Healthy = taking part and contributing a gradient
+// (a zero-gradient participant trains on no data in this step).  linear is the fp32 quotient of
+// the two counts; root is the binary64 square root of the binary64 quotient, rounded to fp32.
+int oracle_lr_factors(int n, uint64_t live_mask, uint64_t zero_mask, float* linear, float* root) {
+  int ring[64];
+  int N = live_ring(n, live_mask, ring);
+  if (N < 0) return N;
+  if ((zero_mask & ~live_mask) != 0) return -3;
+  int healthy = 0;
+  for (int j = 0; j < N; ++j) healthy += ((zero_mask >> ring[j]) & 1u) ? 0 : 1;
+  *linear = static_cast<float>(healthy) / static_cast<float>(n);
+  *root = static_cast<float>(std::sqrt(static_cast<double>(healthy) / static_cast<double>(n)));
   return N;
 }
 

@@ -58,6 +58,10 @@ def lib():
         L.oracle_reduce_masked.argtypes = [vp, ci, u64, sz, ci, ci, vp]
         L.oracle_reduce_masked_zero.restype = ci
         L.oracle_reduce_masked_zero.argtypes = [vp, ci, u64, u64, ci, sz, ci, vp]
+        L.oracle_reduce_masked_ex.restype = ci
+        L.oracle_reduce_masked_ex.argtypes = [vp, ci, u64, u64, ci, sz, ci, ci, ci, vp]
+        L.oracle_lr_factors.restype = ci
+        L.oracle_lr_factors.argtypes = [ci, u64, u64, vp, vp]
         L.oracle_ring_closed_form_zero.restype = ci
         L.oracle_ring_closed_form_zero.argtypes = [vp, ci, u64, u64, ci, sz, sz, ci, sz, sz, vp]
         L.oracle_reduce_f64.restype = ci
@@ -155,6 +159,27 @@ def reduce_masked_zero(bufs, live_mask, zero_mask, dtype, contributors_only=Fals
     _check(lib().oracle_reduce_masked_zero(tab, n, live_mask, zero_mask, int(contributors_only), count,
                                            dtype, out.ctypes.data))
     return out
+
+
+def reduce_masked_ex(bufs, live_mask, dtype, out_dtype=None, zero_mask=0, contributors_only=False,
+                     sum_only=False, count=None):
+    """One-shot reduction with a result type and operation of choice; zero participants may be None."""
+    n = len(bufs)
+    out_dtype = dtype if out_dtype is None else out_dtype
+    if count is None:
+        count = [b for b in bufs if b is not None][0].size
+    out = np.empty(count, dtype=_np_dtype(out_dtype))
+    tab = _ptr_table(bufs, dtype, live_mask & ~zero_mask)
+    _check(lib().oracle_reduce_masked_ex(tab, n, live_mask, zero_mask, int(contributors_only), count,
+                                         dtype, out_dtype, int(sum_only), out.ctypes.data))
+    return out
+
+
+def lr_factors(n, live_mask, zero_mask=0):
+    """(linear, sqrt) learning-rate factors as two numpy float32 scalars."""
+    lin, root = np.zeros(1, np.float32), np.zeros(1, np.float32)
+    _check(lib().oracle_lr_factors(n, live_mask, zero_mask, lin.ctypes.data, root.ctypes.data))
+    return lin[0], root[0]
 
 
 def ring_closed_form_zero(bufs, live_mask, zero_mask, count, chunk_elems, dtype, contributors_only=False,

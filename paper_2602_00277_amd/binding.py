@@ -27,6 +27,9 @@ FTAR_ERR_BAD_STEP = 4
 FTAR_ERR_STALE_PLAN = 16
 FTAR_ERR_DEVICE = 32
 
+FTAR_MEAN = 0
+FTAR_SUM = 1
+
 FTAR_PERSIST_PUBLISH = 1
 FTAR_PERSIST_ALIGN = 2
 
@@ -41,7 +44,7 @@ EXPORTS = [
     "ftar_ctrl_cancel", "ftar_ctrl_progress", "ftar_ctrl_result",
     "ftar_plan_set_partition", "ftar_plan_n_partitions", "ftar_plan_n_slots",
     "ftar_plan_partition_segment", "ftar_allreduce_onepass", "ftar_plan_set_zero_mask",
-    "ftar_reduce_masked_zero",
+    "ftar_reduce_masked_zero", "ftar_plan_set_op", "ftar_reduce_masked_ex", "ftar_plan_lr_factors",
 ]
 
 _lib = None
@@ -112,6 +115,12 @@ def lib():
     L.ftar_plan_set_zero_mask.argtypes = [vp, u64, ci]
     L.ftar_reduce_masked_zero.restype = ci
     L.ftar_reduce_masked_zero.argtypes = [vp, ci, u64, u64, ci, sz, ci, vp, vp]
+    L.ftar_plan_set_op.restype = ci
+    L.ftar_plan_set_op.argtypes = [vp, ci]
+    L.ftar_reduce_masked_ex.restype = ci
+    L.ftar_reduce_masked_ex.argtypes = [vp, ci, u64, u64, ci, sz, ci, ci, ci, vp, vp]
+    L.ftar_plan_lr_factors.restype = ci
+    L.ftar_plan_lr_factors.argtypes = [vp, vp, vp]
     L.ftar_allreduce_onepass.restype = ci
     L.ftar_allreduce_onepass.argtypes = [vp, vp, vp]
     L.ftar_ctrl_create.restype = vp
@@ -305,6 +314,40 @@ def ftar_reduce_masked_zero(bufs: Sequence[Optional[torch.Tensor]], live_mask: i
     if st != FTAR_OK:
         raise FtarError(st, "ftar_reduce_masked_zero")
     return out
+
+
+def ftar_reduce_masked_ex(bufs: Sequence[Optional[torch.Tensor]], live_mask: int, out: torch.Tensor,
+                          zero_mask: int = 0, contributors_only: bool = False, op: int = FTAR_MEAN,
+                          count: Optional[int] = None, stream=None) -> torch.Tensor:
+    """in_dtype is the buffers' dtype, out_dtype is out's."""
+    count = out.numel() if count is None else count
+    read = live_mask & ~zero_mask
+    srcs = [b for r, b in enumerate(bufs) if b is not None and (read >> r) & 1] or \
+           [b for b in bufs if b is not None]
+    in_dtype = srcs[0].dtype if srcs else out.dtype
+    _check_bufs(bufs, read, count, in_dtype)
+    _check_bufs([out], 1, count, out.dtype)
+    st = lib().ftar_reduce_masked_ex(_ptr_array(bufs), len(bufs), live_mask, zero_mask,
+                                     int(contributors_only), count, dtype_code(in_dtype),
+                                     dtype_code(out.dtype), op, out.data_ptr(), _stream_handle(stream))
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_reduce_masked_ex")
+    return out
+
+
+def ftar_plan_set_op(plan: "Plan", op: int) -> None:
+    st = lib().ftar_plan_set_op(plan.handle, op)
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_plan_set_op")
+
+
+def ftar_plan_lr_factors(plan: "Plan"):
+    """(linear, sqrt) learning-rate factors as Python floats holding fp32 values."""
+    lin, root = ctypes.c_float(), ctypes.c_float()
+    st = lib().ftar_plan_lr_factors(plan.handle, ctypes.byref(lin), ctypes.byref(root))
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_plan_lr_factors")
+    return lin.value, root.value
 
 
 def ftar_plan_set_zero_mask(plan: "Plan", zero_mask: int, contributors_only: bool = False) -> None:

@@ -7,6 +7,7 @@
 
 #include <atomic>
 #include <cstdlib>
+#include <cmath>
 #include <cstring>
 #include <new>
 
@@ -99,11 +100,19 @@ struct ftar_plan_s {
   SegTable seg;            // portion boundaries, n_live+1 entries (of the whole buffer)
   // partitioned ring (persistent kernel only); part_elems == 0: one partition = the whole buffer
   unsigned long long zero_pos;  // bit p: ring position p is a zero-gradient participant
+  int n_zero;                   // popcount(zero_pos)
+  int contributors_only;        // divisor = n_live - n_zero instead of n_live
+  ftar_op_t op;
   size_t part_elems;
   size_t n_parts;
   SegTable part_seg_full;  // portions of a full partition, relative to its first element
   SegTable part_seg_last;  // portions of the last partition
 };
+
+static void refresh_scale(ftar_plan_s* p) {
+  const int divisor = p->contributors_only ? p->n_live - p->n_zero : p->n_live;
+  p->scale = p->op == FTAR_SUM ? 1.0f : 1.0f / static_cast<float>(divisor);
+}
 
 // Portions are whole chunks, as even as whole chunks allow: portion k starts at chunk
 // floor(k * n_chunks / N).  Only the very last chunk can be short.
@@ -173,7 +182,25 @@ ftar_status_t ftar_plan_set_zero_mask(ftar_plan_t* plan, uint64_t zero_mask, int
   const int divisor = contributors_only ? plan->n_live - Z : plan->n_live;
   if (divisor <= 0) return fail(FTAR_ERR_NO_LIVE);
   plan->zero_pos = zpos;
-  plan->scale = 1.0f / static_cast<float>(divisor);
+  plan->n_zero = Z;
+  plan->contributors_only = contributors_only ? 1 : 0;
+  refresh_scale(plan);
+  return FTAR_OK;
+}
+
+ftar_status_t ftar_plan_set_op(ftar_plan_t* plan, ftar_op_t op) {
+  if (!plan_ok(plan) || (op != FTAR_MEAN && op != FTAR_SUM)) return fail(FTAR_ERR_INVALID_ARG);
+  plan->op = op;
+  refresh_scale(plan);
+  return FTAR_OK;
+}
+
+ftar_status_t ftar_plan_lr_factors(const ftar_plan_t* plan, float* linear, float* root) {
+  if (!plan_ok(plan)) return fail(FTAR_ERR_INVALID_ARG);
+  const int healthy = plan->n_live - plan->n_zero;
+  if (linear) *linear = static_cast<float>(healthy) / static_cast<float>(plan->n_replicas);
+  if (root)
+    *root = static_cast<float>(std::sqrt(static_cast<double>(healthy) / static_cast<double>(plan->n_replicas)));
   return FTAR_OK;
 }
 
@@ -298,16 +325,19 @@ ftar_status_t ftar_allgather_step(const ftar_plan_t* plan, int step, void* const
 
 static ftar_status_t reduce_masked_common(const void* const* bufs, int n_replicas, uint64_t live_mask,
                                           uint64_t zero_mask, int contributors_only, size_t count,
-                                          ftar_dtype_t dtype, void* out, void* stream) {
-  if (!bufs || !out || count == 0 || (dtype != FTAR_F32 && dtype != FTAR_BF16))
+                                          ftar_dtype_t dtype, ftar_dtype_t out_dtype, ftar_op_t op,
+                                          void* out, void* stream) {
+  if (!bufs || !out || count == 0 || (dtype != FTAR_F32 && dtype != FTAR_BF16) ||
+      (op != FTAR_MEAN && op != FTAR_SUM))
     return fail(FTAR_ERR_INVALID_ARG);
+  if (out_dtype != dtype && !(dtype == FTAR_BF16 && out_dtype == FTAR_F32)) return fail(FTAR_ERR_INVALID_ARG);
   int ring[kMaxReplicas];
   int N = 0;
   ftar_status_t s = resolve_mask(n_replicas, live_mask, ring, &N);
   if (s != FTAR_OK) return fail(s);
   if ((zero_mask & ~live_mask) != 0) return fail(FTAR_ERR_BAD_MASK);
   const size_t es = elem_size(dtype);
-  if (!aligned(out, es)) return fail(FTAR_ERR_INVALID_ARG);
+  if (!aligned(out, elem_size(out_dtype))) return fail(FTAR_ERR_INVALID_ARG);
   bool vec = aligned(out, 16);
   PtrTable tab;
   std::memset(&tab, 0, sizeof(tab));
@@ -321,22 +351,31 @@ static ftar_status_t reduce_masked_common(const void* const* bufs, int n_replica
   }
   const int divisor = contributors_only ? n_src : N;
   if (divisor <= 0) return fail(FTAR_ERR_NO_LIVE);
-  hipError_t e = launch_reduce_masked(tab, n_src, count, dtype, vec, out,
-                                      1.0f / static_cast<float>(divisor), n_src != N,
+  const float scale = op == FTAR_SUM ? 1.0f : 1.0f / static_cast<float>(divisor);
+  hipError_t e = launch_reduce_masked(tab, n_src, count, dtype, out_dtype, vec, out, scale, n_src != N,
                                       static_cast<hipStream_t>(stream));
   return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
 }
 
 ftar_status_t ftar_reduce_masked(const void* const* bufs, int n_replicas, uint64_t live_mask,
                                  size_t count, ftar_dtype_t dtype, void* out, void* stream) {
-  return reduce_masked_common(bufs, n_replicas, live_mask, 0, 0, count, dtype, out, stream);
+  return reduce_masked_common(bufs, n_replicas, live_mask, 0, 0, count, dtype, dtype, FTAR_MEAN, out,
+                              stream);
 }
 
 ftar_status_t ftar_reduce_masked_zero(const void* const* bufs, int n_replicas, uint64_t live_mask,
                                       uint64_t zero_mask, int contributors_only, size_t count,
                                       ftar_dtype_t dtype, void* out, void* stream) {
   return reduce_masked_common(bufs, n_replicas, live_mask, zero_mask, contributors_only, count, dtype,
-                              out, stream);
+                              dtype, FTAR_MEAN, out, stream);
+}
+
+ftar_status_t ftar_reduce_masked_ex(const void* const* bufs, int n_replicas, uint64_t live_mask,
+                                    uint64_t zero_mask, int contributors_only, size_t count,
+                                    ftar_dtype_t in_dtype, ftar_dtype_t out_dtype, ftar_op_t op,
+                                    void* out, void* stream) {
+  return reduce_masked_common(bufs, n_replicas, live_mask, zero_mask, contributors_only, count,
+                              in_dtype, out_dtype, op, out, stream);
 }
 
 ftar_status_t ftar_reduce_masked_bucketed(const void* const* bufs, int n_replicas,

@@ -84,9 +84,10 @@ int device_cu_count();  // of the current device; cached
 // participant: it contributes +0.0 and its buffer is never read.
 // live: the n_src buffers that are read, in summation order (zero-gradient participants already
 // left out: zero_participants says whether there were any; n_src may then be 0).
+// out_dtype == dtype, or fp32 from bf16 inputs.
 hipError_t launch_reduce_masked(const PtrTable& live, int n_src, size_t count, ftar_dtype_t dtype,
-                                bool vec, void* out, float scale, bool zero_participants,
-                                hipStream_t stream);
+                                ftar_dtype_t out_dtype, bool vec, void* out, float scale,
+                                bool zero_participants, hipStream_t stream);
 
 hipError_t launch_reduce_bucketed(const PtrTable& all, int n_replicas, const BucketTable& masks,
                                   int n_buckets, size_t first_elem, size_t bucket_elems,

@@ -120,7 +120,8 @@ __device__ __forceinline__ P* uniform_ptr(P* p) {
 // ---- one tile of the sum --------------------------------------------------
 // For U vectors per lane (vector v + u*kThreads):
 //   a = ACC_IN ? acc_in : x_0 ;  a = a + x_j for the remaining sources in order;
-//   ACC_OUT ? acc_out = a  :  out = cvt(scale * a)
+//   ACC_OUT == 1: acc_out = a (fp32, unscaled);  ACC_OUT == 0: out = cvt(scale * a);
+//   ACC_OUT == 2: acc_out = scale * a (fp32 result from any input type)
 // Every load of the tile is issued before the first use.  `out` may alias
 // src[NSRC-1] (the in-place last ReduceScatter step): a lane only ever writes
 // the elements it has itself already loaded.
@@ -131,7 +132,7 @@ __device__ __forceinline__ P* uniform_ptr(P* p) {
 // participants were left out of src altogether, -0.0 (the identity of IEEE addition) otherwise.
 // x_1 + ... + x_n with +0.0 terms anywhere in between equals (x_1 + ... + x_n) + 0.0 bit for bit:
 // a +0.0 term only ever changes a running sum of -0.0, and that happens iff every x_i is -0.0.
-template <typename T, int VEC, int NSRC, bool ACC_IN, bool ACC_OUT, int U, int POL, bool ZM = false,
+template <typename T, int VEC, int NSRC, bool ACC_IN, int ACC_OUT, int U, int POL, bool ZM = false,
           bool ZT = false>
 __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc_in, float* acc_out,
                                          T* out, float scale, size_t v, unsigned long long zm = 0,
@@ -164,7 +165,7 @@ __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc
 #pragma unroll
       for (int e = 0; e < VEC; ++e) a[e] = a[e] + x[e];
     }
-    if constexpr (ACC_OUT) {
+    if constexpr (ACC_OUT == 1) {
       st<POL>(reinterpret_cast<A*>(acc_out) + v + u * kThreads, narrow<A, VEC>(a));
     } else {
       if constexpr (ZT) {
@@ -173,7 +174,8 @@ __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc
       }
 #pragma unroll
       for (int e = 0; e < VEC; ++e) a[e] = a[e] * scale;
-      st<POL>(reinterpret_cast<R*>(out) + v + u * kThreads, narrow<R, VEC>(a));
+      if constexpr (ACC_OUT == 2) st<POL>(reinterpret_cast<A*>(acc_out) + v + u * kThreads, narrow<A, VEC>(a));
+      else st<POL>(reinterpret_cast<R*>(out) + v + u * kThreads, narrow<R, VEC>(a));
     }
   }
 }
@@ -181,7 +183,7 @@ __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc
 // Persistent loop of block bx of gx over the `len` elements that start at the
 // given pointers: full tiles grid-strided, then one block finishes the whole
 // vectors past the last full tile and the last len % VEC single elements.
-template <typename T, int VEC, int NSRC, bool ACC_IN, bool ACC_OUT, int U, int POL, bool ZM,
+template <typename T, int VEC, int NSRC, bool ACC_IN, int ACC_OUT, int U, int POL, bool ZM,
           bool ZT = false>
 __device__ __forceinline__ void sum_range_z(T* const (&src)[NSRC], const float* acc_in, float* acc_out,
                                             T* out, float scale, size_t len, unsigned bx,
@@ -220,10 +222,11 @@ __host__ __device__ constexpr int unroll_narrow(int n_src) {
 }
 
 // ---- any number of sources (runtime N): loads in groups of 8 ---------------
-template <typename T, int VEC, int POL>
-__device__ __forceinline__ void sum_any_one(T* const* s_tab, size_t base, int N, T* out, float scale,
+template <typename T, int VEC, int POL, typename TO = T>
+__device__ __forceinline__ void sum_any_one(T* const* s_tab, size_t base, int N, TO* out, float scale,
                                             size_t v, float zterm) {
   typedef typename Raw<T, VEC>::type R;
+  typedef typename Raw<TO, VEC>::type RO;
   float a[VEC];
   for (int j0 = 0; j0 < N; j0 += 8) {
     R raw[8];
@@ -247,20 +250,20 @@ __device__ __forceinline__ void sum_any_one(T* const* s_tab, size_t base, int N,
   }
 #pragma unroll
   for (int e = 0; e < VEC; ++e) a[e] = (a[e] + zterm) * scale;
-  st<POL>(reinterpret_cast<R*>(out) + v, narrow<R, VEC>(a));
+  st<POL>(reinterpret_cast<RO*>(out) + v, narrow<RO, VEC>(a));
 }
 
-template <typename T, int VEC, int POL>
-__device__ __forceinline__ void sum_any_range(T* const* s_tab, size_t base, int N, T* out, float scale,
+template <typename T, int VEC, int POL, typename TO = T>
+__device__ __forceinline__ void sum_any_range(T* const* s_tab, size_t base, int N, TO* out, float scale,
                                               size_t len, unsigned bx, unsigned gx, float zterm) {
   const size_t n_vec = len / VEC;
   for (size_t v = static_cast<size_t>(bx) * kThreads + threadIdx.x; v < n_vec;
        v += static_cast<size_t>(gx) * kThreads)
-    sum_any_one<T, VEC, POL>(s_tab, base, N, out, scale, v, zterm);
+    sum_any_one<T, VEC, POL, TO>(s_tab, base, N, out, scale, v, zterm);
   if constexpr (VEC > 1) {
     if (bx == 0) {
       const size_t e = n_vec * VEC + threadIdx.x;
-      if (e < len) sum_any_one<T, 1, POL>(s_tab, base, N, out, scale, e, zterm);
+      if (e < len) sum_any_one<T, 1, POL, TO>(s_tab, base, N, out, scale, e, zterm);
     }
   }
 }
@@ -281,14 +284,28 @@ k_reduce_masked(PtrTable live, T* out, float scale, size_t count, float zterm) {
                                                             blockIdx.x, gridDim.x, 0, zterm);
 }
 
-// One-shot masked mean, any N up to 64 (also the element-wise path for unaligned buffers).
-template <typename T, int VEC, int POL>
+// The same with an fp32 result from bf16 inputs: 8-byte loads, 16-byte stores.
+template <int VEC, int N, int U, int POL>
 __global__ void __launch_bounds__(kThreads)
-k_reduce_masked_any(PtrTable live, int N, T* out, float scale, size_t count, float zterm) {
+k_reduce_masked_f32out(PtrTable live, float* out, float scale, size_t count, float zterm) {
+  __shared__ bf16* s_tab[kMaxReplicas];
+  if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<bf16*>(live.p[threadIdx.x]);
+  __syncthreads();
+  bf16* src[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) src[j] = uniform_ptr(s_tab[j]);
+  sum_range_z<bf16, VEC, N, false, 2, U, POL, false, true>(src, nullptr, out, nullptr, scale, count,
+                                                           blockIdx.x, gridDim.x, 0, zterm);
+}
+
+// One-shot masked mean, any N up to 64 (also the element-wise path for unaligned buffers).
+template <typename T, int VEC, int POL, typename TO = T>
+__global__ void __launch_bounds__(kThreads)
+k_reduce_masked_any(PtrTable live, int N, TO* out, float scale, size_t count, float zterm) {
   __shared__ T* s_tab[kMaxReplicas];
   if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<T*>(live.p[threadIdx.x]);
   __syncthreads();
-  sum_any_range<T, VEC, POL>(s_tab, 0, N, out, scale, count, blockIdx.x, gridDim.x, zterm);
+  sum_any_range<T, VEC, POL, TO>(s_tab, 0, N, out, scale, count, blockIdx.x, gridDim.x, zterm);
 }
 
 // Every participant is a zero-gradient one: the mean is +0.0 (all-zero bits in both element types).
@@ -959,16 +976,48 @@ struct ReduceFixed {
   }
 };
 
-template <typename T, int VEC>
+template <typename T, int VEC, typename TO = T>
 struct ReduceAny {
-  const PtrTable& live; int N; size_t count; T* out; float scale; float zterm; hipStream_t stream;
+  const PtrTable& live; int N; size_t count; TO* out; float scale; float zterm; hipStream_t stream;
   template <int POL> hipError_t operator()(unsigned blocks) const {
     const size_t tiles = (count / VEC + kThreads - 1) / kThreads;
     const dim3 grid(grid_x_for(tiles, blocks)), block(kThreads);
-    launch(k_reduce_masked_any<T, VEC, POL>, grid, block, stream, live, N, out, scale, count, zterm);
+    launch(k_reduce_masked_any<T, VEC, POL, TO>, grid, block, stream, live, N, out, scale, count, zterm);
     return hipGetLastError();
   }
 };
+
+// bf16 in, fp32 out: 4 elements per lane and vector (8-byte loads), as many vectors in flight
+// as the wide tiles of the same-type kernel have bytes.
+struct ReduceFixedF32Out {
+  const PtrTable& live; int N; size_t count; float* out; float scale; float zterm; hipStream_t stream;
+  template <int POL> hipError_t operator()(unsigned blocks) const {
+    const int U = unroll_wide(N);
+    const size_t tiles = count / 4 / (static_cast<size_t>(kThreads) * U);
+    const dim3 grid(grid_x_for(tiles, blocks)), block(kThreads);
+    switch (N) {
+#define FTAR_CASE(n)                                                                               \
+  case n:                                                                                          \
+    launch(k_reduce_masked_f32out<4, n, unroll_wide(n), POL>, grid, block, stream, live, out, scale, \
+           count, zterm);                                                                          \
+    break;
+      FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
+      FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
+      FTAR_CASE(14) FTAR_CASE(15) FTAR_CASE(16)
+#undef FTAR_CASE
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
+};
+
+hipError_t reduce_masked_f32out(const PtrTable& live, int N, size_t count, bool vec, float* out,
+                                float scale, float zterm, hipStream_t stream) {
+  const LaunchCfg cfg = reduce_cfg(N, count * sizeof(float));
+  if (vec && N <= 16) return with_policy(cfg, ReduceFixedF32Out{live, N, count, out, scale, zterm, stream});
+  if (vec) return with_policy(cfg, ReduceAny<bf16, 4, float>{live, N, count, out, scale, zterm, stream});
+  return with_policy(cfg, ReduceAny<bf16, 1, float>{live, N, count, out, scale, zterm, stream});
+}
 
 template <typename T, int VECW>
 hipError_t reduce_masked_typed(const PtrTable& live, int N, size_t count, bool vec, void* out,
@@ -1125,11 +1174,12 @@ struct RingPersistent {
 // ---- exported launchers ----------------------------------------------------
 
 hipError_t launch_reduce_masked(const PtrTable& live, int n_src, size_t count, ftar_dtype_t dtype,
-                                bool vec, void* out, float scale, bool zero_participants,
-                                hipStream_t stream) {
+                                ftar_dtype_t out_dtype, bool vec, void* out, float scale,
+                                bool zero_participants, hipStream_t stream) {
+  if (out_dtype != dtype && !(dtype == FTAR_BF16 && out_dtype == FTAR_F32)) return hipErrorInvalidValue;
   if (n_src == 0) {  // nothing to read; bf16 buffers are only 2-byte aligned: head/tail by halves
     if (!zero_participants) return hipErrorInvalidValue;
-    const size_t bytes = count * (dtype == FTAR_F32 ? 4 : 2);
+    const size_t bytes = count * (out_dtype == FTAR_F32 ? 4 : 2);
     char* o = static_cast<char*>(out);
     uint16_t *head = nullptr, *odd = nullptr;
     size_t left = bytes;
@@ -1146,6 +1196,8 @@ hipError_t launch_reduce_masked(const PtrTable& live, int n_src, size_t count, f
     return hipGetLastError();
   }
   const float zterm = zero_participants ? 0.0f : -0.0f;
+  if (out_dtype != dtype)
+    return reduce_masked_f32out(live, n_src, count, vec, static_cast<float*>(out), scale, zterm, stream);
   if (dtype == FTAR_F32)
     return reduce_masked_typed<float, 4>(live, n_src, count, vec, out, scale, zterm, stream);
   return reduce_masked_typed<bf16, 8>(live, n_src, count, vec, out, scale, zterm, stream);

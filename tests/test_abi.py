@@ -81,3 +81,22 @@ def test_oracle_is_not_reachable_from_the_product(B):
     osrc = open(os.path.join(ROOT, "oracle", "ftar_oracle.py")).read() + \
         open(os.path.join(ROOT, "oracle", "ftar_oracle.cpp")).read()
     assert "paper_2602_00277_amd" not in osrc and "ftar.h" not in osrc and "libftar.so" not in osrc
+
+
+def test_lr_factors_match_the_oracle(oracle):
+    # host-only call: no GPU needed
+    import ctypes
+    from paper_2602_00277_amd import binding as B
+    L = B.lib()
+    for n, live, zmask in [(8, 0xFF, 0), (16, 0x01FF, 0), (16, 0x00FF, 0x000F), (7, 0b1010101, 0b0000100),
+                           (64, (1 << 64) - 1, 1 << 63), (3, 0b011, 0b011)]:
+        plan = L.ftar_plan(n, live, 1000, 10)
+        assert plan
+        assert L.ftar_plan_set_zero_mask(plan, zmask, 0) == 0
+        lin, root = ctypes.c_float(), ctypes.c_float()
+        assert L.ftar_plan_lr_factors(plan, ctypes.byref(lin), ctypes.byref(root)) == 0
+        want_lin, want_root = oracle.lr_factors(n, live, zmask)
+        assert lin.value == float(want_lin) and root.value == float(want_root), (n, hex(live), hex(zmask))
+        assert L.ftar_plan_lr_factors(plan, None, None) == 0
+        L.ftar_plan_destroy(plan)
+    assert L.ftar_plan_lr_factors(None, None, None) == B.FTAR_ERR_INVALID_ARG

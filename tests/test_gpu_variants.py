@@ -1,0 +1,125 @@
+"""GPU: delivery variants - the sum of paper section 4.1 instead of the mean, an fp32 result from
+bf16 inputs - and the learning-rate factors of section 6.2.  Bit-exact against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import BF16, F32, assert_same, code, host, rand_bufs, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2602_00277_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.mark.parametrize("n_live", list(range(1, 18)) + [20])
+@pytest.mark.parametrize("sum_only", [False, True], ids=["mean", "sum"])
+def test_f32_result_from_bf16_inputs(B, oracle, n_live, sum_only):
+    n = n_live + 2
+    live = ((1 << n) - 1) & ~0b1010 if n > 3 else (1 << n_live) - 1
+    n = max(n, live.bit_length())
+    count = 256 * 4 * 8 * 3 + 4 * 37 + 3          # several tiles of every unroll, a vector tail, an element tail
+    say("bf16 -> f32", n_live, "sum" if sum_only else "mean")
+    bufs = rand_bufs(n, count, torch.bfloat16, seed=60 + n_live, dist="student_t3", mask=live)
+    assert bin(live).count("1") == n_live
+    out = torch.empty(count, dtype=torch.float32, device="cuda")
+    B.ftar_reduce_masked_ex(bufs, live, out, op=B.FTAR_SUM if sum_only else B.FTAR_MEAN)
+    torch.cuda.synchronize()
+    want = oracle.reduce_masked_ex([host(b) for b in bufs], live, BF16, out_dtype=F32, sum_only=sum_only)
+    assert_same(host(out), want)
+
+
+@pytest.mark.parametrize("in_dtype,out_dtype", [(torch.float32, torch.float32), (torch.bfloat16, torch.bfloat16),
+                                                (torch.bfloat16, torch.float32)], ids=["f32", "bf16", "bf16-f32"])
+def test_every_option_together(B, oracle, in_dtype, out_dtype):
+    n, live, count = 6, 0b110111, 10000 + 5
+    bufs = rand_bufs(n, count, in_dtype, seed=61, mask=live)
+    for b in bufs:
+        b[:4] = -0.0
+    out = torch.empty(count, dtype=out_dtype, device="cuda")
+    for zmask in (0, 0b000100, 0b110001, live):
+        for contributors_only in (False, True):
+            for sum_only in (False, True):
+                if contributors_only and zmask == live:
+                    continue
+                say("reduce_masked_ex", in_dtype, out_dtype, bin(zmask), contributors_only, sum_only)
+                work = [None if (zmask >> r) & 1 else b for r, b in enumerate(bufs)]
+                B.ftar_reduce_masked_ex(work, live, out, zero_mask=zmask, contributors_only=contributors_only,
+                                        op=B.FTAR_SUM if sum_only else B.FTAR_MEAN)
+                torch.cuda.synchronize()
+                want = oracle.reduce_masked_ex([host(b) for b in work], live, code(in_dtype), code(out_dtype), zmask,
+                                               contributors_only, sum_only, count=count)
+                assert_same(host(out), want, "zmask %s co %s sum %s" % (bin(zmask), contributors_only, sum_only))
+
+
+def test_unaligned_buffers_take_the_element_path(B, oracle):
+    n, live, count = 3, 0b111, 5001
+    store = rand_bufs(n, count + 8, torch.bfloat16, seed=62)
+    bufs = [s[1:1 + count] for s in store]        # 2-byte aligned only
+    out_store = torch.empty(count + 4, dtype=torch.float32, device="cuda")
+    out = out_store[1:1 + count]
+    say("bf16 -> f32 unaligned")
+    B.ftar_reduce_masked_ex(bufs, live, out, op=B.FTAR_SUM)
+    torch.cuda.synchronize()
+    want = oracle.reduce_masked_ex([host(b) for b in bufs], live, BF16, out_dtype=F32, sum_only=True)
+    assert_same(host(out), want)
+
+
+def test_type_pairs_that_are_not_offered(B):
+    bufs = rand_bufs(2, 64, torch.float32, seed=63)
+    out = torch.empty(64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.FtarError) as e:
+        B.ftar_reduce_masked_ex(bufs, 0b11, out)
+    assert e.value.status == B.FTAR_ERR_INVALID_ARG
+    out = torch.empty(64, dtype=torch.float32, device="cuda")
+    with pytest.raises(B.FtarError) as e:
+        B.ftar_reduce_masked_ex(bufs, 0b11, out, op=2)
+    assert e.value.status == B.FTAR_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("n,live,zmask", [(2, 0b11, 0), (3, 0b111, 0), (8, 0b11110111, 0), (8, 0xFF, 0b00100100),
+                                          (16, 0xFFFF, 0), (18, (1 << 18) - 1, 0)])
+def test_ring_paths_deliver_the_sum(B, oracle, dtype, n, live, zmask):
+    N = bin(live).count("1")
+    chunk = 256
+    count = N * chunk * 13 + 101
+    say("ring sum", dtype, n, hex(live), hex(zmask))
+    orig_t = rand_bufs(n, count, dtype, seed=n + 70, dist="student_t3", mask=live)
+    orig = [host(b) for b in orig_t]
+    zero = np.zeros(count, dtype=orig[[r for r in range(n) if (live >> r) & 1][0]].dtype)
+    with_zeros = [zero if (zmask >> r) & 1 else b for r, b in enumerate(orig)]
+    want = oracle.ring_closed_form(with_zeros, live, count, chunk, code(dtype), sum_only=True)
+    plan = B.ftar_plan(n, live, count, chunk, dtype)
+    B.ftar_plan_set_zero_mask(plan, zmask, True)     # the divisor policy must not matter for a sum
+    B.ftar_plan_set_op(plan, B.FTAR_SUM)
+    assert plan.scale == 1.0
+    acc = torch.empty(count, dtype=torch.float32, device="cuda")
+    ctrl = B.ftar_ctrl_create()
+    for name in ("steps", "onepass", "persistent"):
+        bufs = [b.clone() for b in orig_t]
+        for r in range(n):
+            if (zmask >> r) & 1:
+                bufs[r].fill_(float("nan"))
+        if name == "steps":
+            B.ring_allreduce(plan, bufs, acc)
+        elif name == "onepass":
+            B.ftar_allreduce_onepass(plan, bufs)
+        else:
+            B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=5, timeout_us=5_000_000)
+            ctrl.release(plan.n_slots)
+        torch.cuda.synchronize()
+        for r in range(n):
+            assert_same(host(bufs[r]), want if (live >> r) & 1 else orig[r], "%s buf %d" % (name, r))
+    # back to the mean with the same plan
+    B.ftar_plan_set_op(plan, B.FTAR_MEAN)
+    B.ftar_plan_set_zero_mask(plan, 0)
+    bufs = [b.clone() for b in orig_t]
+    B.ftar_allreduce_onepass(plan, bufs)
+    torch.cuda.synchronize()
+    first = [r for r in range(n) if (live >> r) & 1][0]
+    assert_same(host(bufs[first]), oracle.ring_closed_form(orig, live, count, chunk, code(dtype)), "mean again")
