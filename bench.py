@@ -129,9 +129,10 @@ def all_configs_report(path, B, W, torch, np):
 
     def add_row(name, what, gbytes, med, mn, ok, cpu_gbs, cpu_note):
         verdict = ("bit-exact" if ok else "MISMATCH") if cpu_note != "-" else ("completed" if ok else "MISMATCH")
-        rows.append("| %s | %s | %.3f | %.1f | %.0f | %.1f | %.0f | %s | %.2f (%s) |" % (
+        cpu = "-" if cpu_note == "-" else "%.2f (%s)" % (cpu_gbs, cpu_note)
+        rows.append("| %s | %s | %.3f | %.1f | %.0f | %.1f | %.0f | %s | %s |" % (
             name, what, gbytes, med * 1e6, gbytes / med, 100 * gbytes / med / HBM_PEAK_GBS,
-            gbytes / mn, verdict, cpu_gbs, cpu_note))
+            gbytes / mn, verdict, cpu))
         print(rows[-1], file=sys.stderr, flush=True)
 
     cfgs = W.configs()
@@ -156,6 +157,32 @@ def all_configs_report(path, B, W, torch, np):
         med, mn = time_schedule(lambda: B.ftar_reduce_masked(bufs, w.live_mask, out), 20)
         add_row(w.name, "ftar_reduce_masked, N=%d" % N, gb, med, mn, ok,
                 (N + 1) * w.elem_bytes * cpu_elems / cpu_s / 1e9, "%d elems" % cpu_elems)
+        if idx == 1:
+            # the same buffers through the delivery variants of the one-shot reduce
+            zmask = 1 << 5
+            out32 = torch.empty(w.count, dtype=torch.float32, device=dev)
+            for what, kw, o, per_elem in (
+                    ("replica 5 a zero-gradient participant (never read), divisor 7", dict(zero_mask=zmask), out,
+                     (N - 1 + 1) * w.elem_bytes),
+                    ("sum instead of mean", dict(op=B.FTAR_SUM), out, (N + 1) * w.elem_bytes),
+                    ("fp32 mean from the bf16 inputs", dict(), out32, N * w.elem_bytes + 4)):
+                B.ftar_reduce_masked_ex(bufs, w.live_mask, o, **kw)
+                torch.cuda.synchronize()
+                ok, cpu_s, cpu_elems = True, 0.0, 0
+                for st in starts_for(w.count, [], w.seed + 1):
+                    hb = [None if not (w.live_mask >> r) & 1 else W.to_numpy_bits(b[st:st + SLAB])
+                          for r, b in enumerate(bufs)]
+                    t0 = time.perf_counter()
+                    want = oracle.reduce_masked_ex(hb, w.live_mask, code(w.dtype), code(o.dtype),
+                                                   kw.get("zero_mask", 0), False, kw.get("op", 0) == B.FTAR_SUM)
+                    cpu_s += time.perf_counter() - t0
+                    cpu_elems += want.size
+                    ok = ok and same(W.to_numpy_bits(o[st:st + SLAB]), want)
+                gbv = per_elem * w.count / 1e9
+                med, mn = time_schedule(lambda: B.ftar_reduce_masked_ex(bufs, w.live_mask, o, **kw), 20)
+                add_row(w.name, "ftar_reduce_masked_ex: " + what, gbv, med, mn, ok,
+                        per_elem * cpu_elems / cpu_s / 1e9, "%d elems" % cpu_elems)
+            del out32
         del bufs, out
         torch.cuda.empty_cache()
     # ---- ring: cfg 3a (clean 16-ring) and 3b (5 steps, replica 9 leaves, re-plan) ------
