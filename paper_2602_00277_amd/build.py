@@ -12,10 +12,11 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libftar.so")
 
-SOURCES = ["ftar_kernels.hip", "ftar_api.cpp"]
+SOURCES = ["ftar_reduce.hip", "ftar_ring.hip", "ftar_persistent.hip", "ftar_api.cpp"]
+HEADERS = ["ftar_internal.h", "ftar_device.h"]
 
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-ffp-contract=off",                      # no fused multiply-add: additions and the scale stay separate roundings
     "-fno-gpu-flush-denormals-to-zero",            # fp32 denormals are kept, as on the host
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -31,16 +32,29 @@ def stale():
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, "ftar_internal.h"), os.path.join(ROOT, "include", "ftar.h")]
+    deps = sources() + [os.path.join(CSRC, h) for h in HEADERS] + [os.path.join(ROOT, "include", "ftar.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 
 def build(verbose=True):
+    """Compiles every source to an object file (all at once: the files are independent) and links."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB] + sources()
+    objdir = os.path.join(PKG, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    jobs = []
+    for src in sources():
+        obj = os.path.join(objdir, os.path.basename(src) + ".o")
+        cmd = [hipcc] + FLAGS + ["-x", "hip", "-c", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", obj, src]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        jobs.append((cmd, obj, subprocess.Popen(cmd)))
+    failed = [cmd for cmd, _, p in jobs if p.wait() != 0]
+    if failed:
+        raise subprocess.CalledProcessError(1, failed[0])
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + [obj for _, obj, _ in jobs]
     if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+        print(" ".join(link), flush=True)
+    subprocess.run(link, check=True)
     return LIB
 
 

@@ -1,5 +1,5 @@
-// Internal interface between the host API (ftar_api.cpp, ftar_plan.cpp) and the
-// kernel launchers (ftar_kernels.hip).  Not installed; the public surface is
+// Internal interface between the host API (ftar_api.cpp) and the kernel launchers
+// (ftar_reduce.hip, ftar_ring.hip, ftar_persistent.hip).  Not installed; the public surface is
 // include/ftar.h.
 #ifndef FTAR_INTERNAL_H_
 #define FTAR_INTERNAL_H_

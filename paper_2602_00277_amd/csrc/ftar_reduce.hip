@@ -1,0 +1,287 @@
+// One-shot masked reduction kernels (fixed and runtime number of sources, fp32 result from bf16,
+// per-bucket masks) and their launchers.
+
+#include "ftar_device.h"
+
+namespace ftar {
+namespace {
+
+// ---- kernels -------------------------------------------------------------
+
+// One-shot masked mean over N live buffers (N fixed at compile time, 1..16).
+template <typename T, int VEC, int N, int U, int POL>
+__global__ void __launch_bounds__(kThreads)
+k_reduce_masked(PtrTable live, T* out, float scale, size_t count, float zterm) {
+  __shared__ T* s_tab[kMaxReplicas];
+  if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<T*>(live.p[threadIdx.x]);
+  __syncthreads();
+  T* src[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) src[j] = uniform_ptr(s_tab[j]);
+  sum_range_z<T, VEC, N, false, false, U, POL, false, true>(src, nullptr, nullptr, out, scale, count,
+                                                            blockIdx.x, gridDim.x, 0, zterm);
+}
+
+// The same with an fp32 result from bf16 inputs: 8-byte loads, 16-byte stores.
+template <int VEC, int N, int U, int POL>
+__global__ void __launch_bounds__(kThreads)
+k_reduce_masked_f32out(PtrTable live, float* out, float scale, size_t count, float zterm) {
+  __shared__ bf16* s_tab[kMaxReplicas];
+  if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<bf16*>(live.p[threadIdx.x]);
+  __syncthreads();
+  bf16* src[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) src[j] = uniform_ptr(s_tab[j]);
+  sum_range_z<bf16, VEC, N, false, 2, U, POL, false, true>(src, nullptr, out, nullptr, scale, count,
+                                                           blockIdx.x, gridDim.x, 0, zterm);
+}
+
+// One-shot masked mean, any N up to 64 (also the element-wise path for unaligned buffers).
+template <typename T, int VEC, int POL, typename TO = T>
+__global__ void __launch_bounds__(kThreads)
+k_reduce_masked_any(PtrTable live, int N, TO* out, float scale, size_t count, float zterm) {
+  __shared__ T* s_tab[kMaxReplicas];
+  if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<T*>(live.p[threadIdx.x]);
+  __syncthreads();
+  sum_any_range<T, VEC, POL, TO>(s_tab, 0, N, out, scale, count, blockIdx.x, gridDim.x, zterm);
+}
+
+// Every participant is a zero-gradient one: the mean is +0.0 (all-zero bits in both element types).
+__global__ void __launch_bounds__(kThreads)
+k_fill_zero(uint16_t* head16, uint32_t* out32, size_t n32, uint16_t* tail16) {
+  for (size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x; i < n32;
+       i += static_cast<size_t>(gridDim.x) * kThreads)
+    out32[i] = 0u;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (head16 != nullptr) *head16 = 0;
+    if (tail16 != nullptr) *tail16 = 0;
+  }
+}
+
+constexpr int kBucketUnroll = 4;  // vectors per lane in one tile of the bucketed kernel
+
+template <typename T, int VEC, int N, int POL>
+__device__ __forceinline__ void bucket_tile_n(T* const* s_tab, T* out, float scale, size_t begin,
+                                              size_t rem) {
+  constexpr int UN = unroll_narrow(N) < kBucketUnroll ? unroll_narrow(N) : kBucketUnroll;
+  T* src[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) src[j] = uniform_ptr(s_tab[j]) + begin;
+  if (rem >= static_cast<size_t>(kThreads) * kBucketUnroll * VEC) {
+#pragma unroll
+    for (int it = 0; it < kBucketUnroll / UN; ++it)
+      sum_tile<T, VEC, N, false, false, UN, POL>(src, nullptr, nullptr, out + begin, scale,
+                                                 static_cast<size_t>(it) * kThreads * UN + threadIdx.x);
+  } else {
+    sum_range<T, VEC, N, false, false, 1, POL>(src, nullptr, nullptr, out + begin, scale, rem, 0u, 1u);
+  }
+}
+
+// Masked mean with one live mask per bucket.  When a block's next tile lies in another bucket it
+// re-compacts that bucket's mask into the LDS pointer table (lane r places replica r at the rank
+// of its bit) and switches to the loop specialised for that bucket's N.
+template <typename T, int VEC, int POL>
+__global__ void __launch_bounds__(kThreads)
+k_reduce_bucketed(PtrTable all, int n_replicas, BucketTable masks, ScaleTable scales,
+                  size_t first_elem, size_t bucket_elems, size_t last_len, int n_buckets,
+                  size_t tiles_per_bucket, size_t total_tiles, T* out) {
+  // last_len = length of this launch's last bucket; tiles_per_bucket = ceil(bucket_elems / tile);
+  // total_tiles = (n_buckets-1)*tiles_per_bucket + ceil(last_len / tile): all computed on the host.
+  __shared__ T* s_tab[kMaxReplicas];
+  constexpr size_t kTileElems = static_cast<size_t>(kThreads) * kBucketUnroll * VEC;
+  int cur = -1, N = 0;
+  float scale = 0.0f;
+  for (size_t g = blockIdx.x; g < total_tiles; g += gridDim.x) {
+    const int b = static_cast<int>(g / tiles_per_bucket);
+    const size_t in_bucket = (g - b * tiles_per_bucket) * kTileElems;  // offset of the tile in its bucket
+    const size_t begin = first_elem + b * bucket_elems + in_bucket;
+    const size_t rem = (b == n_buckets - 1 ? last_len : bucket_elems) - in_bucket;
+    if (b != cur) {  // same for every lane of the block
+      __syncthreads();                 // nobody still reads the previous bucket's table
+      const unsigned long long mask = masks.mask[b];
+      const unsigned r = threadIdx.x;
+      if (r < static_cast<unsigned>(n_replicas) && ((mask >> r) & 1ull))
+        s_tab[__popcll(mask & ((1ull << r) - 1ull))] = static_cast<T*>(all.p[r]);
+      __syncthreads();
+      cur = b;
+      N = __popcll(mask);
+      scale = scales.s[N];
+    }
+    bool done = false;
+    if constexpr (VEC > 1) {
+      done = true;
+      switch (N) {
+#define FTAR_CASE(n) case n: bucket_tile_n<T, VEC, n, POL>(s_tab, out, scale, begin, rem); break;
+        FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
+        FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
+        FTAR_CASE(14) FTAR_CASE(15) FTAR_CASE(16)
+#undef FTAR_CASE
+        default: done = false; break;
+      }
+    }
+    if (!done) {
+      if (rem >= kTileElems) sum_any_range<T, VEC, POL>(s_tab, begin, N, out + begin, scale, kTileElems, 0u, 1u, -0.0f);
+      else sum_any_range<T, VEC, POL>(s_tab, begin, N, out + begin, scale, rem, 0u, 1u, -0.0f);
+    }
+  }
+}
+
+// Tuning flag bit 5 selects the wide tiles for the one-shot reduce (default: narrow).
+bool wide_tiles() { return (current_tuning().flags & 0x20) != 0; }
+
+template <typename T, int VEC>
+struct ReduceFixed {
+  const PtrTable& live; int N; size_t count; T* out; float scale; float zterm; hipStream_t stream;
+  template <int POL> hipError_t operator()(unsigned blocks) const {
+    const bool wide = wide_tiles();
+    const int U = wide ? unroll_wide(N) : unroll_narrow(N);
+    const size_t tiles = count / VEC / (static_cast<size_t>(kThreads) * U);
+    const dim3 grid(grid_x_for(tiles, blocks)), block(kThreads);
+    switch (N) {
+#define FTAR_CASE(n)                                                                              \
+  case n:                                                                                         \
+    if (wide)                                                                                     \
+      launch(k_reduce_masked<T, VEC, n, unroll_wide(n), POL>, grid, block, stream, live, out, scale, \
+                                                                                  count, zterm);  \
+    else                                                                                          \
+      launch(k_reduce_masked<T, VEC, n, unroll_narrow(n), POL>, grid, block, stream, live, out,    \
+                                                                                    scale, count, zterm); \
+    break;
+      FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
+      FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
+      FTAR_CASE(14) FTAR_CASE(15) FTAR_CASE(16)
+#undef FTAR_CASE
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
+};
+
+template <typename T, int VEC, typename TO = T>
+struct ReduceAny {
+  const PtrTable& live; int N; size_t count; TO* out; float scale; float zterm; hipStream_t stream;
+  template <int POL> hipError_t operator()(unsigned blocks) const {
+    const size_t tiles = (count / VEC + kThreads - 1) / kThreads;
+    const dim3 grid(grid_x_for(tiles, blocks)), block(kThreads);
+    launch(k_reduce_masked_any<T, VEC, POL, TO>, grid, block, stream, live, N, out, scale, count, zterm);
+    return hipGetLastError();
+  }
+};
+
+// bf16 in, fp32 out: 4 elements per lane and vector (8-byte loads), as many vectors in flight
+// as the wide tiles of the same-type kernel have bytes.
+struct ReduceFixedF32Out {
+  const PtrTable& live; int N; size_t count; float* out; float scale; float zterm; hipStream_t stream;
+  template <int POL> hipError_t operator()(unsigned blocks) const {
+    const int U = unroll_wide(N);
+    const size_t tiles = count / 4 / (static_cast<size_t>(kThreads) * U);
+    const dim3 grid(grid_x_for(tiles, blocks)), block(kThreads);
+    switch (N) {
+#define FTAR_CASE(n)                                                                               \
+  case n:                                                                                          \
+    launch(k_reduce_masked_f32out<4, n, unroll_wide(n), POL>, grid, block, stream, live, out, scale, \
+           count, zterm);                                                                          \
+    break;
+      FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
+      FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
+      FTAR_CASE(14) FTAR_CASE(15) FTAR_CASE(16)
+#undef FTAR_CASE
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
+};
+
+hipError_t reduce_masked_f32out(const PtrTable& live, int N, size_t count, bool vec, float* out,
+                                float scale, float zterm, hipStream_t stream) {
+  const LaunchCfg cfg = reduce_cfg(N, count * sizeof(float));
+  if (vec && N <= 16) return with_policy(cfg, ReduceFixedF32Out{live, N, count, out, scale, zterm, stream});
+  if (vec) return with_policy(cfg, ReduceAny<bf16, 4, float>{live, N, count, out, scale, zterm, stream});
+  return with_policy(cfg, ReduceAny<bf16, 1, float>{live, N, count, out, scale, zterm, stream});
+}
+
+template <typename T, int VECW>
+hipError_t reduce_masked_typed(const PtrTable& live, int N, size_t count, bool vec, void* out,
+                               float scale, float zterm, hipStream_t stream) {
+  T* o = static_cast<T*>(out);
+  const LaunchCfg cfg = reduce_cfg(N, count * sizeof(T));
+  if (vec && N <= 16) return with_policy(cfg, ReduceFixed<T, VECW>{live, N, count, o, scale, zterm, stream});
+  if (vec) return with_policy(cfg, ReduceAny<T, VECW>{live, N, count, o, scale, zterm, stream});
+  return with_policy(cfg, ReduceAny<T, 1>{live, N, count, o, scale, zterm, stream});
+}
+
+template <typename T, int VEC>
+struct Bucketed {
+  const PtrTable& all; int n_replicas; const BucketTable& masks; int n_buckets; size_t first_elem;
+  size_t bucket_elems; size_t count; const ScaleTable& scales; T* out; hipStream_t stream;
+  template <int POL> hipError_t operator()(unsigned blocks) const {
+    const size_t tile_elems = static_cast<size_t>(kThreads) * kBucketUnroll * VEC;
+    const size_t tiles_per_bucket = (bucket_elems + tile_elems - 1) / tile_elems;
+    const size_t last_begin = first_elem + static_cast<size_t>(n_buckets - 1) * bucket_elems;
+    const size_t last_len = count - last_begin < bucket_elems ? count - last_begin : bucket_elems;
+    const size_t tiles = static_cast<size_t>(n_buckets - 1) * tiles_per_bucket +
+                         (last_len + tile_elems - 1) / tile_elems;
+    const dim3 grid(grid_x_for(tiles, blocks)), block(kThreads);
+    launch(k_reduce_bucketed<T, VEC, POL>, grid, block, stream, all, n_replicas, masks, scales,
+                                                               first_elem, bucket_elems, last_len,
+                                                               n_buckets, tiles_per_bucket, tiles, out);
+    return hipGetLastError();
+  }
+};
+
+template <typename T, int VECW>
+hipError_t bucketed_typed(const PtrTable& all, int n_replicas, const BucketTable& masks,
+                          int n_buckets, size_t first_elem, size_t bucket_elems, size_t count,
+                          const ScaleTable& scales, bool vec, void* out, hipStream_t stream) {
+  T* o = static_cast<T*>(out);
+  if (vec)
+    return with_policy(reduce_cfg(n_replicas, (count - first_elem) * sizeof(T)), Bucketed<T, VECW>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
+                                         count, scales, o, stream});
+  return with_policy(reduce_cfg(n_replicas, (count - first_elem) * sizeof(T)), Bucketed<T, 1>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
+                                    count, scales, o, stream});
+}
+
+}  // namespace
+
+hipError_t launch_reduce_masked(const PtrTable& live, int n_src, size_t count, ftar_dtype_t dtype,
+                                ftar_dtype_t out_dtype, bool vec, void* out, float scale,
+                                bool zero_participants, hipStream_t stream) {
+  if (out_dtype != dtype && !(dtype == FTAR_BF16 && out_dtype == FTAR_F32)) return hipErrorInvalidValue;
+  if (n_src == 0) {  // nothing to read; bf16 buffers are only 2-byte aligned: head/tail by halves
+    if (!zero_participants) return hipErrorInvalidValue;
+    const size_t bytes = count * (out_dtype == FTAR_F32 ? 4 : 2);
+    char* o = static_cast<char*>(out);
+    uint16_t *head = nullptr, *odd = nullptr;
+    size_t left = bytes;
+    if (reinterpret_cast<uintptr_t>(o) % 4 != 0) {  // 2-byte aligned bf16: first half alone
+      head = reinterpret_cast<uint16_t*>(o);
+      o += 2;
+      left -= 2;
+    }
+    const size_t n32 = left / 4;
+    if (left % 4) odd = reinterpret_cast<uint16_t*>(o + n32 * 4);
+    const unsigned blocks = static_cast<unsigned>(std::min<size_t>((n32 + kThreads - 1) / kThreads + 1,
+                                                                  static_cast<size_t>(device_cu_count()) * 8));
+    launch(k_fill_zero, dim3(blocks), dim3(kThreads), stream, head, reinterpret_cast<uint32_t*>(o), n32, odd);
+    return hipGetLastError();
+  }
+  const float zterm = zero_participants ? 0.0f : -0.0f;
+  if (out_dtype != dtype)
+    return reduce_masked_f32out(live, n_src, count, vec, static_cast<float*>(out), scale, zterm, stream);
+  if (dtype == FTAR_F32)
+    return reduce_masked_typed<float, 4>(live, n_src, count, vec, out, scale, zterm, stream);
+  return reduce_masked_typed<bf16, 8>(live, n_src, count, vec, out, scale, zterm, stream);
+}
+
+hipError_t launch_reduce_bucketed(const PtrTable& all, int n_replicas, const BucketTable& masks,
+                                  int n_buckets, size_t first_elem, size_t bucket_elems,
+                                  size_t count, const ScaleTable& scales, ftar_dtype_t dtype,
+                                  bool vec, void* out, hipStream_t stream) {
+  if (dtype == FTAR_F32)
+    return bucketed_typed<float, 4>(all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
+                                    count, scales, vec, out, stream);
+  return bucketed_typed<bf16, 8>(all, n_replicas, masks, n_buckets, first_elem, bucket_elems, count,
+                                 scales, vec, out, stream);
+}
+
+}  // namespace ftar

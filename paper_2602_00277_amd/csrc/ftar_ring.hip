@@ -1,0 +1,254 @@
+// Ring all-reduce kernels - one ReduceScatter step, one AllGather step, the whole schedule in one
+// pass - and their launchers.
+
+#include "ftar_device.h"
+
+namespace ftar {
+namespace {
+
+// One ReduceScatter step over all N portions.
+template <typename T, int VEC, int MODE, int U, int POL>
+__global__ void __launch_bounds__(kThreads)
+k_ring_reduce(PtrTable ring, SegTable seg, SegTable tile0, int N, int step, float* acc, float scale,
+              unsigned long long zpos) {
+  __shared__ T* s_tab[kMaxReplicas];
+  __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
+  stage_ring_tables<T>(ring, seg, tile0, N, s_tab, s_seg, s_tile);
+  ring_reduce_pass<T, VEC, MODE, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale, blockIdx.x, gridDim.x, 0,
+                                         zpos);
+}
+
+// One AllGather step over all N portions.
+template <typename T, int VEC, int U, int POL>
+__global__ void __launch_bounds__(kThreads)
+k_ring_allgather(PtrTable ring, SegTable seg, SegTable tile0, int N, int step) {
+  __shared__ T* s_tab[kMaxReplicas];
+  __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
+  stage_ring_tables<T>(ring, seg, tile0, N, s_tab, s_seg, s_tile);
+  ring_allgather_pass<T, VEC, U, POL>(s_tab, s_seg, s_tile, N, step, blockIdx.x, gridDim.x);
+}
+
+// ---- the ring's result in one pass ------------------------------------------------
+// On one device nothing forces the 2N-2 steps to be separate passes over memory: the partial sum
+// of an element can stay in a register while its N contributions are added in the ring's order
+// (portion k: positions k, k+1, ..., k+N-1 mod N), and the rounded mean can be written straight
+// into all N replica buffers.  Same bits as the step schedule, 2*N*E bytes per element instead
+// of 4*N*E + 10*N - 20 (N = 16, bf16: 64 instead of 206).
+template <typename T, int VEC, int N, int U, int POL, bool ZM>
+__device__ __forceinline__ void onepass_tile(T* const (&buf)[N], float scale, size_t v,
+                                             unsigned long long zm) {
+  typedef typename Raw<T, VEC>::type R;
+  R raw[U][N];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+      if (ZM && ((zm >> j) & 1ull)) raw[u][j] = R{};
+      else raw[u][j] = ld<POL>(reinterpret_cast<const R*>(buf[j]) + v + u * kThreads);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    float a[VEC], x[VEC];
+    widen(raw[u][0], a);
+#pragma unroll
+    for (int j = 1; j < N; ++j) {
+      widen(raw[u][j], x);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) a[e] = a[e] + x[e];
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) a[e] = a[e] * scale;
+    const R r = narrow<R, VEC>(a);
+#pragma unroll
+    for (int j = 0; j < N; ++j) st<POL>(reinterpret_cast<R*>(buf[j]) + v + u * kThreads, r);
+  }
+}
+
+// Any N (runtime): loads in groups of 8 in ring order starting at position k, then N stores.
+template <typename T, int VEC, int POL>
+__device__ __forceinline__ void onepass_any_one(T* const* s_tab, int N, int k, size_t base, float scale,
+                                                size_t v, unsigned long long zpos) {
+  typedef typename Raw<T, VEC>::type R;
+  float a[VEC];
+  for (int j0 = 0; j0 < N; j0 += 8) {
+    R raw[8];
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj)
+      if (j0 + jj < N) {
+        const int p = (k + j0 + jj) % N;
+        if ((zpos >> p) & 1ull) raw[jj] = R{};
+        else raw[jj] = ld<POL>(reinterpret_cast<const R*>(uniform_ptr(s_tab[p]) + base) + v);
+      }
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) {
+      if (j0 + jj < N) {
+        float x[VEC];
+        widen(raw[jj], x);
+        if (j0 + jj == 0) {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) a[e] = x[e];
+        } else {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) a[e] = a[e] + x[e];
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) a[e] = a[e] * scale;
+  const R r = narrow<R, VEC>(a);
+  for (int j = 0; j < N; ++j) st<POL>(reinterpret_cast<R*>(uniform_ptr(s_tab[j]) + base) + v, r);
+}
+
+template <typename T, int VEC, int POL>
+__device__ __forceinline__ void onepass_any_range(T* const* s_tab, int N, int k, size_t base, float scale,
+                                                  size_t len, unsigned long long zpos) {
+  const size_t n_vec = len / VEC;
+  for (size_t v = threadIdx.x; v < n_vec; v += kThreads)
+    onepass_any_one<T, VEC, POL>(s_tab, N, k, base, scale, v, zpos);
+  if constexpr (VEC > 1) {
+    const size_t e = n_vec * VEC + threadIdx.x;
+    if (e < len) onepass_any_one<T, 1, POL>(s_tab, N, k, base, scale, e, zpos);
+  }
+}
+
+// NT = compile-time N for the unrolled tile (1..16), or 0: any N through the grouped loop.
+template <typename T, int VEC, int NT, int POL>
+__global__ void __launch_bounds__(kThreads)
+k_ring_onepass(PtrTable ring, SegTable seg, SegTable tile0, int N, float scale, unsigned long long zpos) {
+  __shared__ T* s_tab[kMaxReplicas];
+  __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
+  stage_ring_tables<T>(ring, seg, tile0, N, s_tab, s_seg, s_tile);
+  constexpr int U = NT == 0 ? 1 : unroll_narrow(NT);
+  constexpr size_t kTileElems = static_cast<size_t>(kThreads) * U * VEC;
+  const size_t total = uniform_u64(s_tile[N]);
+  int k = 0;
+  size_t next = uniform_u64(s_tile[1]);
+  for (size_t g = blockIdx.x; g < total; g += gridDim.x) {
+    const RingTile t = ring_tile_of<kTileElems>(g, k, next, s_seg, s_tile);
+    if constexpr (NT > 0) {
+      if (t.rem >= kTileElems) {
+        T* buf[NT];
+        unsigned long long zm = 0;
+#pragma unroll
+        for (int m = 0; m < NT; ++m) {
+          const int p = (t.k + m) % NT;
+          buf[m] = uniform_ptr(s_tab[p]) + t.begin;
+          zm |= ((zpos >> p) & 1ull) << m;
+        }
+        if (zm == 0) onepass_tile<T, VEC, NT, U, POL, false>(buf, scale, threadIdx.x, 0);
+        else onepass_tile<T, VEC, NT, U, POL, true>(buf, scale, threadIdx.x, zm);
+        continue;
+      }
+    }
+    if (t.rem >= kTileElems) onepass_any_range<T, VEC, POL>(s_tab, N, t.k, t.begin, scale, kTileElems, zpos);
+    else onepass_any_range<T, VEC, POL>(s_tab, N, t.k, t.begin, scale, t.rem, zpos);
+  }
+}
+
+template <typename T, int VEC>
+struct RingReduce {
+  RingMode mode; const PtrTable& ring; int N; int step; const SegTable& seg; float* acc; float scale;
+  unsigned long long zpos; hipStream_t stream;
+  template <int MODE, int U, int POL> void go(unsigned blocks) const {
+    const SegTable tiles = ring_tiles(seg, N, VEC, U);
+    const dim3 grid(grid_x_for(tiles.begin[N], blocks)), block(kThreads);
+    launch(k_ring_reduce<T, VEC, MODE, U, POL>, grid, block, stream, ring, seg, tiles, N, step, acc, scale, zpos);
+  }
+  template <int MODE, int POL> void pick_unroll(unsigned blocks) const {
+    const int U = ring_unroll();
+    if (U == 2) go<MODE, 2, POL>(blocks);
+    else if (U == 8) go<MODE, 8, POL>(blocks);
+    else go<MODE, 4, POL>(blocks);
+  }
+  template <int POL> hipError_t operator()(unsigned blocks) const {
+    switch (mode) {
+      case kRsFirst: pick_unroll<kRsFirst, POL>(blocks); break;
+      case kRsMid: pick_unroll<kRsMid, POL>(blocks); break;
+      case kRsLast: pick_unroll<kRsLast, POL>(blocks); break;
+      case kRsOnly: pick_unroll<kRsOnly, POL>(blocks); break;
+    }
+    return hipGetLastError();
+  }
+};
+
+template <typename T, int VEC>
+struct RingAllgather {
+  const PtrTable& ring; int N; int step; const SegTable& seg; hipStream_t stream;
+  template <int U, int POL> void go(unsigned blocks) const {
+    const SegTable tiles = ring_tiles(seg, N, VEC, U);
+    const dim3 grid(grid_x_for(tiles.begin[N], blocks)), block(kThreads);
+    launch(k_ring_allgather<T, VEC, U, POL>, grid, block, stream, ring, seg, tiles, N, step);
+  }
+  template <int POL> hipError_t operator()(unsigned blocks) const {
+    const int U = ring_unroll();
+    if (U == 2) go<2, POL>(blocks);
+    else if (U == 8) go<8, POL>(blocks);
+    else go<4, POL>(blocks);
+    return hipGetLastError();
+  }
+};
+
+template <typename T, int VEC>
+struct RingOnepass {
+  const PtrTable& ring; int N; const SegTable& seg; float scale; unsigned long long zpos; hipStream_t stream;
+  template <int POL> hipError_t operator()(unsigned blocks) const {
+    const int U = (VEC == 1 || N > 16) ? 1 : unroll_narrow(N);  // must match the kernel's tile
+    const SegTable tiles = ring_tiles(seg, N, VEC, U);
+    const dim3 grid(grid_x_for(tiles.begin[N], blocks)), block(kThreads);
+    if (VEC == 1 || N > 16) {
+      launch(k_ring_onepass<T, VEC, 0, POL>, grid, block, stream, ring, seg, tiles, N, scale, zpos);
+      return hipGetLastError();
+    }
+    switch (N) {
+#define FTAR_CASE(n) \
+  case n: launch(k_ring_onepass<T, VEC, (VEC == 1 ? 0 : n), POL>, grid, block, stream, ring, seg, tiles, N, scale, zpos); break;
+      FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7) FTAR_CASE(8)
+      FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13) FTAR_CASE(14)
+      FTAR_CASE(15) FTAR_CASE(16)
+#undef FTAR_CASE
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
+};
+
+}  // namespace
+
+hipError_t launch_ring_reduce(RingMode mode, const PtrTable& ring, int n_live, int step,
+                              const SegTable& seg, ftar_dtype_t dtype, bool vec, float* acc,
+                              float scale, unsigned long long zpos, hipStream_t stream) {
+  if (dtype == FTAR_F32) {
+    if (vec) return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<float, 4>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
+    return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<float, 1>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
+  }
+  if (vec) return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<bf16, 4>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
+  return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<bf16, 1>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
+}
+
+hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, const SegTable& seg,
+                                 ftar_dtype_t dtype, bool vec, hipStream_t stream) {
+  if (dtype == FTAR_F32) {
+    if (vec) return with_policy(ring_allgather_cfg(seg.begin[n_live], 4), RingAllgather<float, 4>{ring, n_live, step, seg, stream});
+    return with_policy(ring_allgather_cfg(seg.begin[n_live], 4), RingAllgather<float, 1>{ring, n_live, step, seg, stream});
+  }
+  if (vec) return with_policy(ring_allgather_cfg(seg.begin[n_live], 2), RingAllgather<bf16, 8>{ring, n_live, step, seg, stream});
+  return with_policy(ring_allgather_cfg(seg.begin[n_live], 2), RingAllgather<bf16, 1>{ring, n_live, step, seg, stream});
+}
+
+hipError_t launch_ring_onepass(const PtrTable& ring, int n_live, const SegTable& seg,
+                               ftar_dtype_t dtype, bool vec, float scale, unsigned long long zpos,
+                               hipStream_t stream) {
+  // N reads and N writes per element, as many write streams as read streams: non-temporal
+  // stores and one workgroup per CU are best at every size measured
+  const LaunchCfg cfg = launch_cfg(1, 3);
+  if (dtype == FTAR_F32) {
+    if (vec) return with_policy(cfg, RingOnepass<float, 4>{ring, n_live, seg, scale, zpos, stream});
+    return with_policy(cfg, RingOnepass<float, 1>{ring, n_live, seg, scale, zpos, stream});
+  }
+  if (vec) return with_policy(cfg, RingOnepass<bf16, 8>{ring, n_live, seg, scale, zpos, stream});
+  return with_policy(cfg, RingOnepass<bf16, 1>{ring, n_live, seg, scale, zpos, stream});
+}
+
+}  // namespace ftar
