@@ -117,7 +117,8 @@ ftar_status_t ftar_plan_segment(const ftar_plan_t* plan, int k, size_t* begin, s
  * bit-identical to running with buffers that hold +0.0 everywhere.
  * The divisor is N (a catching-up replica is a participant); with contributors_only != 0 it is
  * N - N_zero.  FTAR_ERR_BAD_MASK if zero_mask has a bit outside live_mask; FTAR_ERR_NO_LIVE if
- * contributors_only leaves nobody.
+ * contributors_only leaves nobody, or (plan only) if the single live replica is a zero participant:
+ * a ring of one has no steps that could deliver its +0.0.
  * ftar_plan_set_zero_mask applies to every ring call made with the plan afterwards (step calls,
  * one-pass, persistent); ftar_reduce_masked_zero is the one-shot form, where a zero
  * participant's entry in bufs may be NULL.

@@ -181,6 +181,8 @@ ftar_status_t ftar_plan_set_zero_mask(ftar_plan_t* plan, uint64_t zero_mask, int
   }
   const int divisor = contributors_only ? plan->n_live - Z : plan->n_live;
   if (divisor <= 0) return fail(FTAR_ERR_NO_LIVE);
+  // a ring of one has no steps, so nothing could write the +0.0 a lone zero participant is owed
+  if (plan->n_live == 1 && Z == 1) return fail(FTAR_ERR_NO_LIVE);
   plan->zero_pos = zpos;
   plan->n_zero = Z;
   plan->contributors_only = contributors_only ? 1 : 0;

@@ -13,11 +13,15 @@ namespace {
 // in-flight partial sums never leave the caches.
 //
 // Element i of acc (and of every replica buffer) is only ever touched by the block that owns
-// the tile holding i, and the tile -> block assignment is the same in every slot, so consecutive
-// slots need no synchronisation between blocks: a block-wide barrier with workgroup-scope
-// release/acquire between two slots is enough (all waves of a block share one CU and its L1).
-// That also lets the AllGather steps copy 16 bytes per lane although the ReduceScatter steps
-// hand each lane 8 bytes of bf16.
+// the tile holding i, and the tile -> block assignment is the same in every slot of partitions
+// of the same length, so consecutive slots need no synchronisation between blocks: a block-wide
+// barrier with workgroup-scope release/acquire between two slots is enough (all waves of a
+// block share one CU and its L1).  That also lets the AllGather steps copy 16 bytes per lane
+// although the ReduceScatter steps hand each lane 8 bytes of bf16.
+// The one exception is a shorter last partition: its portions, and with them its tiles, fall
+// elsewhere in acc, so a block may overwrite partial sums that another block has not consumed
+// yet.  Before its first slot every worker therefore waits until all workers have finished the
+// last ReduceScatter step of the partition before (the last reader of acc): the acc handover.
 //
 // What the blocks do wait for is the CPU.  The grid is n workers plus one relay block, and the
 // relay is the only one that talks to the CPU: it copies the gate word from host-pinned memory
@@ -105,6 +109,7 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
   __shared__ T* s_tab[kMaxReplicas];
   __shared__ unsigned long long s_seg[2][kMaxReplicas + 1], s_tile[2][kMaxReplicas + 1];
   __shared__ unsigned long long s_gate;  // what lane 0 saw: released slots, or a verdict in bits 32..33
+  __shared__ unsigned s_hand;            // verdict of the acc handover wait (0 = go on)
   const unsigned n_workers = gridDim.x - 1;
   if (blockIdx.x == 0) {  // the first block (dispatched first, so always resident) is the relay
     relay_loop(ctrl, mirror, n_workers, max_spins, flags);
@@ -124,6 +129,11 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
   const unsigned n_steps = static_cast<unsigned>(2 * N - 2);
   const unsigned n_slots = geom.n_parts * n_steps;
   unsigned released = 0;  // slots [0, released) are known to be released
+  // acc handover before a shorter last partition (see above); hand_pub = the slot whose end every
+  // worker publishes, hand_slot = the slot that may only start when all have published it
+  const bool handover = N >= 3 && geom.n_parts >= 2 && geom.seg_last.begin[N] != geom.part_elems;
+  const unsigned hand_pub = handover ? (geom.n_parts - 2) * n_steps + static_cast<unsigned>(N - 2) : 0xffffffffu;
+  const unsigned hand_slot = handover ? (geom.n_parts - 1) * n_steps : 0xffffffffu;
   unsigned part = 0, ustep = 0;
   for (unsigned slot = 0; slot < n_slots; ++slot, ++ustep) {
     if (ustep == n_steps) {
@@ -159,6 +169,33 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
       }
       released = static_cast<unsigned>(seen);
     }
+    if (slot == hand_slot) {
+      if (tid == 0) {
+        unsigned verdict = 1;  // timed out unless the loop says otherwise
+        const long long t0 = wall_clock64();
+        for (unsigned long long spin = 0; spin < max_spins; ++spin) {
+          if (dev_load(&mirror->min_slot) > hand_pub) { verdict = 0; break; }
+          if ((dev_load(&mirror->gate) & kGateCancel) != 0) { verdict = 2; break; }
+          const unsigned v = dev_load(&mirror->verdict);
+          if (v != 0) { verdict = v; break; }
+          if (static_cast<unsigned long long>(wall_clock64() - t0) > timeout_ticks) break;
+          __builtin_amdgcn_s_sleep(4);
+        }
+        s_hand = verdict;
+      }
+      __syncthreads();
+      const unsigned verdict = s_hand;
+      if (verdict != 0) {
+        if (tid == 0) {
+          dev_store(&mirror->verdict, verdict);
+          sys_store(&ctrl->blocked_step, static_cast<unsigned long long>(slot));
+          sys_store(&ctrl->status, static_cast<unsigned long long>(verdict));
+          __hip_atomic_fetch_add(&mirror->exited, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        return;
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
     const int step = static_cast<int>(ustep);
     if (step == N - 1) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // first AllGather step: see the block's stores
     const int sel = part + 1 == geom.n_parts ? 1 : 0;
@@ -182,7 +219,8 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
     // every lane only re-reads its own stores, so slots that are already released run back to
     // back.  Reporting is skipped while the next slot is already released: the progress the CPU
     // sees is then a lower bound, exact whenever the kernel waits.
-    const bool report = slot + 1 >= released || slot + 1 == n_slots || (flags & FTAR_PERSIST_ALIGN) != 0;
+    const bool report = slot + 1 >= released || slot + 1 == n_slots || (flags & FTAR_PERSIST_ALIGN) != 0 ||
+                        slot == hand_pub;
     if (report || step == N - 2) {
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       __syncthreads();
@@ -192,7 +230,7 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
     // is what a NIC reading the buffers on the CPU's signal would need (one L2 write-back per
     // block and report: 18 % at 64 Mi elements when every slot is reported).
     if (report && tid == 0) {
-      if (flags & FTAR_PERSIST_PUBLISH)
+      if ((flags & FTAR_PERSIST_PUBLISH) || slot == hand_pub)  // the handover orders this block's reads of acc first
         __hip_atomic_store(&mirror->worker_slot[worker], slot + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
       else
         dev_store(&mirror->worker_slot[worker], slot + 1);

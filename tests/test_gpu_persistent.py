@@ -258,3 +258,30 @@ def test_partitioned_cancel_leaves_earlier_partitions_done_and_later_ones_untouc
         got = host(bufs[r])
         assert_same(got[:2 * part], want[:2 * part], "finished partitions, buf %d" % r)
         assert_same(got[2 * part:], orig[r][2 * part:], "untouched partitions, buf %d" % r)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("workers", [2, 16, 255, 600])
+@pytest.mark.parametrize("part,count,chunk", [(24655, 53150, 1000), (65536, 65536 * 6 + 5000, 256),
+                                              (40000, 40000 * 3 + 39000, 8), (8192, 8192 * 20 + 8, 64)])
+def test_shorter_last_partition_reuses_acc_only_after_everybody_is_done_with_it(B, oracle, dtype, workers, part,
+                                                                                count, chunk):
+    # the last partition's tiles fall elsewhere in acc than those of the partitions before it: the
+    # workers hand acc over (a wait for each other) before its first slot
+    n, mask = 8, 0b11010110
+    say("persistent short last partition", dtype, workers, part, count, chunk)
+    bufs0 = rand_bufs(n, count, dtype, seed=part % 89, dist="student_t3", mask=mask)
+    orig = [host(b) for b in bufs0]
+    want = _partitioned_reference(oracle, orig, n, mask, count, chunk, part, code(dtype))
+    plan = B.ftar_plan(n, mask, count, chunk, dtype)
+    plan.set_partition(part)
+    acc = torch.empty(part, dtype=torch.float32, device="cuda")
+    ctrl = B.ftar_ctrl_create()
+    for rep in range(3):
+        bufs = [b.clone() for b in bufs0]
+        B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=workers, timeout_us=10_000_000)
+        ctrl.release(plan.n_slots)
+        torch.cuda.synchronize()
+        assert ctrl.result() == (B.FTAR_OK, plan.n_slots)
+        for r in range(n):
+            assert_same(host(bufs[r]), want if (mask >> r) & 1 else orig[r], "rep %d buf %d" % (rep, r))
