@@ -44,7 +44,9 @@ def _draw(rng):
         if rng.random() < 0.5:
             part = max(8, part // 8 * 8)
     workers = int(rng.choice([1, 3, 16, 200]))
-    return dict(n=n, live=live, zmask=zmask, contributors_only=contributors_only, sum_only=sum_only,
+    flags = int(rng.choice([0, 0, 1, 2, 3]))
+    release = str(rng.choice(["all", "all", "batches", "each"]))
+    return dict(flags=flags, release=release, n=n, live=live, zmask=zmask, contributors_only=contributors_only, sum_only=sum_only,
                 chunk=chunk, count=count, dtype=dtype, offset=offset, part=part, workers=workers)
 
 
@@ -60,7 +62,25 @@ def _ring_reference(oracle, orig, c, lo, hi):
     return oracle.ring_closed_form_zero(sl, c["live"], c["zmask"], hi - lo, c["chunk"], dt, c["contributors_only"])
 
 
-@pytest.mark.parametrize("seed", range(60))
+def _release(ctrl, n_slots, how, rng):
+    """The CPU side of the gate: everything at once, in random batches, or slot by slot waiting for
+    the reported progress in between (bounded: the kernel's own timeout ends a stuck run)."""
+    import time
+    if how == "all" or n_slots == 0:
+        ctrl.release(n_slots)
+        return
+    done = 0
+    while done < n_slots:
+        done = min(n_slots, done + (1 if how == "each" else int(rng.integers(1, 9))))
+        ctrl.release(done)
+        if how == "each":
+            t0 = time.time()
+            while ctrl.progress() < done and time.time() - t0 < 20:
+                pass
+            assert ctrl.progress() >= done, "progress stuck at %d of %d" % (ctrl.progress(), done)
+
+
+@pytest.mark.parametrize("seed", range(120))
 def test_random_option_draw(B, oracle, seed):
     rng = np.random.default_rng(1000 + seed)
     c = _draw(rng)
@@ -112,11 +132,39 @@ def test_random_option_draw(B, oracle, seed):
                 plan.set_partition(c["part"])
                 ref = np.concatenate([_ring_reference(oracle, orig, c, lo, min(count, lo + c["part"]))
                                       for lo in range(0, count, c["part"])])
-            B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=c["workers"], timeout_us=10_000_000)
-            ctrl.release(plan.n_slots)
+            B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=c["workers"], timeout_us=10_000_000,
+                                   flags=c["flags"])
+            _release(ctrl, plan.n_slots, c["release"], rng)
             torch.cuda.synchronize()
             assert ctrl.result() == (B.FTAR_OK, plan.n_slots), name
         torch.cuda.synchronize()
         for r in range(n):
             assert_same(host(bufs[r]), ref if (live >> r) & 1 else orig[r], "%s buf %d" % (name, r))
     ctrl.destroy()
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_bucketed_draw(B, oracle, seed):
+    rng = np.random.default_rng(5000 + seed)
+    n = int(rng.choice([1, 2, 3, 5, 8, 13, 16, 17, 30]))
+    dtype = torch.bfloat16 if rng.random() < 0.5 else torch.float32
+    bucket = int(rng.choice([1, 7, 8, 100, 1024, 4096, 5000, 50000]))
+    n_buckets = int(rng.integers(1, 40 if bucket >= 100 else 300))
+    count = (n_buckets - 1) * bucket + int(rng.integers(1, bucket + 1))
+    offset = int(rng.choice([0, 0, 1, 8]))
+    masks = []
+    for b in range(n_buckets):
+        m = int(rng.integers(0, 1 << n)) if rng.random() < 0.8 else (1 << n) - 1
+        masks.append(m if m else 1 << (b % n))
+    say("bucketed draw", seed, n, dtype, bucket, n_buckets, count, offset)
+    store = rand_bufs(n, count + 16, dtype, seed=seed)
+    views = [s[offset:offset + count] for s in store]
+    out = torch.empty(count + 16, dtype=dtype, device="cuda")[offset:offset + count]
+    B.ftar_reduce_masked_bucketed(views, masks, bucket, out)
+    torch.cuda.synchronize()
+    got, hv = host(out), [host(v) for v in views]
+    for b, m in enumerate(masks):
+        lo, hi = b * bucket, min(count, (b + 1) * bucket)
+        want = oracle.reduce_masked([np.ascontiguousarray(h[lo:hi]) if (m >> r) & 1 else None
+                                     for r, h in enumerate(hv)], m, code(dtype))
+        assert_same(got[lo:hi], want, "bucket %d mask %s" % (b, hex(m)))

@@ -1,0 +1,77 @@
+"""GPU: the compute calls only enqueue kernels on the caller's stream (no allocation, no memset, no
+synchronisation), so a caller may record them into a HIP graph.  Every replay must give the eager
+result."""
+import pytest
+import torch
+
+from gpu_util import assert_same, code, host, rand_bufs, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2602_00277_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_graph_replays_equal_eager(B, oracle, dtype):
+    n, live, chunk = 8, 0b11110111, 1024
+    count = 7 * chunk * 9 + 123
+    say("graph capture", dtype)
+    pristine = rand_bufs(n, count, dtype, seed=77, dist="student_t3", mask=live)
+    orig = [host(b) for b in pristine]
+    masks = [0b11110111, 0b00010001, 0b11111111, 0b01000000]
+    bucket = (count + 3) // 4
+    plan = B.ftar_plan(n, live, count, chunk, dtype)
+    zplan = B.ftar_plan(n, live, count, chunk, dtype)
+    B.ftar_plan_set_zero_mask(zplan, 0b00100000)
+    work = [torch.empty_like(b) for b in pristine]
+    work2 = [torch.empty_like(b) for b in pristine]
+    acc = torch.empty(count, dtype=torch.float32, device="cuda")
+    one_shot = torch.empty(count, dtype=dtype, device="cuda")
+    bucketed = torch.empty(count, dtype=dtype, device="cuda")
+    wide = torch.empty(count, dtype=torch.float32, device="cuda")
+    all_zero = torch.empty(count, dtype=dtype, device="cuda")
+
+    def enqueue():
+        for w, w2, p in zip(work, work2, pristine):
+            w.copy_(p)
+            w2.copy_(p)
+        B.ftar_reduce_masked(work, live, one_shot)
+        B.ftar_reduce_masked_bucketed(work, masks, bucket, bucketed)
+        B.ftar_reduce_masked_ex(work, live, wide, op=B.FTAR_SUM)
+        B.ftar_reduce_masked_ex(work, live, all_zero, zero_mask=live)
+        B.ring_allreduce(plan, work, acc)
+        B.ftar_allreduce_onepass(zplan, work2)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [host(t).copy() for t in (one_shot, bucketed, wide, all_zero, *work, *work2)]
+
+    enqueue()
+    eager = snapshot()
+    # the eager result is the oracle's
+    assert_same(eager[0], oracle.reduce_masked(orig, live, code(dtype)), "one-shot")
+    assert_same(eager[4], oracle.ring_closed_form(orig, live, count, chunk, code(dtype)), "ring")
+    assert_same(eager[4 + n], oracle.ring_closed_form_zero(orig, live, 0b00100000, count, chunk, code(dtype)),
+                "one-pass with a zero participant")
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            enqueue()
+    torch.cuda.current_stream().wait_stream(side)
+    for replay in range(4):
+        # the program's own eager work between replays: scribble over every output
+        for t in (one_shot, bucketed, wide, all_zero, acc, *work, *work2):
+            t.fill_(float(replay + 1))
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for i, (g, e) in enumerate(zip(got, eager)):
+            assert_same(g, e, "replay %d output %d" % (replay, i))
