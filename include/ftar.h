@@ -307,14 +307,17 @@ const char* ftar_status_str(ftar_status_t s); /* static string */
 /* Launch shape and cache policy, for measurement only (results never depend on it).
  * blocks_per_cu: workgroups launched per compute unit (0 = each kernel's default);
  * flags: 0 = each kernel's default policy; 0x10 | p = explicit policy p, where bit 0 of p
- * asks for non-temporal loads and bit 1 for non-temporal stores. */
+ * asks for non-temporal loads and bit 1 for non-temporal stores; 0x20 = wide tiles in the
+ * one-shot reduce; 0x40 = never split a long one-shot reduce into several launches;
+ * bits 8..11 = vectors per lane and tile in the ring kernels (2, 4 or 8). */
 void ftar_set_tuning(int blocks_per_cu, int flags);
 
 /* Measurement only: arms two hipEvent_t (passed as void*, either may be NULL) for the NEXT kernel
  * this thread launches through the library.  That dispatch records them itself: `start` when the
  * kernel begins on the GPU, `stop` when it ends, so hipEventElapsedTime(start, stop) is the
- * kernel's own duration.  The pair is consumed by one launch (the first one, for a bucketed call
- * that needs several) and cleared.  The caller owns the events. */
+ * kernel's own duration.  A one-shot or bucketed reduce that goes out as several launches records
+ * `start` with its first and `stop` with its last launch.  The pair is consumed by that call and
+ * cleared.  The caller owns the events. */
 void ftar_time_next_launch(void* start_event, void* stop_event);
 
 #ifdef __cplusplus

@@ -413,12 +413,15 @@ ftar_status_t ftar_reduce_masked_bucketed(const void* const* bufs, int n_replica
   ScaleTable scales;
   scales.s[0] = 0.0f;
   for (int n = 1; n <= kMaxReplicas; ++n) scales.s[n] = 1.0f / static_cast<float>(n);
-  for (size_t b0 = 0; b0 < n_buckets; b0 += kMaxBucketsPerLaunch) {
-    const size_t nb = n_buckets - b0 < static_cast<size_t>(kMaxBucketsPerLaunch)
-                          ? n_buckets - b0 : static_cast<size_t>(kMaxBucketsPerLaunch);
+  const size_t per = kMaxBucketsPerLaunch;
+  const hipEvent_t t_start = t_time_start, t_stop = t_time_stop;  // a timed call brackets the whole series
+  for (size_t b0 = 0; b0 < n_buckets; b0 += per) {
+    const size_t nb = n_buckets - b0 < per ? n_buckets - b0 : per;
     BucketTable bt;
     std::memset(&bt, 0, sizeof(bt));
     for (size_t i = 0; i < nb; ++i) bt.mask[i] = masks[b0 + i];
+    t_time_start = b0 == 0 ? t_start : nullptr;
+    t_time_stop = b0 + nb >= n_buckets ? t_stop : nullptr;
     hipError_t e = launch_reduce_bucketed(tab, n_replicas, bt, static_cast<int>(nb), b0 * bucket_elems,
                                           bucket_elems, count, scales, dtype, vec, out,
                                           static_cast<hipStream_t>(stream));

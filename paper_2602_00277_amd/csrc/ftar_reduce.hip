@@ -142,10 +142,10 @@ struct ReduceFixed {
   case n:                                                                                         \
     if (wide)                                                                                     \
       launch(k_reduce_masked<T, VEC, n, unroll_wide(n), POL>, grid, block, stream, live, out, scale, \
-                                                                                  count, zterm);  \
+             count, zterm);                                                                       \
     else                                                                                          \
       launch(k_reduce_masked<T, VEC, n, unroll_narrow(n), POL>, grid, block, stream, live, out,    \
-                                                                                    scale, count, zterm); \
+             scale, count, zterm);                                                                \
     break;
       FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
       FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
@@ -192,9 +192,10 @@ struct ReduceFixedF32Out {
   }
 };
 
+// whole_out_bytes: output size of the whole call (a long call goes out as several launches)
 hipError_t reduce_masked_f32out(const PtrTable& live, int N, size_t count, bool vec, float* out,
-                                float scale, float zterm, hipStream_t stream) {
-  const LaunchCfg cfg = reduce_cfg(N, count * sizeof(float));
+                                float scale, float zterm, size_t whole_out_bytes, hipStream_t stream) {
+  const LaunchCfg cfg = reduce_cfg(N, whole_out_bytes);
   if (vec && N <= 16) return with_policy(cfg, ReduceFixedF32Out{live, N, count, out, scale, zterm, stream});
   if (vec) return with_policy(cfg, ReduceAny<bf16, 4, float>{live, N, count, out, scale, zterm, stream});
   return with_policy(cfg, ReduceAny<bf16, 1, float>{live, N, count, out, scale, zterm, stream});
@@ -202,9 +203,9 @@ hipError_t reduce_masked_f32out(const PtrTable& live, int N, size_t count, bool 
 
 template <typename T, int VECW>
 hipError_t reduce_masked_typed(const PtrTable& live, int N, size_t count, bool vec, void* out,
-                               float scale, float zterm, hipStream_t stream) {
+                               float scale, float zterm, size_t whole_out_bytes, hipStream_t stream) {
   T* o = static_cast<T*>(out);
-  const LaunchCfg cfg = reduce_cfg(N, count * sizeof(T));
+  const LaunchCfg cfg = reduce_cfg(N, whole_out_bytes);
   if (vec && N <= 16) return with_policy(cfg, ReduceFixed<T, VECW>{live, N, count, o, scale, zterm, stream});
   if (vec) return with_policy(cfg, ReduceAny<T, VECW>{live, N, count, o, scale, zterm, stream});
   return with_policy(cfg, ReduceAny<T, 1>{live, N, count, o, scale, zterm, stream});
@@ -235,9 +236,9 @@ hipError_t bucketed_typed(const PtrTable& all, int n_replicas, const BucketTable
                           const ScaleTable& scales, bool vec, void* out, hipStream_t stream) {
   T* o = static_cast<T*>(out);
   if (vec)
-    return with_policy(reduce_cfg(n_replicas, (count - first_elem) * sizeof(T)), Bucketed<T, VECW>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
+    return with_policy(reduce_cfg(n_replicas, count * sizeof(T)), Bucketed<T, VECW>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
                                          count, scales, o, stream});
-  return with_policy(reduce_cfg(n_replicas, (count - first_elem) * sizeof(T)), Bucketed<T, 1>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
+  return with_policy(reduce_cfg(n_replicas, count * sizeof(T)), Bucketed<T, 1>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
                                     count, scales, o, stream});
 }
 
@@ -266,11 +267,35 @@ hipError_t launch_reduce_masked(const PtrTable& live, int n_src, size_t count, f
     return hipGetLastError();
   }
   const float zterm = zero_participants ? 0.0f : -0.0f;
-  if (out_dtype != dtype)
-    return reduce_masked_f32out(live, n_src, count, vec, static_cast<float*>(out), scale, zterm, stream);
-  if (dtype == FTAR_F32)
-    return reduce_masked_typed<float, 4>(live, n_src, count, vec, out, scale, zterm, stream);
-  return reduce_masked_typed<bf16, 8>(live, n_src, count, vec, out, scale, zterm, stream);
+  // A long reduction goes out as several launches of about 1 GiB of traffic each.  The blocks of
+  // a launch stride over their tiles without ever waiting for each other; over some 100 MiB per
+  // stream they drift apart, the window of addresses in use widens and the DRAM sees less
+  // locality (8 x 2e9 bf16: 5.14 TB/s as one launch, 5.65 TB/s in launches of 128 MiB per stream).
+  // Tuning flag 0x40 forces one launch.
+  const size_t es_in = dtype == FTAR_F32 ? 4 : 2, es_out = out_dtype == FTAR_F32 ? 4 : 2;
+  size_t chunk = (static_cast<size_t>(1) << 30) / (static_cast<size_t>(n_src) * es_in + es_out);
+  chunk &= ~static_cast<size_t>(0xffff);  // whole tiles of every shape, 16-byte aligned in both types
+  if ((current_tuning().flags & 0x40) != 0 || count <= chunk + chunk / 2) chunk = count;
+  hipEvent_t t_start = nullptr, t_stop = nullptr;
+  if (chunk < count) take_timing_events(&t_start, &t_stop);
+  for (size_t first = 0; first < count; first += chunk) {
+    const size_t len = count - first < chunk + chunk / 2 ? count - first : chunk;  // no short last launch
+    PtrTable part = live;
+    for (int j = 0; j < n_src; ++j) part.p[j] = static_cast<char*>(live.p[j]) + first * es_in;
+    void* o = static_cast<char*>(out) + first * es_out;
+    if (chunk < count)  // the events of a timed call bracket the whole series
+      ftar_time_next_launch(first == 0 ? t_start : nullptr, first + len >= count ? t_stop : nullptr);
+    hipError_t e;
+    if (out_dtype != dtype)
+      e = reduce_masked_f32out(part, n_src, len, vec, static_cast<float*>(o), scale, zterm, count * es_out, stream);
+    else if (dtype == FTAR_F32)
+      e = reduce_masked_typed<float, 4>(part, n_src, len, vec, o, scale, zterm, count * es_out, stream);
+    else
+      e = reduce_masked_typed<bf16, 8>(part, n_src, len, vec, o, scale, zterm, count * es_out, stream);
+    if (e != hipSuccess) return e;
+    if (len != chunk) break;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_reduce_bucketed(const PtrTable& all, int n_replicas, const BucketTable& masks,

@@ -86,3 +86,47 @@ def test_time_next_launch_records_the_kernel(B):
     torch.cuda.synchronize()
     hip.hipEventDestroy(a)
     hip.hipEventDestroy(b)
+
+
+def test_long_reduce_goes_out_in_several_launches_with_the_same_bits_and_one_bracket(B, oracle):
+    # 3 streams of 640 MiB: beyond the size up to which a one-shot reduce is a single launch
+    hip = None
+    for line in open("/proc/self/maps"):
+        if "libamdhip64" in line:
+            hip = ctypes.CDLL(line.split()[-1])
+            break
+    assert hip is not None
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+    hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+    a, b = ctypes.c_void_p(), ctypes.c_void_p()
+    assert hip.hipEventCreate(ctypes.byref(a)) == 0 and hip.hipEventCreate(ctypes.byref(b)) == 0
+    count = 320 * (1 << 20) + 12345
+    say("long reduce in several launches", count)
+    bufs = rand_bufs(3, count, torch.bfloat16, seed=9, mask=0b101)
+    split, single = torch.empty(count, dtype=torch.bfloat16, device="cuda"), torch.empty(count, dtype=torch.bfloat16,
+                                                                                       device="cuda")
+    B.ftar_reduce_masked(bufs, 0b101, split)
+    B.ftar_time_next_launch(a, b)
+    B.ftar_reduce_masked(bufs, 0b101, split)
+    assert hip.hipEventSynchronize(b) == 0
+    ms = ctypes.c_float()
+    assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+    # 1.9 GiB moved in all: a bracket around the whole series is above 0.2 ms; one launch of it
+    # (about 1 GiB) at the 8 TB/s peak would already take 0.13 ms
+    assert 0.2 < ms.value < 20.0, ms.value
+    B.ftar_set_tuning(0, 0x40)
+    B.ftar_reduce_masked(bufs, 0b101, single)
+    B.ftar_set_tuning(0, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(split.view(torch.int16), single.view(torch.int16))
+    # sampled against the oracle, around every place a launch could begin and at both ends
+    for lo in [0, count - 4096] + [k * 65536 * 16 - 2048 for k in range(1, 300, 23)]:
+        if lo < 0 or lo + 4096 > count:
+            continue
+        want = oracle.reduce_masked([None if x is None else host(x[lo:lo + 4096]) for x in
+                                     [bufs[0], None, bufs[2]]], 0b101, code(torch.bfloat16))
+        assert_same(host(split[lo:lo + 4096]), want, "slab at %d" % lo)
+    hip.hipEventDestroy(a)
+    hip.hipEventDestroy(b)
