@@ -2,6 +2,8 @@
 zero-gradient participants, divisor policy, sum or mean, chunk size, ragged count, pointer
 alignment, partition size, worker budget - every ring path and the one-shot reduce against the
 oracle, bit-exact."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -9,6 +11,9 @@ import torch
 from gpu_util import assert_same, code, host, rand_bufs, say
 
 pytestmark = pytest.mark.gpu
+
+# FTAR_SWEEP_BASE shifts every seed: a different base gives a different set of draws
+BASE = int(os.environ.get("FTAR_SWEEP_BASE", "0"))
 
 
 @pytest.fixture(scope="module")
@@ -82,7 +87,7 @@ def _release(ctrl, n_slots, how, rng):
 
 @pytest.mark.parametrize("seed", range(120))
 def test_random_option_draw(B, oracle, seed):
-    rng = np.random.default_rng(1000 + seed)
+    rng = np.random.default_rng(1000 + BASE + seed)
     c = _draw(rng)
     say("cross options", seed, {k: (hex(v) if k in ("live", "zmask") else v) for k, v in c.items()})
     n, live, count, dtype = c["n"], c["live"], c["count"], c["dtype"]
@@ -145,7 +150,7 @@ def test_random_option_draw(B, oracle, seed):
 
 @pytest.mark.parametrize("seed", range(40))
 def test_random_bucketed_draw(B, oracle, seed):
-    rng = np.random.default_rng(5000 + seed)
+    rng = np.random.default_rng(5000 + BASE + seed)
     n = int(rng.choice([1, 2, 3, 5, 8, 13, 16, 17, 30]))
     dtype = torch.bfloat16 if rng.random() < 0.5 else torch.float32
     bucket = int(rng.choice([1, 7, 8, 100, 1024, 4096, 5000, 50000]))
