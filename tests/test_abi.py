@@ -83,10 +83,8 @@ def test_oracle_is_not_reachable_from_the_product(B):
     assert "paper_2602_00277_amd" not in osrc and "ftar.h" not in osrc and "libftar.so" not in osrc
 
 
-def test_lr_factors_match_the_oracle(oracle):
+def test_lr_factors_match_the_oracle(B, oracle):
     # host-only call: no GPU needed
-    import ctypes
-    from paper_2602_00277_amd import binding as B
     L = B.lib()
     for n, live, zmask in [(8, 0xFF, 0), (16, 0x01FF, 0), (16, 0x00FF, 0x000F), (7, 0b1010101, 0b0000100),
                            (64, (1 << 64) - 1, 1 << 63), (3, 0b011, 0b011)]:
