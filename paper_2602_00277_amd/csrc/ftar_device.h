@@ -449,6 +449,18 @@ inline LaunchCfg reduce_cfg(int n_live, size_t out_bytes) {
 // the first AllGather step reads: ordinary stores leave them in the Infinity Cache (8 x 64 Mi bf16
 // inside the whole schedule: first step 87 -> 79 us, last step 87 -> 80 us against non-temporal
 // stores; no difference once nothing fits any more).
+// Per-bucket masks: the tile body re-specialises per bucket and runs four short sub-tiles, so two
+// workgroups per CU keep more loads in flight (8 x 64 Mi bf16: 167 -> 158 us); over long streams
+// (8 x 512 Mi fp32) the extra blocks drift apart and one per CU is 3 % faster.
+inline LaunchCfg bucketed_cfg(int n_replicas, size_t out_bytes) {
+  LaunchCfg c = reduce_cfg(n_replicas, out_bytes);
+  if (out_bytes <= 512 * kMiB && current_tuning().blocks_per_cu <= 0) {
+    const LaunchCfg two = launch_cfg(2, c.pol);
+    if (two.blocks > c.blocks) c.blocks = two.blocks;
+  }
+  return c;
+}
+
 inline LaunchCfg ring_reduce_cfg(RingMode mode, size_t count) {
   if (mode == kRsMid) return launch_cfg(1, count * 4 <= 256 * kMiB ? 1 : 3);
   return launch_cfg(2, 1);

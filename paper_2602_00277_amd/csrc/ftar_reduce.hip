@@ -236,9 +236,9 @@ hipError_t bucketed_typed(const PtrTable& all, int n_replicas, const BucketTable
                           const ScaleTable& scales, bool vec, void* out, hipStream_t stream) {
   T* o = static_cast<T*>(out);
   if (vec)
-    return with_policy(reduce_cfg(n_replicas, count * sizeof(T)), Bucketed<T, VECW>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
+    return with_policy(bucketed_cfg(n_replicas, count * sizeof(T)), Bucketed<T, VECW>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
                                          count, scales, o, stream});
-  return with_policy(reduce_cfg(n_replicas, count * sizeof(T)), Bucketed<T, 1>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
+  return with_policy(bucketed_cfg(n_replicas, count * sizeof(T)), Bucketed<T, 1>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
                                     count, scales, o, stream});
 }
 
