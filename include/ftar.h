@@ -199,9 +199,10 @@ ftar_status_t ftar_reduce_masked(const void* const* bufs, int n_replicas, uint64
  * is unchanged.  ftar_plan_set_op applies to every ring call made with the plan afterwards;
  * ftar_plan_scale reports the factor in force.
  * ftar_reduce_masked_ex is the one-shot reduce with everything selectable: zero-gradient
- * participants (as ftar_reduce_masked_zero), the operation, and the result type, which is
- * in_dtype or FTAR_F32 from FTAR_BF16 inputs (the fp32 sum/mean is then stored unrounded:
- * 2N read + 4 written bytes per element).  Other type pairs: FTAR_ERR_INVALID_ARG.
+ * participants (as ftar_reduce_masked_zero), the operation, and the result type independently of
+ * the input type: FTAR_F32 from FTAR_BF16 inputs stores the fp32 sum/mean unrounded (2N read + 4
+ * written bytes per element); FTAR_BF16 from FTAR_F32 inputs rounds it once, to nearest even (4N
+ * read + 2 written).
  */
 typedef enum { FTAR_MEAN = 0, FTAR_SUM = 1 } ftar_op_t;
 ftar_status_t ftar_plan_set_op(ftar_plan_t* plan, ftar_op_t op);

@@ -330,9 +330,8 @@ static ftar_status_t reduce_masked_common(const void* const* bufs, int n_replica
                                           ftar_dtype_t dtype, ftar_dtype_t out_dtype, ftar_op_t op,
                                           void* out, void* stream) {
   if (!bufs || !out || count == 0 || (dtype != FTAR_F32 && dtype != FTAR_BF16) ||
-      (op != FTAR_MEAN && op != FTAR_SUM))
+      (out_dtype != FTAR_F32 && out_dtype != FTAR_BF16) || (op != FTAR_MEAN && op != FTAR_SUM))
     return fail(FTAR_ERR_INVALID_ARG);
-  if (out_dtype != dtype && !(dtype == FTAR_BF16 && out_dtype == FTAR_F32)) return fail(FTAR_ERR_INVALID_ARG);
   int ring[kMaxReplicas];
   int N = 0;
   ftar_status_t s = resolve_mask(n_replicas, live_mask, ring, &N);

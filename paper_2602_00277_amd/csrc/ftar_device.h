@@ -85,12 +85,19 @@ __device__ __forceinline__ void widen(uint16_t r, float (&x)[1]) {
 }
 
 // ---- narrowing: round to nearest, ties to even; NaN stays a (quiet) NaN ------
-__device__ __forceinline__ uint32_t bf16_rne(float f) {
-  const uint32_t u = __float_as_uint(f);
-  const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-  const uint32_t quiet = ((u >> 16) | 0x40u) & 0xffffu;
-  return ((u & 0x7fffffffu) > 0x7f800000u) ? quiet : rounded;
+// gfx950 converts in hardware (v_cvt_pk_bf16_f32, two values per instruction).  On all 2^32
+// patterns it gives what the integer rule gives - add 0x7fff plus the lowest kept bit, shift by
+// 16; NaN: sign and upper payload kept, quiet bit set; fp32 denormals are not flushed.
+__device__ __forceinline__ uint32_t bf16_rne2(float lo, float hi) {  // lo in bits 0..15
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  const f32x2 v = {lo, hi};
+  const bf16x2 r = __builtin_convertvector(v, bf16x2);
+  uint32_t u;
+  __builtin_memcpy(&u, &r, 4);
+  return u;
 }
+__device__ __forceinline__ uint32_t bf16_rne(float f) { return bf16_rne2(f, 0.0f) & 0xffffu; }
 
 template <typename R, int VEC>
 __device__ __forceinline__ R narrow(const float (&x)[VEC]) {
@@ -102,12 +109,12 @@ __device__ __forceinline__ R narrow(const float (&x)[VEC]) {
   } else if constexpr (__is_same(R, u32x4)) {
     u32x4 r;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) r[i] = bf16_rne(x[2 * i]) | (bf16_rne(x[2 * i + 1]) << 16);
+    for (int i = 0; i < 4; ++i) r[i] = bf16_rne2(x[2 * i], x[2 * i + 1]);
     return r;
   } else if constexpr (__is_same(R, u32x2)) {
     u32x2 r;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) r[i] = bf16_rne(x[2 * i]) | (bf16_rne(x[2 * i + 1]) << 16);
+    for (int i = 0; i < 2; ++i) r[i] = bf16_rne2(x[2 * i], x[2 * i + 1]);
     return r;
   } else {
     return static_cast<uint16_t>(bf16_rne(x[0]));
@@ -127,7 +134,8 @@ __device__ __forceinline__ P* uniform_ptr(P* p) {
 // For U vectors per lane (vector v + u*kThreads):
 //   a = ACC_IN ? acc_in : x_0 ;  a = a + x_j for the remaining sources in order;
 //   ACC_OUT == 1: acc_out = a (fp32, unscaled);  ACC_OUT == 0: out = cvt(scale * a);
-//   ACC_OUT == 2: acc_out = scale * a (fp32 result from any input type)
+//   ACC_OUT == 2: acc_out = scale * a (fp32 result from any input type);
+//   ACC_OUT == 3: acc_out = bf16(scale * a) (bf16 result from fp32 inputs)
 // Every load of the tile is issued before the first use.  `out` may alias
 // src[NSRC-1] (the in-place last ReduceScatter step): a lane only ever writes
 // the elements it has itself already loaded.
@@ -144,6 +152,7 @@ __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc
                                          T* out, float scale, size_t v, unsigned long long zm = 0,
                                          float zterm = 0.0f) {
   static_assert(!(ACC_IN || ACC_OUT) || VEC <= 4, "fp32 partials are moved 4 at a time");
+  static_assert(ACC_OUT != 3 || __is_same(T, float), "mode 3 narrows fp32 inputs");
   typedef typename Raw<T, VEC>::type R;
   typedef typename Raw<float, (VEC == 1 ? 1 : 4)>::type A;
   R raw[U][NSRC];
@@ -180,8 +189,14 @@ __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc
       }
 #pragma unroll
       for (int e = 0; e < VEC; ++e) a[e] = a[e] * scale;
-      if constexpr (ACC_OUT == 2) st<POL>(reinterpret_cast<A*>(acc_out) + v + u * kThreads, narrow<A, VEC>(a));
-      else st<POL>(reinterpret_cast<R*>(out) + v + u * kThreads, narrow<R, VEC>(a));
+      if constexpr (ACC_OUT == 2) {
+        st<POL>(reinterpret_cast<A*>(acc_out) + v + u * kThreads, narrow<A, VEC>(a));
+      } else if constexpr (ACC_OUT == 3) {
+        typedef typename Raw<bf16, VEC>::type B;
+        st<POL>(reinterpret_cast<B*>(acc_out) + v + u * kThreads, narrow<B, VEC>(a));
+      } else {
+        st<POL>(reinterpret_cast<R*>(out) + v + u * kThreads, narrow<R, VEC>(a));
+      }
     }
   }
 }

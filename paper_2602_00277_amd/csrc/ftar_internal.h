@@ -84,7 +84,7 @@ int device_cu_count();  // of the current device; cached
 // participant: it contributes +0.0 and its buffer is never read.
 // live: the n_src buffers that are read, in summation order (zero-gradient participants already
 // left out: zero_participants says whether there were any; n_src may then be 0).
-// out_dtype == dtype, or fp32 from bf16 inputs.
+// dtype: element type of the inputs; out_dtype: of the result (any of the four pairs).
 hipError_t launch_reduce_masked(const PtrTable& live, int n_src, size_t count, ftar_dtype_t dtype,
                                 ftar_dtype_t out_dtype, bool vec, void* out, float scale,
                                 bool zero_participants, hipStream_t stream);

@@ -22,18 +22,21 @@ k_reduce_masked(PtrTable live, T* out, float scale, size_t count, float zterm) {
                                                             blockIdx.x, gridDim.x, 0, zterm);
 }
 
-// The same with an fp32 result from bf16 inputs: 8-byte loads, 16-byte stores.
-template <int VEC, int N, int U, int POL>
+// The same with a result of the other element type, 4 elements per lane and vector: an fp32 result
+// from bf16 inputs (8-byte loads, 16-byte stores) or a bf16 result from fp32 inputs (16-byte loads,
+// 8-byte stores).  TI = input type; out is float* for bf16 inputs and bf16* for fp32 inputs.
+template <typename TI, int VEC, int N, int U, int POL>
 __global__ void __launch_bounds__(kThreads)
-k_reduce_masked_f32out(PtrTable live, float* out, float scale, size_t count, float zterm) {
-  __shared__ bf16* s_tab[kMaxReplicas];
-  if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<bf16*>(live.p[threadIdx.x]);
+k_reduce_masked_cvt(PtrTable live, void* out, float scale, size_t count, float zterm) {
+  __shared__ TI* s_tab[kMaxReplicas];
+  if (threadIdx.x < static_cast<unsigned>(N)) s_tab[threadIdx.x] = static_cast<TI*>(live.p[threadIdx.x]);
   __syncthreads();
-  bf16* src[N];
+  TI* src[N];
 #pragma unroll
   for (int j = 0; j < N; ++j) src[j] = uniform_ptr(s_tab[j]);
-  sum_range_z<bf16, VEC, N, false, 2, U, POL, false, true>(src, nullptr, out, nullptr, scale, count,
-                                                           blockIdx.x, gridDim.x, 0, zterm);
+  constexpr int kMode = __is_same(TI, float) ? 3 : 2;
+  sum_range_z<TI, VEC, N, false, kMode, U, POL, false, true>(src, nullptr, static_cast<float*>(out), nullptr,
+                                                             scale, count, blockIdx.x, gridDim.x, 0, zterm);
 }
 
 // One-shot masked mean, any N up to 64 (also the element-wise path for unaligned buffers).
@@ -168,19 +171,22 @@ struct ReduceAny {
   }
 };
 
-// bf16 in, fp32 out: 4 elements per lane and vector (8-byte loads), as many vectors in flight
-// as the wide tiles of the same-type kernel have bytes.
-struct ReduceFixedF32Out {
-  const PtrTable& live; int N; size_t count; float* out; float scale; float zterm; hipStream_t stream;
+// Result of the other element type: 4 elements per lane and vector.  bf16 inputs (8-byte loads)
+// take the wide tiles, fp32 inputs (16-byte loads) the narrow ones: the same bytes in flight as the
+// same-type kernel has.
+template <typename TI>
+struct ReduceFixedCvt {
+  const PtrTable& live; int N; size_t count; void* out; float scale; float zterm; hipStream_t stream;
   template <int POL> hipError_t operator()(unsigned blocks) const {
-    const int U = unroll_wide(N);
+    constexpr bool kWide = !__is_same(TI, float);
+    const int U = kWide ? unroll_wide(N) : unroll_narrow(N);
     const size_t tiles = count / 4 / (static_cast<size_t>(kThreads) * U);
     const dim3 grid(grid_x_for(tiles, blocks)), block(kThreads);
     switch (N) {
 #define FTAR_CASE(n)                                                                               \
   case n:                                                                                          \
-    launch(k_reduce_masked_f32out<4, n, unroll_wide(n), POL>, grid, block, stream, live, out, scale, \
-           count, zterm);                                                                          \
+    launch(k_reduce_masked_cvt<TI, 4, n, (kWide ? unroll_wide(n) : unroll_narrow(n)), POL>, grid, block, \
+           stream, live, out, scale, count, zterm);                                                \
     break;
       FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
       FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
@@ -193,12 +199,14 @@ struct ReduceFixedF32Out {
 };
 
 // whole_out_bytes: output size of the whole call (a long call goes out as several launches)
-hipError_t reduce_masked_f32out(const PtrTable& live, int N, size_t count, bool vec, float* out,
-                                float scale, float zterm, size_t whole_out_bytes, hipStream_t stream) {
+template <typename TI, typename TO>
+hipError_t reduce_masked_cvt(const PtrTable& live, int N, size_t count, bool vec, void* out, float scale,
+                             float zterm, size_t whole_out_bytes, hipStream_t stream) {
   const LaunchCfg cfg = reduce_cfg(N, whole_out_bytes);
-  if (vec && N <= 16) return with_policy(cfg, ReduceFixedF32Out{live, N, count, out, scale, zterm, stream});
-  if (vec) return with_policy(cfg, ReduceAny<bf16, 4, float>{live, N, count, out, scale, zterm, stream});
-  return with_policy(cfg, ReduceAny<bf16, 1, float>{live, N, count, out, scale, zterm, stream});
+  TO* o = static_cast<TO*>(out);
+  if (vec && N <= 16) return with_policy(cfg, ReduceFixedCvt<TI>{live, N, count, out, scale, zterm, stream});
+  if (vec) return with_policy(cfg, ReduceAny<TI, 4, TO>{live, N, count, o, scale, zterm, stream});
+  return with_policy(cfg, ReduceAny<TI, 1, TO>{live, N, count, o, scale, zterm, stream});
 }
 
 template <typename T, int VECW>
@@ -247,7 +255,6 @@ hipError_t bucketed_typed(const PtrTable& all, int n_replicas, const BucketTable
 hipError_t launch_reduce_masked(const PtrTable& live, int n_src, size_t count, ftar_dtype_t dtype,
                                 ftar_dtype_t out_dtype, bool vec, void* out, float scale,
                                 bool zero_participants, hipStream_t stream) {
-  if (out_dtype != dtype && !(dtype == FTAR_BF16 && out_dtype == FTAR_F32)) return hipErrorInvalidValue;
   if (n_src == 0) {  // nothing to read; bf16 buffers are only 2-byte aligned: head/tail by halves
     if (!zero_participants) return hipErrorInvalidValue;
     const size_t bytes = count * (out_dtype == FTAR_F32 ? 4 : 2);
@@ -286,8 +293,10 @@ hipError_t launch_reduce_masked(const PtrTable& live, int n_src, size_t count, f
     if (chunk < count)  // the events of a timed call bracket the whole series
       ftar_time_next_launch(first == 0 ? t_start : nullptr, first + len >= count ? t_stop : nullptr);
     hipError_t e;
-    if (out_dtype != dtype)
-      e = reduce_masked_f32out(part, n_src, len, vec, static_cast<float*>(o), scale, zterm, count * es_out, stream);
+    if (out_dtype != dtype && dtype == FTAR_BF16)
+      e = reduce_masked_cvt<bf16, float>(part, n_src, len, vec, o, scale, zterm, count * es_out, stream);
+    else if (out_dtype != dtype)
+      e = reduce_masked_cvt<float, bf16>(part, n_src, len, vec, o, scale, zterm, count * es_out, stream);
     else if (dtype == FTAR_F32)
       e = reduce_masked_typed<float, 4>(part, n_src, len, vec, o, scale, zterm, count * es_out, stream);
     else

@@ -1,5 +1,7 @@
 """GPU: delivery variants - the sum of paper section 4.1 instead of the mean, an fp32 result from
 bf16 inputs - and the learning-rate factors of section 6.2.  Bit-exact against the oracle."""
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -34,7 +36,8 @@ def test_f32_result_from_bf16_inputs(B, oracle, n_live, sum_only):
 
 
 @pytest.mark.parametrize("in_dtype,out_dtype", [(torch.float32, torch.float32), (torch.bfloat16, torch.bfloat16),
-                                                (torch.bfloat16, torch.float32)], ids=["f32", "bf16", "bf16-f32"])
+                                                (torch.bfloat16, torch.float32), (torch.float32, torch.bfloat16)],
+                         ids=["f32", "bf16", "bf16-f32", "f32-bf16"])
 def test_every_option_together(B, oracle, in_dtype, out_dtype):
     n, live, count = 6, 0b110111, 10000 + 5
     bufs = rand_bufs(n, count, in_dtype, seed=61, mask=live)
@@ -69,16 +72,57 @@ def test_unaligned_buffers_take_the_element_path(B, oracle):
     assert_same(host(out), want)
 
 
-def test_type_pairs_that_are_not_offered(B):
+def test_unknown_operation_and_type_codes(B):
     bufs = rand_bufs(2, 64, torch.float32, seed=63)
-    out = torch.empty(64, dtype=torch.bfloat16, device="cuda")
-    with pytest.raises(B.FtarError) as e:
-        B.ftar_reduce_masked_ex(bufs, 0b11, out)
-    assert e.value.status == B.FTAR_ERR_INVALID_ARG
     out = torch.empty(64, dtype=torch.float32, device="cuda")
     with pytest.raises(B.FtarError) as e:
         B.ftar_reduce_masked_ex(bufs, 0b11, out, op=2)
     assert e.value.status == B.FTAR_ERR_INVALID_ARG
+    ptrs = (ctypes.c_void_p * 2)(bufs[0].data_ptr(), bufs[1].data_ptr())
+    for in_code, out_code in ((0, 2), (3, 0), (-1, 1)):
+        st = B.lib().ftar_reduce_masked_ex(ptrs, 2, 0b11, 0, 0, 64, in_code, out_code, 0, out.data_ptr(), None)
+        assert st == B.FTAR_ERR_INVALID_ARG, (in_code, out_code)
+
+
+@pytest.mark.parametrize("n_live", [1, 2, 3, 7, 8, 16, 17])
+@pytest.mark.parametrize("sum_only", [False, True], ids=["mean", "sum"])
+def test_bf16_result_from_f32_inputs(B, oracle, n_live, sum_only):
+    n, live = n_live + 1, ((1 << (n_live + 1)) - 1) & ~0b10 if n_live > 1 else 0b01
+    if n_live > 1:
+        n, live = n_live + 1, ((1 << (n_live + 1)) - 1) & ~0b10
+    count = 256 * 4 * 4 * 3 + 4 * 19 + 2
+    say("f32 -> bf16", n_live, "sum" if sum_only else "mean")
+    bufs = rand_bufs(n, count, torch.float32, seed=80 + n_live, dist="student_t3", mask=live)
+    assert bin(live).count("1") == n_live
+    out = torch.empty(count, dtype=torch.bfloat16, device="cuda")
+    B.ftar_reduce_masked_ex(bufs, live, out, op=B.FTAR_SUM if sum_only else B.FTAR_MEAN)
+    torch.cuda.synchronize()
+    want = oracle.reduce_masked_ex([host(b) for b in bufs], live, F32, out_dtype=BF16, sum_only=sum_only)
+    assert_same(host(out), want)
+
+
+def test_narrowing_of_every_fp32_pattern(B, oracle):
+    # one live fp32 replica, sum, bf16 result: the kernel's whole arithmetic is x * 1.0f and the one
+    # rounding to bf16, on x itself - all 2^32 patterns, NaNs, infinities and denormals included
+    chunk = 1 << 26
+    out = torch.empty(chunk, dtype=torch.bfloat16, device="cuda")
+    say("fp32 -> bf16 narrowing, 64 chunks of 2^26 patterns")
+    for i in range(0, 1 << 32, chunk):
+        x = torch.arange(i, i + chunk, dtype=torch.int64, device="cuda").to(torch.int32).view(torch.float32)
+        B.ftar_reduce_masked_ex([x], 0b1, out, op=B.FTAR_SUM)
+        torch.cuda.synchronize()
+        want = x.to(torch.bfloat16)                        # torch's converter: same rule for non-NaN
+        nan = torch.isnan(x)
+        assert bool((torch.isnan(out.float()) == nan).all()), "NaN positions, chunk at %#x" % i
+        same = (out.view(torch.int16) == want.view(torch.int16)) | nan
+        assert bool(same.all()), "chunk at %#x" % i
+        idx = torch.arange(0, chunk, 251, device="cuda")   # strided sample against the oracle's converter
+        got = out[idx].cpu().view(torch.int16).numpy().view(np.uint16)
+        ref = oracle.f32_to_bf16(x[idx].cpu().numpy())
+        both_nan = nan[idx].cpu().numpy()
+        assert np.array_equal(got[~both_nan], ref[~both_nan]), "chunk at %#x (oracle sample)" % i
+        # a NaN keeps its sign and upper payload and gets the quiet bit, as in the oracle
+        assert np.array_equal(got[both_nan], ref[both_nan]), "chunk at %#x (NaN payloads)" % i
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
