@@ -146,3 +146,42 @@ def test_portion_zero_equals_one_shot_reduce(B, oracle):
     # every live replica ends bit-identical
     for r in range(1, n):
         assert torch.equal(bufs[r].view(torch.int16), bufs[0].view(torch.int16))
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+@pytest.mark.parametrize("n,mask", [(64, (1 << 64) - 1), (64, 0xF0F0F0F0F0F0F0F1), (33, (1 << 33) - 1 - (1 << 16)),
+                                    (64, 1 << 63), (64, (1 << 63) | 1)])
+def test_largest_groups_on_every_ring_path(B, oracle, dtype, n, mask):
+    # the mask is 64 bits wide: 64 replicas is the largest group the interface can name
+    N = bin(mask).count("1")
+    chunk = 64
+    count = N * chunk * 5 + 41
+    say("ring, largest groups", dtype, n, hex(mask), count)
+    orig_t = rand_bufs(n, count, dtype, seed=64 + N, dist="student_t3", mask=mask)
+    orig = [host(b) for b in orig_t]
+    want = oracle.ring_closed_form(orig, mask, count, chunk, code(dtype))
+    plan = B.ftar_plan(n, mask, count, chunk, dtype)
+    assert plan.n_live == N and plan.n_steps == N - 1
+    acc = torch.empty(count, dtype=torch.float32, device="cuda")
+    ctrl = B.ftar_ctrl_create()
+    for name in ("steps", "onepass", "persistent", "partitioned"):
+        bufs = [b.clone() for b in orig_t]
+        ref = want
+        if name == "steps":
+            B.ring_allreduce(plan, bufs, acc)
+        elif name == "onepass":
+            B.ftar_allreduce_onepass(plan, bufs)
+        else:
+            if name == "partitioned":
+                part = N * chunk * 2
+                plan.set_partition(part)
+                ref = np.concatenate([oracle.ring_closed_form([None if o is None else np.ascontiguousarray(o[lo:lo + part])
+                                                               for o in orig], mask, min(part, count - lo), chunk,
+                                                              code(dtype)) for lo in range(0, count, part)])
+            B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=9, timeout_us=10_000_000)
+            ctrl.release(plan.n_slots)
+            torch.cuda.synchronize()
+            assert ctrl.result() == (B.FTAR_OK, plan.n_slots)
+        torch.cuda.synchronize()
+        for r in range(n):
+            assert_same(host(bufs[r]), ref if (mask >> r) & 1 else orig[r], "%s buf %d" % (name, r))
