@@ -251,7 +251,6 @@ def all_configs_report(path, B, W, torch, np):
                         while ctrl.progress() < s + 1:
                             pass
             for label2, fn in (("persistent kernel, all steps released at once", lambda: persistent()),
-                               ("persistent kernel, ALIGN", lambda: persistent(flags=B.FTAR_PERSIST_ALIGN)),
                                ("persistent kernel, PUBLISH|ALIGN, CPU releases step by step",
                                 lambda: persistent(flags=3, gate=True))):
                 med, mn = time_schedule(fn, 5)

@@ -281,6 +281,8 @@ ftar_status_t ftar_allreduce_onepass(const ftar_plan_t* plan, void* const* bufs,
  *               is guaranteed visible off the GPU once the stream has been synchronised.
  *               FTAR_PERSIST_ALIGN: workgroups that ran ahead wait (bounded) for the others after
  *               every step; a performance hint for long steps, never needed for correctness.
+ *               The library sets it by itself when the partial sums of one partition exceed
+ *               256 MiB (steps of hundreds of microseconds: +5..9 %; below that it costs).
  * Returns at once like every other compute call.  After the stream has been synchronised,
  * ftar_ctrl_result tells how it ended: FTAR_OK (all steps done), or FTAR_ERR_STALE_PLAN
  * (retryable: cancelled or timed out); *steps_done = steps completed by every workgroup.
