@@ -93,6 +93,7 @@ def all_configs_report(path, B, W, torch, np):
     SLAB = 1 << 18
     rows = []
     curve = []
+    share = []
 
     def code(dt):
         return oracle.BF16 if dt == torch.bfloat16 else oracle.F32
@@ -259,6 +260,43 @@ def all_configs_report(path, B, W, torch, np):
             for nb in (2, 4, 8, 16, 32, 64, 128):
                 med, mn = time_schedule(lambda: persistent(nb=nb), 1 if nb < 16 else 3)
                 curve.append((nb, gb / med))
+            # the paper's reason for a small budget: the ring must not take the chip away from the
+            # training compute.  Other work on a second stream, alone and next to the ring.
+            side = torch.cuda.Stream()
+            g1 = [torch.randn(8192, 8192, device=dev, dtype=torch.bfloat16) for _ in range(2)]
+            o1 = torch.empty(8192, 8192, device=dev, dtype=torch.bfloat16)
+            g2 = [torch.randn(5000, 7000, device=dev, dtype=torch.bfloat16),
+                  torch.randn(7000, 9000, device=dev, dtype=torch.bfloat16)]
+            o2 = torch.empty(5000, 9000, device=dev, dtype=torch.bfloat16)
+            ew = torch.randn(256 * W.M, device=dev)
+            others = (("bf16 GEMM 8192 x 8192 x 8192 (torch.matmul)", lambda: torch.matmul(g1[0], g1[1], out=o1)),
+                      ("bf16 GEMM 5000 x 7000 x 9000 (torch.matmul)", lambda: torch.matmul(g2[0], g2[1], out=o2)),
+                      ("fp32 elementwise x *= c over 1 GiB", lambda: ew.mul_(1.0001)))
+
+            def other_loop(fn, reps=40):
+                with torch.cuda.stream(side):
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    fn()
+                    a.record(side)
+                    for _ in range(reps):
+                        fn()
+                    b.record(side)
+                side.synchronize()
+                return a.elapsed_time(b) * 1e-3 / reps
+            for name, fn in others:
+                alone = other_loop(fn)
+                cells = []
+                for nb, release in ((2, False), (2, True), (8, True)):
+                    B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=nb, timeout_us=60_000_000)
+                    if release:
+                        ctrl.release(n_steps)
+                    t = other_loop(fn)
+                    still = ctrl.progress() < n_steps
+                    ctrl.cancel()                  # the ring has served its purpose: end it at its next wait
+                    torch.cuda.synchronize()
+                    cells.append("%+.1f %%%s" % (100 * (t / alone - 1), "" if still else " (ring ended early)"))
+                share.append("| %s | %.3f | %s |" % (name, alone * 1e3, " | ".join(cells)))
+            del g1, o1, g2, o2, ew
             # partitions of 4 Mi elements: acc (16 MiB) and the partition's slices stay in the caches
             plan.set_partition(4 * W.M)
             n_steps = plan.n_slots
@@ -316,6 +354,13 @@ def all_configs_report(path, B, W, torch, np):
             "| worker workgroups | " + " | ".join(str(nb) for nb, _ in curve) + " |",
             "|---|" + "---|" * len(curve),
             "| GB/s | " + " | ".join("%.0f" % g for _, g in curve) + " |"]
+    tail += ["", "## Other work next to the persistent ring (cfg 3a buffers)", "",
+             "40 launches in a row on a second stream of the same priority: alone, next to a ring whose two "
+             "worker workgroups only wait (nothing released), and next to a running ring with 2 and 8 worker "
+             "workgroups. Change of the other work's time per launch; the ring is cancelled when the loop ends.", "",
+             "| other work | alone, ms | 2 workers, waiting only | 2 workers, running | 8 workers, running |",
+             "|---|---|---|---|---|"]
+    tail += share
     with open(path, "w") as f:
         f.write("\n".join(head + rows + tail) + "\n")
     if any("MISMATCH" in r for r in rows):
