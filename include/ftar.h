@@ -18,8 +18,9 @@
  *   - `bufs` is a HOST array of n_replicas DEVICE pointers indexed by replica
  *     id.  Entries of dead replicas are never dereferenced and may be NULL.
  *     The library copies what it needs before returning; the caller may free
- *     the host array at once.  All device memory is caller-owned; no call
- *     allocates or frees device memory.
+ *     the host array at once.  All device memory that holds data is caller-owned;
+ *     no compute call allocates or frees memory (only ftar_ctrl_create/destroy do,
+ *     at set-up: the control block of the persistent ring).
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *     Compute calls only enqueue work on it and return; they never
  *     synchronise.  Calls on one stream are ordered by the stream.
@@ -84,8 +85,9 @@ typedef enum {
  * Ring position p is the p-th live replica in ascending index order; the right
  * neighbour of p is (p+1) mod N.
  * Returns a plan (default dtype FTAR_BF16) or NULL; ftar_last_error() tells why.
- * The plan is immutable apart from ftar_plan_set_dtype, holds no device
- * memory, and the same arguments always give the same plan.
+ * The plan holds no device memory and the same arguments always give the same
+ * plan; only the ftar_plan_set_* calls below change it (element type, zero-gradient
+ * participants, sum or mean, partition size), never a compute call.
  * A membership change is handled by destroying the plan, making a new one and
  * restarting from ReduceScatter step 0; this is sound as long as the last
  * ReduceScatter step of the old plan has not been enqueued, because until then
