@@ -270,8 +270,12 @@ ftar_status_t ftar_allreduce_onepass(const ftar_plan_t* plan, void* const* bufs,
  * bufs[r] untouched and the caller re-plans and restarts.
  *
  * ctrl is a control block made by ftar_ctrl_create(): coherent host-pinned memory plus a mirror
- * of a few hundred bytes in device memory (both allocated at set-up, not on the hot path).  One control block serves one call at a time;
- * ftar_ring_persistent re-arms it (released = 0, no cancel) before launching.
+ * of 4 KiB in device memory (both allocated at set-up, not on the hot path).  One control block
+ * serves one call at a time; ftar_ring_persistent re-arms it (released = 0, no cancel) before
+ * launching.  With a partitioned plan whose last partition is shorter, the workgroups also wait
+ * for each other once (bounded by timeout_us like every wait), before that partition's first slot.
+ * Every workgroup must be resident at once: on a stream that is restricted to some of the
+ * compute units the caller chooses n_blocks to fit them.
  *   n_blocks    worker workgroups (= compute units used), 1..1024; 0 = one per compute unit
  *               (two with a partitioned plan); one more workgroup relays the CPU's gate word;
  *               clamped to what the GPU can keep resident at once (a waiting workgroup keeps
