@@ -192,3 +192,39 @@ def test_cfg5_bucketed_dynamic_membership(B, oracle):
         B.ftar_reduce_masked([x[lo:hi] for x in bufs], masks[b], out2[lo:hi])
     torch.cuda.synchronize()
     assert torch.equal(out.view(torch.int32), out2.view(torch.int32))
+
+
+def test_more_than_two_to_the_thirty_two_elements(B, oracle):
+    # element indices that do not fit 32 bits: 2 live of 3 replicas, 2^32 + 70001 bf16 elements each
+    count = (1 << 32) + 70001
+    say("beyond 2^32 elements", count)
+    bufs = [torch.empty(count, dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4242)
+    step = 1 << 28
+    for b in bufs:
+        for lo in range(0, count, step):
+            hi = min(count, lo + step)
+            b[lo:hi] = torch.randn(hi - lo, device="cuda", generator=gen).mul_(1e-3).to(torch.bfloat16)
+    live = 0b101
+    table = [bufs[0], None, bufs[1]]
+    out = torch.empty(count, dtype=torch.bfloat16, device="cuda")
+    B.ftar_reduce_masked(table, live, out)
+    torch.cuda.synchronize()
+    starts = _slab_starts(count, [1 << 31, 1 << 32, (1 << 32) + 65536], 12, seed=7)
+    for s in starts:
+        hb = [host_slab(bufs[0], s, s + SLAB), None, host_slab(bufs[1], s, s + SLAB)]
+        assert_same(host_slab(out, s, s + SLAB), oracle.reduce_masked(hb, live, code(torch.bfloat16)), "slab %d" % s)
+    for lo in range(0, count, step):           # every element, with torch's fp32 ops in the same order
+        hi = min(count, lo + step)
+        a = ((bufs[0][lo:hi].float() + bufs[1][lo:hi].float()) * 0.5).to(torch.bfloat16)
+        assert torch.equal(a.view(torch.int16), out[lo:hi].view(torch.int16)), lo
+    # the ring of two in one pass, in place: both buffers end with the mean (addition commutes,
+    # so both portions equal the one-shot result bit for bit)
+    plan = B.ftar_plan(3, live, count, 16384, torch.bfloat16)
+    B.ftar_allreduce_onepass(plan, table)
+    torch.cuda.synchronize()
+    for b in bufs:
+        for lo in range(0, count, step):
+            hi = min(count, lo + step)
+            assert torch.equal(b[lo:hi].view(torch.int16), out[lo:hi].view(torch.int16)), lo
