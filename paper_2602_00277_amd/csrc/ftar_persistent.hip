@@ -200,16 +200,25 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
     const int step = static_cast<int>(ustep);
-    if (step == N - 1) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // first AllGather step: see the block's stores
+    // first AllGather step: see the block's stores
+    if (step == N - 1) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     const int sel = part + 1 == geom.n_parts ? 1 : 0;
     const unsigned long long* seg = s_seg[sel];
     const unsigned long long* til = s_tile[sel];
     const size_t off = static_cast<size_t>(part) * geom.part_elems;
     if (step < N - 1) {
-      if (N == 2) ring_reduce_pass<T, VEC, kRsOnly, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off, zpos);
-      else if (step == 0) ring_reduce_pass<T, VEC, kRsFirst, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off, zpos);
-      else if (step == N - 2) ring_reduce_pass<T, VEC, kRsLast, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off, zpos);
-      else ring_reduce_pass<T, VEC, kRsMid, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off, zpos);
+      if (N == 2)
+        ring_reduce_pass<T, VEC, kRsOnly, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off,
+                                                  zpos);
+      else if (step == 0)
+        ring_reduce_pass<T, VEC, kRsFirst, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off,
+                                                   zpos);
+      else if (step == N - 2)
+        ring_reduce_pass<T, VEC, kRsLast, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off,
+                                                  zpos);
+      else
+        ring_reduce_pass<T, VEC, kRsMid, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off,
+                                                 zpos);
     } else {
       // same tiles, widest copy: kThreads*U*VEC == kThreads*(U*VEC/CV)*CV
       constexpr int CV = VEC == 1 ? 1 : 16 / static_cast<int>(sizeof(T));

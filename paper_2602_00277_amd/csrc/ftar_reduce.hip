@@ -243,11 +243,12 @@ hipError_t bucketed_typed(const PtrTable& all, int n_replicas, const BucketTable
                           int n_buckets, size_t first_elem, size_t bucket_elems, size_t count,
                           const ScaleTable& scales, bool vec, void* out, hipStream_t stream) {
   T* o = static_cast<T*>(out);
+  const LaunchCfg cfg = bucketed_cfg(n_replicas, count * sizeof(T));
   if (vec)
-    return with_policy(bucketed_cfg(n_replicas, count * sizeof(T)), Bucketed<T, VECW>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
-                                         count, scales, o, stream});
-  return with_policy(bucketed_cfg(n_replicas, count * sizeof(T)), Bucketed<T, 1>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems,
-                                    count, scales, o, stream});
+    return with_policy(cfg, Bucketed<T, VECW>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems, count,
+                                              scales, o, stream});
+  return with_policy(cfg, Bucketed<T, 1>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems, count,
+                                         scales, o, stream});
 }
 
 }  // namespace

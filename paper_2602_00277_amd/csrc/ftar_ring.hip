@@ -202,8 +202,11 @@ struct RingOnepass {
       return hipGetLastError();
     }
     switch (N) {
-#define FTAR_CASE(n) \
-  case n: launch(k_ring_onepass<T, VEC, (VEC == 1 ? 0 : n), POL>, grid, block, stream, ring, seg, tiles, N, scale, zpos); break;
+#define FTAR_CASE(n)                                                                                       \
+  case n:                                                                                                  \
+    launch(k_ring_onepass<T, VEC, (VEC == 1 ? 0 : n), POL>, grid, block, stream, ring, seg, tiles, N, scale, \
+           zpos);                                                                                          \
+    break;
       FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7) FTAR_CASE(8)
       FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13) FTAR_CASE(14)
       FTAR_CASE(15) FTAR_CASE(16)
@@ -219,22 +222,24 @@ struct RingOnepass {
 hipError_t launch_ring_reduce(RingMode mode, const PtrTable& ring, int n_live, int step,
                               const SegTable& seg, ftar_dtype_t dtype, bool vec, float* acc,
                               float scale, unsigned long long zpos, hipStream_t stream) {
+  const LaunchCfg cfg = ring_reduce_cfg(mode, seg.begin[n_live]);
   if (dtype == FTAR_F32) {
-    if (vec) return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<float, 4>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
-    return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<float, 1>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
+    if (vec) return with_policy(cfg, RingReduce<float, 4>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
+    return with_policy(cfg, RingReduce<float, 1>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
   }
-  if (vec) return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<bf16, 4>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
-  return with_policy(ring_reduce_cfg(mode, seg.begin[n_live]), RingReduce<bf16, 1>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
+  if (vec) return with_policy(cfg, RingReduce<bf16, 4>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
+  return with_policy(cfg, RingReduce<bf16, 1>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
 }
 
 hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, const SegTable& seg,
                                  ftar_dtype_t dtype, bool vec, hipStream_t stream) {
+  const LaunchCfg cfg = ring_allgather_cfg(seg.begin[n_live], dtype == FTAR_F32 ? 4 : 2);
   if (dtype == FTAR_F32) {
-    if (vec) return with_policy(ring_allgather_cfg(seg.begin[n_live], 4), RingAllgather<float, 4>{ring, n_live, step, seg, stream});
-    return with_policy(ring_allgather_cfg(seg.begin[n_live], 4), RingAllgather<float, 1>{ring, n_live, step, seg, stream});
+    if (vec) return with_policy(cfg, RingAllgather<float, 4>{ring, n_live, step, seg, stream});
+    return with_policy(cfg, RingAllgather<float, 1>{ring, n_live, step, seg, stream});
   }
-  if (vec) return with_policy(ring_allgather_cfg(seg.begin[n_live], 2), RingAllgather<bf16, 8>{ring, n_live, step, seg, stream});
-  return with_policy(ring_allgather_cfg(seg.begin[n_live], 2), RingAllgather<bf16, 1>{ring, n_live, step, seg, stream});
+  if (vec) return with_policy(cfg, RingAllgather<bf16, 8>{ring, n_live, step, seg, stream});
+  return with_policy(cfg, RingAllgather<bf16, 1>{ring, n_live, step, seg, stream});
 }
 
 hipError_t launch_ring_onepass(const PtrTable& ring, int n_live, const SegTable& seg,
