@@ -230,7 +230,8 @@ ftar_status_t ftar_plan_lr_factors(const ftar_plan_t* plan, float* linear, float
  * between the iterations of one all-reduce (paper section 4.2: FTAR may run for
  * several iterations, each exchanging a portion of the gradients; membership is
  * decided by the CPU before each).  Same arithmetic as calling
- * ftar_reduce_masked once per bucket with masks[b]; scale is per bucket.
+ * ftar_reduce_masked once per bucket with masks[b]; scale is per bucket.  (Buckets of half a GiB
+ * of traffic or more are in fact run that way, one after the other on the stream.)
  * masks: HOST array of ceil(count/bucket_elems) masks, each valid for n_replicas.
  */
 ftar_status_t ftar_reduce_masked_bucketed(const void* const* bufs, int n_replicas,
@@ -317,7 +318,8 @@ const char* ftar_status_str(ftar_status_t s); /* static string */
  * blocks_per_cu: workgroups launched per compute unit (0 = each kernel's default);
  * flags: 0 = each kernel's default policy; 0x10 | p = explicit policy p, where bit 0 of p
  * asks for non-temporal loads and bit 1 for non-temporal stores; 0x20 = wide tiles in the
- * one-shot reduce; 0x40 = never split a long one-shot reduce into several launches;
+ * one-shot reduce; 0x40 = never split a long one-shot reduce into several launches and never run big
+ * buckets one by one;
  * bits 8..11 = vectors per lane and tile in the ring kernels (2, 4 or 8). */
 void ftar_set_tuning(int blocks_per_cu, int flags);
 
