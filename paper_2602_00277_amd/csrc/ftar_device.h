@@ -49,16 +49,25 @@ template <> struct Raw<bf16, 8> { typedef u32x4 type; };
 template <> struct Raw<bf16, 4> { typedef u32x2 type; };
 template <> struct Raw<bf16, 1> { typedef uint16_t type; };
 
+// Every pointer the kernels dereference is device (global) memory, but most of them reach the
+// kernels through a table, as generic pointers.  Saying "global" at the access gives global_load /
+// global_store instead of flat ones: those return in order, so the compiler may wait for just the
+// loads a computation needs (s_waitcnt vmcnt(k)) and sum the first vectors of a tile while the
+// last ones are still in flight; a flat load forces a wait for everything outstanding.
+#define FTAR_GLOBAL __attribute__((address_space(1)))
+
 template <int POL, typename R>
 __device__ __forceinline__ R ld(const R* p) {
-  if constexpr ((POL & 1) != 0) return __builtin_nontemporal_load(p);
-  else return *p;
+  const FTAR_GLOBAL R* g = (const FTAR_GLOBAL R*)p;
+  if constexpr ((POL & 1) != 0) return __builtin_nontemporal_load(g);
+  else return *g;
 }
 
 template <int POL, typename R>
 __device__ __forceinline__ void st(R* p, R v) {
-  if constexpr ((POL & 2) != 0) __builtin_nontemporal_store(v, p);
-  else *p = v;
+  FTAR_GLOBAL R* g = (FTAR_GLOBAL R*)p;
+  if constexpr ((POL & 2) != 0) __builtin_nontemporal_store(v, g);
+  else *g = v;
 }
 
 // ---- widening: exact -------------------------------------------------------
@@ -417,7 +426,7 @@ __device__ __forceinline__ void ring_allgather_pass(T* const* s_tab, const unsig
         st<POL>(reinterpret_cast<R*>(to) + v, ld<POL>(reinterpret_cast<const R*>(from) + v));
       if constexpr (VEC > 1) {
         const size_t e = n_vec * VEC + tid;
-        if (e < t.rem) reinterpret_cast<R1*>(to)[e] = reinterpret_cast<const R1*>(from)[e];
+        if (e < t.rem) st<POL>(reinterpret_cast<R1*>(to) + e, ld<POL>(reinterpret_cast<const R1*>(from) + e));
       }
     }
   }
