@@ -21,9 +21,8 @@ def B():
 @pytest.mark.parametrize("n_live", list(range(1, 18)) + [20])
 @pytest.mark.parametrize("sum_only", [False, True], ids=["mean", "sum"])
 def test_f32_result_from_bf16_inputs(B, oracle, n_live, sum_only):
-    n = n_live + 2
-    live = ((1 << n) - 1) & ~0b1010 if n > 3 else (1 << n_live) - 1
-    n = max(n, live.bit_length())
+    n = n_live + 2                                   # replicas 1 and 3 are dead
+    live = 0b1 if n_live == 1 else ((1 << n) - 1) & ~0b1010
     count = 256 * 4 * 8 * 3 + 4 * 37 + 3          # several tiles of every unroll, a vector tail, an element tail
     say("bf16 -> f32", n_live, "sum" if sum_only else "mean")
     bufs = rand_bufs(n, count, torch.bfloat16, seed=60 + n_live, dist="student_t3", mask=live)
@@ -87,9 +86,8 @@ def test_unknown_operation_and_type_codes(B):
 @pytest.mark.parametrize("n_live", [1, 2, 3, 7, 8, 16, 17])
 @pytest.mark.parametrize("sum_only", [False, True], ids=["mean", "sum"])
 def test_bf16_result_from_f32_inputs(B, oracle, n_live, sum_only):
-    n, live = n_live + 1, ((1 << (n_live + 1)) - 1) & ~0b10 if n_live > 1 else 0b01
-    if n_live > 1:
-        n, live = n_live + 1, ((1 << (n_live + 1)) - 1) & ~0b10
+    n = n_live + 1                                   # replica 1 is dead
+    live = ((1 << n) - 1) & ~0b10
     count = 256 * 4 * 4 * 3 + 4 * 19 + 2
     say("f32 -> bf16", n_live, "sum" if sum_only else "mean")
     bufs = rand_bufs(n, count, torch.float32, seed=80 + n_live, dist="student_t3", mask=live)
