@@ -137,6 +137,31 @@ def all_configs_report(path, B, W, torch, np):
         print(rows[-1], file=sys.stderr, flush=True)
 
     cfgs = W.configs()
+    # ---- this box's own ceilings: bare streaming kernels, dispatch-recorded times --------
+    ceil_rows = []
+    ev = HipEvents()
+    pairs = [(ev.create(), ev.create()) for _ in range(20)]
+    for mib in (128, 1024):
+        words = mib * W.M // 4
+        pool = [torch.randint(-2**31, 2**31 - 1, (words,), dtype=torch.int32, device=dev) for _ in range(9)]
+        for n_read, n_written in ((8, 0), (1, 0), (0, 1), (0, 8), (1, 1), (7, 1), (8, 1), (4, 4)):
+            if n_read + n_written > len(pool):
+                continue
+            rd, wr = pool[:n_read], pool[n_read:n_read + n_written]
+            for _ in range(2):
+                B.ftar_probe_stream(rd, wr, fill=1)
+            for a, b in pairs:
+                B.ftar_time_next_launch(a, b)
+                B.ftar_probe_stream(rd, wr, fill=1)
+            torch.cuda.synchronize()
+            ts = sorted(ev.elapsed_s(a, b) for a, b in pairs)
+            t = ts[len(ts) // 2]
+            gbs = (n_read + n_written) * mib * W.M / 1e9 / t
+            ceil_rows.append("| %d MiB | %d | %d | %.1f | %.0f | %.1f |" % (mib, n_read, n_written, t * 1e6, gbs,
+                                                                        100 * gbs / HBM_PEAK_GBS))
+            print(ceil_rows[-1], file=sys.stderr, flush=True)
+        del pool
+        torch.cuda.empty_cache()
     # ---- one-shot reduces: cfg 1, 2, 4 -------------------------------------------------
     for idx in (0, 1, 3):
         w = cfgs[idx]
@@ -354,6 +379,11 @@ def all_configs_report(path, B, W, torch, np):
             "| worker workgroups | " + " | ".join(str(nb) for nb, _ in curve) + " |",
             "|---|" + "---|" * len(curve),
             "| GB/s | " + " | ".join("%.0f" % g for _, g in curve) + " |"]
+    tail += ["", "## What the memory system gives: bare streaming kernels on this GPU", "",
+             "`ftar_probe_stream`: r buffers read and w buffers written by a kernel that does nothing else "
+             "(16-byte lanes, non-temporal accesses, one workgroup per compute unit for five or more streams, "
+             "random data; median of 20 launches, dispatch-recorded times).", "",
+             "| stream size | read | written | us | GB/s | % of 8 TB/s |", "|---|---|---|---|---|---|"] + ceil_rows
     tail += ["", "## Other work next to the persistent ring (cfg 3a buffers)", "",
              "40 launches in a row on a second stream of the same priority: alone, next to a ring whose two "
              "worker workgroups only wait (nothing released), and next to a running ring with 2 and 8 worker "

@@ -331,6 +331,16 @@ void ftar_set_tuning(int blocks_per_cu, int flags);
  * cleared.  The caller owns the events. */
 void ftar_time_next_launch(void* start_event, void* stop_event);
 
+/* Measurement only: a bare streaming kernel over n_read + n_written device buffers of `bytes`
+ * bytes each (bufs: HOST array, the read buffers first; 16-byte aligned; bytes a multiple of 32 KiB).
+ * The first n_read are read, each of the others receives the xor of the read ones at the same
+ * offset (or the 32-bit word `fill` when n_read == 0); with n_written == 0 nothing is stored.
+ * It gives this GPU's own ceiling for a mix of streams, next to which the reduce and ring kernels
+ * are judged.  Mixes offered: reads only 1/2/4/8/16, writes only 1/2/4/8, r+1 for r = 1,2,3,4,7,8,16,
+ * 4+4, 8+8; anything else FTAR_ERR_INVALID_ARG.  Honours ftar_set_tuning and ftar_time_next_launch. */
+ftar_status_t ftar_probe_stream(void* const* bufs, int n_read, int n_written, size_t bytes, uint32_t fill,
+                                void* stream);
+
 #ifdef __cplusplus
 }
 #endif

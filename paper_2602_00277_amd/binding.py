@@ -45,6 +45,7 @@ EXPORTS = [
     "ftar_plan_set_partition", "ftar_plan_n_partitions", "ftar_plan_n_slots",
     "ftar_plan_partition_segment", "ftar_allreduce_onepass", "ftar_plan_set_zero_mask",
     "ftar_reduce_masked_zero", "ftar_plan_set_op", "ftar_reduce_masked_ex", "ftar_plan_lr_factors",
+    "ftar_probe_stream",
 ]
 
 _lib = None
@@ -121,6 +122,8 @@ def lib():
     L.ftar_reduce_masked_ex.argtypes = [vp, ci, u64, u64, ci, sz, ci, ci, ci, vp, vp]
     L.ftar_plan_lr_factors.restype = ci
     L.ftar_plan_lr_factors.argtypes = [vp, vp, vp]
+    L.ftar_probe_stream.restype = ci
+    L.ftar_probe_stream.argtypes = [vp, ci, ci, sz, ctypes.c_uint32, vp]
     L.ftar_allreduce_onepass.restype = ci
     L.ftar_allreduce_onepass.argtypes = [vp, vp, vp]
     L.ftar_ctrl_create.restype = vp
@@ -371,6 +374,19 @@ def ftar_reduce_masked_bucketed(bufs: Sequence[Optional[torch.Tensor]], masks: S
     if st != FTAR_OK:
         raise FtarError(st, "ftar_reduce_masked_bucketed")
     return out
+
+
+def ftar_probe_stream(read: Sequence[torch.Tensor], written: Sequence[torch.Tensor], fill: int = 0,
+                      stream=None) -> None:
+    """Measurement only: bare streaming kernel over equally sized buffers."""
+    bufs = list(read) + list(written)
+    nbytes = bufs[0].numel() * bufs[0].element_size()
+    for b in bufs:
+        if not b.is_cuda or not b.is_contiguous() or b.numel() * b.element_size() != nbytes:
+            raise ValueError("probe buffers must be contiguous GPU tensors of one size")
+    st = lib().ftar_probe_stream(_ptr_array(bufs), len(read), len(written), nbytes, fill, _stream_handle(stream))
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_probe_stream")
 
 
 def ftar_set_tuning(blocks_per_cu: int = 0, flags: int = 0) -> None:

@@ -12,7 +12,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libftar.so")
 
-SOURCES = ["ftar_reduce.hip", "ftar_ring.hip", "ftar_persistent.hip", "ftar_api.cpp"]
+SOURCES = ["ftar_reduce.hip", "ftar_ring.hip", "ftar_persistent.hip", "ftar_probe.hip", "ftar_api.cpp"]
 HEADERS = ["ftar_internal.h", "ftar_device.h"]
 
 FLAGS = [

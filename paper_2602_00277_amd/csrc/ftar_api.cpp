@@ -588,6 +588,22 @@ const char* ftar_status_str(ftar_status_t s) {
   return "unknown status";
 }
 
+ftar_status_t ftar_probe_stream(void* const* bufs, int n_read, int n_written, size_t bytes, uint32_t fill,
+                                void* stream) {
+  if (!bufs || n_read < 0 || n_written < 0 || n_read + n_written < 1 || n_read + n_written > kMaxReplicas ||
+      bytes == 0 || bytes % (32 * 1024) != 0)
+    return fail(FTAR_ERR_INVALID_ARG);
+  PtrTable tab;
+  std::memset(&tab, 0, sizeof(tab));
+  for (int j = 0; j < n_read + n_written; ++j) {
+    if (!bufs[j] || !aligned(bufs[j], 16)) return fail(FTAR_ERR_INVALID_ARG);
+    tab.p[j] = bufs[j];
+  }
+  hipError_t e = launch_probe_stream(tab, n_read, n_written, bytes / 16, fill, static_cast<hipStream_t>(stream));
+  if (e == hipErrorInvalidValue) return fail(FTAR_ERR_INVALID_ARG);
+  return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
+}
+
 void ftar_time_next_launch(void* start_event, void* stop_event) {
   t_time_start = static_cast<hipEvent_t>(start_event);
   t_time_stop = static_cast<hipEvent_t>(stop_event);

@@ -123,6 +123,11 @@ hipError_t launch_ring_persistent(const PtrTable& ring, int n_live, const PartGe
                                   DevCtrl* mirror, unsigned n_blocks, unsigned long long timeout_ticks,
                                   unsigned flags, unsigned long long zpos, hipStream_t stream);
 
+// Measurement only: n_read streams read and n_written streams written, n_vec 16-byte vectors each
+// (tab: the read streams first).  Written streams receive the xor of the read ones, or `fill`.
+hipError_t launch_probe_stream(const PtrTable& tab, int n_read, int n_written, size_t n_vec, uint32_t fill,
+                               hipStream_t stream);
+
 }  // namespace ftar
 
 #endif  // FTAR_INTERNAL_H_

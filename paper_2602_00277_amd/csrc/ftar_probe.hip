@@ -1,0 +1,79 @@
+// Bare streaming kernels that measure what this GPU's memory system gives for a mix of read and
+// written streams - the ceilings the product kernels are compared with.  Measurement only: no
+// arithmetic of the method (words are folded with xor so that the loads cannot be dropped).
+
+#include "ftar_device.h"
+
+namespace ftar {
+namespace {
+
+// NR read streams, NW written streams, all of n_vec 16-byte vectors.  Every written stream gets
+// the xor of the read vectors at the same index (or `fill` when nothing is read).  With NW == 0
+// nothing is stored unless the folded word equals `never` in all four lanes of a vector.
+template <int NR, int NW, int U, int POL>
+__global__ void __launch_bounds__(kThreads)
+k_probe_stream(PtrTable tab, size_t n_vec, uint32_t fill, uint32_t never) {
+  __shared__ u32x4* s_tab[kMaxReplicas];
+  if (threadIdx.x < static_cast<unsigned>(NR + NW)) s_tab[threadIdx.x] = static_cast<u32x4*>(tab.p[threadIdx.x]);
+  __syncthreads();
+  u32x4* p[NR + NW];
+#pragma unroll
+  for (int j = 0; j < NR + NW; ++j) p[j] = uniform_ptr(s_tab[j]);
+  constexpr size_t kTile = static_cast<size_t>(kThreads) * U;
+  const size_t n_tiles = n_vec / kTile;  // the host passes whole tiles only
+  for (size_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+    const size_t v = t * kTile + threadIdx.x;
+    u32x4 x[U][NR > 0 ? NR : 1];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int j = 0; j < NR; ++j) x[u][j] = ld<POL>(p[j] + v + u * kThreads);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      u32x4 f = {fill, fill, fill, fill};
+#pragma unroll
+      for (int j = 0; j < NR; ++j) f = j == 0 ? x[u][0] : f ^ x[u][j];
+      if constexpr (NW > 0) {
+#pragma unroll
+        for (int w = 0; w < NW; ++w) st<POL>(p[NR + w] + v + u * kThreads, f);
+      } else {
+        if (f[0] == never && f[1] == never && f[2] == never && f[3] == never) st<POL>(p[0] + v + u * kThreads, f);
+      }
+    }
+  }
+}
+
+constexpr int probe_unroll(int streams) { return streams <= 2 ? 8 : streams <= 4 ? 4 : streams <= 8 ? 2 : 1; }
+
+template <int NR, int NW>
+struct Probe {
+  const PtrTable& tab; size_t n_vec; uint32_t fill; hipStream_t stream;
+  template <int POL> hipError_t operator()(unsigned blocks) const {
+    constexpr int U = probe_unroll(NR + NW);
+    const size_t tiles = n_vec / (static_cast<size_t>(kThreads) * U);
+    launch(k_probe_stream<NR, NW, U, POL>, dim3(grid_x_for(tiles, blocks)), dim3(kThreads), stream, tab, n_vec, fill,
+           0x9e3779b9u);
+    return hipGetLastError();
+  }
+};
+
+}  // namespace
+
+// Supported mixes only; anything else: hipErrorInvalidValue.
+hipError_t launch_probe_stream(const PtrTable& tab, int n_read, int n_written, size_t n_vec, uint32_t fill,
+                               hipStream_t stream) {
+  // one workgroup per CU and non-temporal accesses unless the tuning says otherwise, like the
+  // product kernels with many streams
+  const LaunchCfg cfg = launch_cfg(n_read + n_written <= 2 ? 4 : n_read + n_written <= 4 ? 2 : 1, 3);
+#define FTAR_PROBE(r, w) \
+  if (n_read == r && n_written == w) return with_policy(cfg, Probe<r, w>{tab, n_vec, fill, stream});
+  FTAR_PROBE(1, 0) FTAR_PROBE(2, 0) FTAR_PROBE(4, 0) FTAR_PROBE(8, 0) FTAR_PROBE(16, 0)
+  FTAR_PROBE(0, 1) FTAR_PROBE(0, 2) FTAR_PROBE(0, 4) FTAR_PROBE(0, 8)
+  FTAR_PROBE(1, 1) FTAR_PROBE(2, 1) FTAR_PROBE(3, 1) FTAR_PROBE(4, 1) FTAR_PROBE(7, 1) FTAR_PROBE(8, 1) FTAR_PROBE(16, 1)
+  FTAR_PROBE(4, 4) FTAR_PROBE(8, 8)
+#undef FTAR_PROBE
+  return hipErrorInvalidValue;
+}
+
+}  // namespace ftar
