@@ -381,8 +381,9 @@ def all_configs_report(path, B, W, torch, np):
             "| GB/s | " + " | ".join("%.0f" % g for _, g in curve) + " |"]
     tail += ["", "## What the memory system gives: bare streaming kernels on this GPU", "",
              "`ftar_probe_stream`: r buffers read and w buffers written by a kernel that does nothing else "
-             "(16-byte lanes, non-temporal accesses, one workgroup per compute unit for five or more streams, "
-             "random data; median of 20 launches, dispatch-recorded times).", "",
+             "(16-byte lanes, non-temporal loads, non-temporal stores when more than 256 MiB are written, "
+             "one workgroup per compute unit for five or more streams, random data; median of 20 launches, "
+             "dispatch-recorded times).", "",
              "| stream size | read | written | us | GB/s | % of 8 TB/s |", "|---|---|---|---|---|---|"] + ceil_rows
     tail += ["", "## Other work next to the persistent ring (cfg 3a buffers)", "",
              "40 launches in a row on a second stream of the same priority: alone, next to a ring whose two "

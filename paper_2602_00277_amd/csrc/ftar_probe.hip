@@ -63,9 +63,10 @@ struct Probe {
 // Supported mixes only; anything else: hipErrorInvalidValue.
 hipError_t launch_probe_stream(const PtrTable& tab, int n_read, int n_written, size_t n_vec, uint32_t fill,
                                hipStream_t stream) {
-  // one workgroup per CU and non-temporal accesses unless the tuning says otherwise, like the
-  // product kernels with many streams
-  const LaunchCfg cfg = launch_cfg(n_read + n_written <= 2 ? 4 : n_read + n_written <= 4 ? 2 : 1, 3);
+  // the product kernels' own choices unless the tuning says otherwise: one workgroup per CU from
+  // five streams on, non-temporal loads, ordinary stores while what is written fits the cache
+  const bool fits = static_cast<size_t>(n_written) * n_vec * 16 <= 256 * kMiB;
+  const LaunchCfg cfg = launch_cfg(n_read + n_written <= 2 ? 4 : n_read + n_written <= 4 ? 2 : 1, fits ? 1 : 3);
 #define FTAR_PROBE(r, w) \
   if (n_read == r && n_written == w) return with_policy(cfg, Probe<r, w>{tab, n_vec, fill, stream});
   FTAR_PROBE(1, 0) FTAR_PROBE(2, 0) FTAR_PROBE(4, 0) FTAR_PROBE(8, 0) FTAR_PROBE(16, 0)
