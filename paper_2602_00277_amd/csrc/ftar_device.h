@@ -1,18 +1,17 @@
 // Device helpers and launch plumbing shared by the kernel files (ftar_reduce.hip, ftar_ring.hip,
-// ftar_persistent.hip).  Everything here is a template or inline and lives in an unnamed
-// namespace: each file gets its own copy.
+// ftar_persistent.hip, ftar_probe.hip).  Everything here is a template or inline and lives in an
+// unnamed namespace: each file gets its own copy.
 //
-//
-// Everything here is a streaming, HBM-bandwidth-bound elementwise pass: a few
+// Every kernel built from these is a streaming, HBM-bandwidth-bound elementwise pass: a few
 // fp32 additions per 16-byte load, no data reuse, no contraction - so no MFMA
 // and no LDS tiling of data.  What matters is (1) every wave instruction
 // touching a contiguous run of full cache lines (lane t reads 16 bytes at
 // 16*t: 1 KiB per wave instruction), (2) many independent loads in flight per
 // lane before the first use (the paper's instruction-level-parallelism remark,
-// section 4.2 "Optimizations", applied at full rather than minimal occupancy),
-// (3) a persistent grid that strides over tiles so consecutive tiles are in
-// flight on different XCDs at the same time, and (4) non-temporal accesses,
-// since no byte is touched twice.  LDS holds only the compact pointer table the
+// section 4.2 "Optimizations"), (3) a persistent grid of few workgroups that
+// strides over tiles, so the whole chip works inside one narrow window of every
+// stream, and (4) non-temporal loads, since no byte is read twice (stores are
+// non-temporal only where nobody reads the data soon).  LDS holds only the compact pointer table the
 // CPU resolved from the live mask; pointers are pulled from it into scalar
 // registers, so address arithmetic stays on the scalar unit.
 //
