@@ -398,6 +398,64 @@ def all_configs_report(path, B, W, torch, np):
         sys.exit(1)
 
 
+def full_size_launches(B, W, torch):
+    """Every product kernel of the full-size workloads once, one workload after the other, for a
+    run under `rocprofv3 --pmc` (FETCH_SIZE or WRITE_SIZE).  Prints the algorithmic bytes that each
+    group of dispatches is expected to move, in dispatch order, as one JSON line."""
+    dev = "cuda:0"
+    cfgs = W.configs()
+    groups = []
+    # a plain copy of known size first: the counters' scale factors come from it
+    a = torch.empty(128 * W.M, dtype=torch.uint8, device=dev)
+    b = torch.empty_like(a)
+    b.copy_(a)
+    torch.cuda.synchronize()
+    for idx in (1, 3):
+        w = cfgs[idx]
+        bufs = W.draw_replicas(w, dev)
+        out = torch.empty(w.count, dtype=w.dtype, device=dev)
+        torch.cuda.synchronize()
+        B.ftar_reduce_masked(bufs, w.live_mask, out)
+        torch.cuda.synchronize()
+        N = bin(w.live_mask).count("1")
+        groups.append({"workload": w.name, "kernel": "k_reduce_masked", "read": N * w.elem_bytes * w.count,
+                       "written": w.elem_bytes * w.count})
+        del bufs, out
+        torch.cuda.empty_cache()
+    w = cfgs[2]
+    E = w.elem_bytes
+    bufs = W.draw_replicas(w, dev)
+    acc = torch.empty(w.count, dtype=torch.float32, device=dev)
+    plan = B.ftar_plan(w.n_replicas, 0xFFFF, w.count, w.chunk_elems, w.dtype)
+    torch.cuda.synchronize()
+    B.ring_allreduce(plan, bufs, acc)
+    torch.cuda.synchronize()
+    N = 16
+    groups.append({"workload": w.name, "kernel": "k_ring_reduce",
+                   "read": (2 * E + (N - 3) * (4 + E) + (4 + E)) * w.count,
+                   "written": (4 + (N - 3) * 4 + E) * w.count})
+    groups.append({"workload": w.name, "kernel": "k_ring_allgather", "read": (N - 1) * E * w.count,
+                   "written": (N - 1) * E * w.count})
+    B.ftar_allreduce_onepass(plan, bufs)
+    torch.cuda.synchronize()
+    groups.append({"workload": w.name, "kernel": "k_ring_onepass", "read": N * E * w.count,
+                   "written": N * E * w.count})
+    del bufs, acc
+    torch.cuda.empty_cache()
+    w = cfgs[4]
+    edges = W.bucket_bounds(w.count, w.bucket_elems)
+    masks = W.bucket_masks(w.n_replicas, len(edges) - 1, w.bucket_p_live, w.seed)
+    bufs = W.draw_replicas(w, dev)
+    out = torch.empty(w.count, dtype=w.dtype, device=dev)
+    torch.cuda.synchronize()
+    B.ftar_reduce_masked_bucketed(bufs, masks, w.bucket_elems, out)
+    torch.cuda.synchronize()
+    groups.append({"workload": w.name, "kernel": "k_reduce_masked",
+                   "read": sum((edges[i + 1] - edges[i]) * 4 * bin(m).count("1") for i, m in enumerate(masks)),
+                   "written": 4 * w.count})
+    print(json.dumps({"copy_bytes": 128 * W.M, "groups": groups}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -409,6 +467,9 @@ def main():
                     help="instead of the step benchmark, run the five benchmark workloads at full "
                          "size (parity on sampled slabs, timing, oracle timing on a sample) and "
                          "write a markdown report to PATH")
+    ap.add_argument("--full-size-launches", action="store_true",
+                    help="launch every product kernel of the full-size workloads once (for a run under "
+                         "rocprofv3 --pmc) and print the bytes each group of dispatches should move")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (simulated replicas are separate buffers on "
@@ -428,6 +489,9 @@ def main():
     dev = "cuda:0"
     if args.all_configs:
         all_configs_report(args.all_configs, B, W, torch, np)
+        return
+    if args.full_size_launches:
+        full_size_launches(B, W, torch)
         return
 
     w = W.configs()[1]
