@@ -33,6 +33,9 @@
  *     Following the paper's split (section 4.2, "Timeout and error handling"):
  *     caller errors and device errors are not retryable; the retryable class
  *     is reserved for a membership change while work is queued.
+ *   - Host threads may call at the same time, each on a stream of its own: the library
+ *     holds no lock, a plan is only read by the compute calls, the last error and the
+ *     timing events are per thread, the tuning is process-wide.
  *   - Arithmetic: inputs are widened exactly to fp32; sums are fp32 additions
  *     in a fixed order; the mean is ONE multiplication by
  *     scale = 1.0f/(float)n_live (one correctly rounded fp32 division, done on
