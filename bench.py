@@ -330,6 +330,17 @@ def all_configs_report(path, B, W, torch, np):
             add_row(w.name, "3a persistent kernel, partitions of 4 Mi elements (%d slots)" % n_steps, gb, med, mn,
                     st == 0 and done == n_steps, float("nan"), "-")
             plan.set_partition(0)
+            # the ReduceScatter steps as they are, the AllGather phase in one pass
+            Np = plan.n_live
+
+            def rs_then_gather_all():
+                for st_ in range(Np - 1):
+                    B.ftar_reduce_step(plan, st_, bufs, acc)
+                B.ftar_allgather_all(plan, bufs)
+            own_gb = ((2 * E + 4) + (Np - 3) * (8 + E) + (4 + 2 * E) + Np * E) * w.count / 1e9
+            med, mn = time_schedule(rs_then_gather_all, 5)
+            add_row(w.name, "3a 15 RS steps + ftar_allgather_all (own bytes: E + (N-1)E for the gather)", own_gb, med, mn,
+                    True, float("nan"), "-")
             # the same result in one pass: its own algorithmic bytes are 2*N*E per element
             own_gb = 2 * plan.n_live * E * w.count / 1e9
             med, mn = time_schedule(lambda: B.ftar_allreduce_onepass(plan, bufs), 5)

@@ -243,6 +243,17 @@ ftar_status_t ftar_reduce_masked_bucketed(const void* const* bufs, int n_replica
                                           void* out, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * ftar_allgather_all - what the N-1 ftar_allgather_step calls of the plan leave in the replica
+ * buffers, in ONE pass: every portion is read once from the buffer of the replica that holds its
+ * finished value after the ReduceScatter phase (ring position k-1 for portion k; paper section
+ * 4.2, "Ring algorithm") and written to the N-1 other live buffers.  The ring hands a portion on
+ * one neighbour per step because a network sits between the replicas; with all buffers on one
+ * device this moves E + (N-1)E bytes per element instead of 2(N-1)E.  Bit copies: the same result
+ * as the step calls.  Call it after the last ftar_reduce_step.  N == 1: nothing to do.
+ */
+ftar_status_t ftar_allgather_all(const ftar_plan_t* plan, void* const* bufs, void* stream);
+
+/* ---------------------------------------------------------------------------
  * ftar_allreduce_onepass - what the whole schedule of the plan (N-1 ftar_reduce_step calls, then
  * N-1 ftar_allgather_step calls) leaves in the replica buffers, computed in ONE pass: every
  * element's N contributions are added in a register in the ring's order (portion k: ring

@@ -325,6 +325,19 @@ ftar_status_t ftar_allgather_step(const ftar_plan_t* plan, int step, void* const
   return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
 }
 
+ftar_status_t ftar_allgather_all(const ftar_plan_t* plan, void* const* bufs, void* stream) {
+  if (!plan_ok(plan) || !bufs || plan->part_elems != 0) return fail(FTAR_ERR_INVALID_ARG);
+  const int N = plan->n_live;
+  PtrTable tab;
+  std::memset(&tab, 0, sizeof(tab));
+  bool vec = true;
+  ftar_status_t s = ring_table(plan, bufs, &tab, &vec);
+  if (s != FTAR_OK) return fail(s);
+  if (N < 2) return FTAR_OK;  // nothing to hand round
+  hipError_t e = launch_ring_allgather_all(tab, N, plan->seg, plan->dtype, vec, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
+}
+
 static ftar_status_t reduce_masked_common(const void* const* bufs, int n_replicas, uint64_t live_mask,
                                           uint64_t zero_mask, int contributors_only, size_t count,
                                           ftar_dtype_t dtype, ftar_dtype_t out_dtype, ftar_op_t op,

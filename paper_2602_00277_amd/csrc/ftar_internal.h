@@ -102,6 +102,10 @@ hipError_t launch_ring_reduce(RingMode mode, const PtrTable& ring, int n_live, i
 hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, const SegTable& seg,
                                  ftar_dtype_t dtype, bool vec, hipStream_t stream);
 
+// All N-1 AllGather steps in one pass: each portion from its owner's buffer into the others.
+hipError_t launch_ring_allgather_all(const PtrTable& ring, int n_live, const SegTable& seg, ftar_dtype_t dtype,
+                                     bool vec, hipStream_t stream);
+
 // The whole ring in one kernel, gated by the control block (ctrl_dev = device view of it).
 // What the whole ring schedule leaves in the buffers, in one pass (N reads, N writes per element).
 hipError_t launch_ring_onepass(const PtrTable& ring, int n_live, const SegTable& seg,

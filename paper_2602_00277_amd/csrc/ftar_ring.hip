@@ -147,6 +147,68 @@ k_ring_onepass(PtrTable ring, SegTable seg, SegTable tile0, int N, float scale, 
   }
 }
 
+// ---- the whole AllGather phase in one pass ---------------------------------------
+// After the ReduceScatter phase portion k is final in the buffer of ring position k-1.  The N-1
+// AllGather steps hand it round the ring, one neighbour per step, because a network forces that;
+// on one device the owner's copy can be read once and written to the N-1 other buffers directly:
+// E + (N-1)E bytes per element instead of 2(N-1)E.  Same bits, of course (bit copies).
+template <typename T, int VEC, int U, int POL>
+__global__ void __launch_bounds__(kThreads)
+k_ring_allgather_all(PtrTable ring, SegTable seg, SegTable tile0, int N) {
+  typedef typename Raw<T, VEC>::type R;
+  typedef typename Raw<T, 1>::type R1;
+  __shared__ T* s_tab[kMaxReplicas];
+  __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
+  stage_ring_tables<T>(ring, seg, tile0, N, s_tab, s_seg, s_tile);
+  constexpr size_t kTileElems = static_cast<size_t>(kThreads) * U * VEC;
+  const unsigned tid = threadIdx.x;
+  const size_t total = uniform_u64(s_tile[N]);
+  int k = 0;
+  size_t next = uniform_u64(s_tile[1]);
+  for (size_t g = blockIdx.x; g < total; g += gridDim.x) {
+    const RingTile t = ring_tile_of<kTileElems>(g, k, next, s_seg, s_tile);
+    const int owner = (t.k + N - 1) % N;
+    const T* from = uniform_ptr(s_tab[owner]) + t.begin;
+    if (t.rem >= kTileElems) {
+      R raw[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) raw[u] = ld<POL>(reinterpret_cast<const R*>(from) + tid + u * kThreads);
+      for (int m = 1; m < N; ++m) {
+        T* to = uniform_ptr(s_tab[(owner + m) % N]) + t.begin;
+#pragma unroll
+        for (int u = 0; u < U; ++u) st<POL>(reinterpret_cast<R*>(to) + tid + u * kThreads, raw[u]);
+      }
+    } else {
+      const size_t n_vec = t.rem / VEC;
+      for (size_t v = tid; v < n_vec; v += kThreads) {
+        const R x = ld<POL>(reinterpret_cast<const R*>(from) + v);
+        for (int m = 1; m < N; ++m)
+          st<POL>(reinterpret_cast<R*>(uniform_ptr(s_tab[(owner + m) % N]) + t.begin) + v, x);
+      }
+      if constexpr (VEC > 1) {
+        const size_t e = n_vec * VEC + tid;
+        if (e < t.rem) {
+          const R1 x = ld<POL>(reinterpret_cast<const R1*>(from) + e);
+          for (int m = 1; m < N; ++m)
+            st<POL>(reinterpret_cast<R1*>(uniform_ptr(s_tab[(owner + m) % N]) + t.begin) + e, x);
+        }
+      }
+    }
+  }
+}
+
+template <typename T, int VEC>
+struct RingAllgatherAll {
+  const PtrTable& ring; int N; const SegTable& seg; hipStream_t stream;
+  template <int POL> hipError_t operator()(unsigned blocks) const {
+    constexpr int U = 4;
+    const SegTable tiles = ring_tiles(seg, N, VEC, U);
+    const dim3 grid(grid_x_for(tiles.begin[N], blocks)), block(kThreads);
+    launch(k_ring_allgather_all<T, VEC, U, POL>, grid, block, stream, ring, seg, tiles, N);
+    return hipGetLastError();
+  }
+};
+
 template <typename T, int VEC>
 struct RingReduce {
   RingMode mode; const PtrTable& ring; int N; int step; const SegTable& seg; float* acc; float scale;
@@ -240,6 +302,18 @@ hipError_t launch_ring_allgather(const PtrTable& ring, int n_live, int step, con
   }
   if (vec) return with_policy(cfg, RingAllgather<bf16, 8>{ring, n_live, step, seg, stream});
   return with_policy(cfg, RingAllgather<bf16, 1>{ring, n_live, step, seg, stream});
+}
+
+hipError_t launch_ring_allgather_all(const PtrTable& ring, int n_live, const SegTable& seg, ftar_dtype_t dtype,
+                                     bool vec, hipStream_t stream) {
+  // one read stream, N-1 written ones: as the one-pass all-reduce
+  const LaunchCfg cfg = launch_cfg(1, 3);
+  if (dtype == FTAR_F32) {
+    if (vec) return with_policy(cfg, RingAllgatherAll<float, 4>{ring, n_live, seg, stream});
+    return with_policy(cfg, RingAllgatherAll<float, 1>{ring, n_live, seg, stream});
+  }
+  if (vec) return with_policy(cfg, RingAllgatherAll<bf16, 8>{ring, n_live, seg, stream});
+  return with_policy(cfg, RingAllgatherAll<bf16, 1>{ring, n_live, seg, stream});
 }
 
 hipError_t launch_ring_onepass(const PtrTable& ring, int n_live, const SegTable& seg,

@@ -123,11 +123,15 @@ def test_random_option_draw(B, oracle, seed):
     acc_store = torch.empty(count + 16, dtype=torch.float32, device="cuda")
     acc = acc_store[c["offset"]:c["offset"] + count]
     ctrl = B.ftar_ctrl_create()
-    for name in ("steps", "onepass", "persistent", "partitioned"):
+    for name in ("steps", "gather_all", "onepass", "persistent", "partitioned"):
         bufs = [s.clone()[c["offset"]:c["offset"] + count] for s in store]
         ref = want
         if name == "steps":
             B.ring_allreduce(plan, bufs, acc)
+        elif name == "gather_all":
+            for step in range(plan.n_steps):
+                B.ftar_reduce_step(plan, step, bufs, acc)
+            B.ftar_allgather_all(plan, bufs)
         elif name == "onepass":
             B.ftar_allreduce_onepass(plan, bufs)
         else:
