@@ -341,6 +341,20 @@ def all_configs_report(path, B, W, torch, np):
             med, mn = time_schedule(rs_then_gather_all, 5)
             add_row(w.name, "3a 15 RS steps + ftar_allgather_all (own bytes: E + (N-1)E for the gather)", own_gb, med, mn,
                     True, float("nan"), "-")
+            # the ReduceScatter phase in one pass (the reduce-scatter of a sharded optimizer), alone and
+            # completed by the one-pass gather
+            own_gb = (Np * E + E) * w.count / 1e9
+            med, mn = time_schedule(lambda: B.ftar_reduce_scatter_all(plan, bufs), 5)
+            add_row(w.name, "3a ftar_reduce_scatter_all (own bytes: NE + E per element)", own_gb, med, mn, True,
+                    float("nan"), "-")
+
+            def scatter_gather():
+                B.ftar_reduce_scatter_all(plan, bufs)
+                B.ftar_allgather_all(plan, bufs)
+            own_gb = ((Np * E + E) + Np * E) * w.count / 1e9
+            med, mn = time_schedule(scatter_gather, 5)
+            add_row(w.name, "3a ftar_reduce_scatter_all + ftar_allgather_all (own bytes: (2N+1)E)", own_gb, med, mn,
+                    True, float("nan"), "-")
             # the same result in one pass: its own algorithmic bytes are 2*N*E per element
             own_gb = 2 * plan.n_live * E * w.count / 1e9
             med, mn = time_schedule(lambda: B.ftar_allreduce_onepass(plan, bufs), 5)

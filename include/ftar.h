@@ -243,6 +243,18 @@ ftar_status_t ftar_reduce_masked_bucketed(const void* const* bufs, int n_replica
                                           void* out, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * ftar_reduce_scatter_all - what the N-1 ftar_reduce_step calls of the plan leave in the replica
+ * buffers, in ONE pass and without `acc`: every element's N contributions are added in a
+ * register in the ring's order for its portion (positions k, k+1, ..., k+N-1 mod N; paper
+ * section 4.2, "Ring algorithm") and the rounded mean is written into the buffer of the portion's
+ * owner (ring position k-1) only; everything else stays as it was.  Bit-identical to the step
+ * calls; N*E + E bytes per element.  This is the reduce-scatter a sharded optimizer wants (every
+ * replica ends with its own portion); ftar_allgather_all or the ftar_allgather_step calls complete
+ * it to the all-reduce.  N == 1: nothing to do.
+ */
+ftar_status_t ftar_reduce_scatter_all(const ftar_plan_t* plan, void* const* bufs, void* stream);
+
+/* ---------------------------------------------------------------------------
  * ftar_allgather_all - what the N-1 ftar_allgather_step calls of the plan leave in the replica
  * buffers, in ONE pass: every portion is read once from the buffer of the replica that holds its
  * finished value after the ReduceScatter phase (ring position k-1 for portion k; paper section

@@ -45,7 +45,7 @@ EXPORTS = [
     "ftar_plan_set_partition", "ftar_plan_n_partitions", "ftar_plan_n_slots",
     "ftar_plan_partition_segment", "ftar_allreduce_onepass", "ftar_plan_set_zero_mask",
     "ftar_reduce_masked_zero", "ftar_plan_set_op", "ftar_reduce_masked_ex", "ftar_plan_lr_factors",
-    "ftar_probe_stream", "ftar_allgather_all",
+    "ftar_probe_stream", "ftar_allgather_all", "ftar_reduce_scatter_all",
 ]
 
 _lib = None
@@ -124,6 +124,8 @@ def lib():
     L.ftar_plan_lr_factors.argtypes = [vp, vp, vp]
     L.ftar_probe_stream.restype = ci
     L.ftar_probe_stream.argtypes = [vp, ci, ci, sz, ctypes.c_uint32, vp]
+    L.ftar_reduce_scatter_all.restype = ci
+    L.ftar_reduce_scatter_all.argtypes = [vp, vp, vp]
     L.ftar_allgather_all.restype = ci
     L.ftar_allgather_all.argtypes = [vp, vp, vp]
     L.ftar_allreduce_onepass.restype = ci
@@ -410,6 +412,15 @@ def ftar_status_str(status: int) -> str:
 
 def ftar_last_error() -> int:
     return lib().ftar_last_error()
+
+
+def ftar_reduce_scatter_all(plan: Plan, bufs: Sequence[Optional[torch.Tensor]], stream=None) -> None:
+    _check_bufs(bufs, plan.live_mask, plan.count, plan.dtype)
+    if len(bufs) != plan.n_replicas:
+        raise ValueError("bufs must have one entry per replica slot")
+    st = lib().ftar_reduce_scatter_all(plan.handle, _ptr_array(bufs), _stream_handle(stream))
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_reduce_scatter_all")
 
 
 def ftar_allgather_all(plan: Plan, bufs: Sequence[Optional[torch.Tensor]], stream=None) -> None:

@@ -470,7 +470,7 @@ ftar_status_t ftar_reduce_masked_bucketed(const void* const* bufs, int n_replica
   return FTAR_OK;
 }
 
-ftar_status_t ftar_allreduce_onepass(const ftar_plan_t* plan, void* const* bufs, void* stream) {
+static ftar_status_t onepass_common(const ftar_plan_t* plan, void* const* bufs, bool owner_only, void* stream) {
   if (!plan_ok(plan) || !bufs || plan->part_elems != 0) return fail(FTAR_ERR_INVALID_ARG);
   const int N = plan->n_live;
   PtrTable tab;
@@ -480,8 +480,16 @@ ftar_status_t ftar_allreduce_onepass(const ftar_plan_t* plan, void* const* bufs,
   if (s != FTAR_OK) return fail(s);
   if (N < 2) return FTAR_OK;  // a ring of one exchanges nothing: the buffer stays as it is
   hipError_t e = launch_ring_onepass(tab, N, plan->seg, plan->dtype, vec, plan->scale, plan->zero_pos,
-                                     static_cast<hipStream_t>(stream));
+                                     owner_only, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
+}
+
+ftar_status_t ftar_allreduce_onepass(const ftar_plan_t* plan, void* const* bufs, void* stream) {
+  return onepass_common(plan, bufs, false, stream);
+}
+
+ftar_status_t ftar_reduce_scatter_all(const ftar_plan_t* plan, void* const* bufs, void* stream) {
+  return onepass_common(plan, bufs, true, stream);
 }
 
 void* ftar_ctrl_create(void) {

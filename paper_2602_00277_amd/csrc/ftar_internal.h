@@ -108,9 +108,10 @@ hipError_t launch_ring_allgather_all(const PtrTable& ring, int n_live, const Seg
 
 // The whole ring in one kernel, gated by the control block (ctrl_dev = device view of it).
 // What the whole ring schedule leaves in the buffers, in one pass (N reads, N writes per element).
+// owner_only: write each portion into its owner's buffer only (the state after the ReduceScatter phase).
 hipError_t launch_ring_onepass(const PtrTable& ring, int n_live, const SegTable& seg,
                                ftar_dtype_t dtype, bool vec, float scale, unsigned long long zpos,
-                               hipStream_t stream);
+                               bool owner_only, hipStream_t stream);
 
 // Geometry of a partitioned ring: n_parts partitions of part_elems elements (the last one may be
 // shorter); portion boundaries are relative to the partition's first element.

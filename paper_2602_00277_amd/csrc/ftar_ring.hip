@@ -34,7 +34,9 @@ k_ring_allgather(PtrTable ring, SegTable seg, SegTable tile0, int N, int step) {
 // (portion k: positions k, k+1, ..., k+N-1 mod N), and the rounded mean can be written straight
 // into all N replica buffers.  Same bits as the step schedule, 2*N*E bytes per element instead
 // of 4*N*E + 10*N - 20 (N = 16, bf16: 64 instead of 206).
-template <typename T, int VEC, int N, int U, int POL, bool ZM>
+// OWNER: store only into the last buffer of the rotated order, the portion's owner (ring position
+// k-1): the state after the ReduceScatter phase instead of the finished all-reduce.
+template <typename T, int VEC, int N, int U, int POL, bool ZM, bool OWNER>
 __device__ __forceinline__ void onepass_tile(T* const (&buf)[N], float scale, size_t v,
                                              unsigned long long zm) {
   typedef typename Raw<T, VEC>::type R;
@@ -60,13 +62,17 @@ __device__ __forceinline__ void onepass_tile(T* const (&buf)[N], float scale, si
 #pragma unroll
     for (int e = 0; e < VEC; ++e) a[e] = a[e] * scale;
     const R r = narrow<R, VEC>(a);
+    if constexpr (OWNER) {
+      st<POL>(reinterpret_cast<R*>(buf[N - 1]) + v + u * kThreads, r);
+    } else {
 #pragma unroll
-    for (int j = 0; j < N; ++j) st<POL>(reinterpret_cast<R*>(buf[j]) + v + u * kThreads, r);
+      for (int j = 0; j < N; ++j) st<POL>(reinterpret_cast<R*>(buf[j]) + v + u * kThreads, r);
+    }
   }
 }
 
 // Any N (runtime): loads in groups of 8 in ring order starting at position k, then N stores.
-template <typename T, int VEC, int POL>
+template <typename T, int VEC, int POL, bool OWNER>
 __device__ __forceinline__ void onepass_any_one(T* const* s_tab, int N, int k, size_t base, float scale,
                                                 size_t v, unsigned long long zpos) {
   typedef typename Raw<T, VEC>::type R;
@@ -98,23 +104,27 @@ __device__ __forceinline__ void onepass_any_one(T* const* s_tab, int N, int k, s
 #pragma unroll
   for (int e = 0; e < VEC; ++e) a[e] = a[e] * scale;
   const R r = narrow<R, VEC>(a);
-  for (int j = 0; j < N; ++j) st<POL>(reinterpret_cast<R*>(uniform_ptr(s_tab[j]) + base) + v, r);
+  if constexpr (OWNER) {
+    st<POL>(reinterpret_cast<R*>(uniform_ptr(s_tab[(k + N - 1) % N]) + base) + v, r);
+  } else {
+    for (int j = 0; j < N; ++j) st<POL>(reinterpret_cast<R*>(uniform_ptr(s_tab[j]) + base) + v, r);
+  }
 }
 
-template <typename T, int VEC, int POL>
+template <typename T, int VEC, int POL, bool OWNER>
 __device__ __forceinline__ void onepass_any_range(T* const* s_tab, int N, int k, size_t base, float scale,
                                                   size_t len, unsigned long long zpos) {
   const size_t n_vec = len / VEC;
   for (size_t v = threadIdx.x; v < n_vec; v += kThreads)
-    onepass_any_one<T, VEC, POL>(s_tab, N, k, base, scale, v, zpos);
+    onepass_any_one<T, VEC, POL, OWNER>(s_tab, N, k, base, scale, v, zpos);
   if constexpr (VEC > 1) {
     const size_t e = n_vec * VEC + threadIdx.x;
-    if (e < len) onepass_any_one<T, 1, POL>(s_tab, N, k, base, scale, e, zpos);
+    if (e < len) onepass_any_one<T, 1, POL, OWNER>(s_tab, N, k, base, scale, e, zpos);
   }
 }
 
 // NT = compile-time N for the unrolled tile (1..16), or 0: any N through the grouped loop.
-template <typename T, int VEC, int NT, int POL>
+template <typename T, int VEC, int NT, int POL, bool OWNER>
 __global__ void __launch_bounds__(kThreads)
 k_ring_onepass(PtrTable ring, SegTable seg, SegTable tile0, int N, float scale, unsigned long long zpos) {
   __shared__ T* s_tab[kMaxReplicas];
@@ -137,13 +147,13 @@ k_ring_onepass(PtrTable ring, SegTable seg, SegTable tile0, int N, float scale, 
           buf[m] = uniform_ptr(s_tab[p]) + t.begin;
           zm |= ((zpos >> p) & 1ull) << m;
         }
-        if (zm == 0) onepass_tile<T, VEC, NT, U, POL, false>(buf, scale, threadIdx.x, 0);
-        else onepass_tile<T, VEC, NT, U, POL, true>(buf, scale, threadIdx.x, zm);
+        if (zm == 0) onepass_tile<T, VEC, NT, U, POL, false, OWNER>(buf, scale, threadIdx.x, 0);
+        else onepass_tile<T, VEC, NT, U, POL, true, OWNER>(buf, scale, threadIdx.x, zm);
         continue;
       }
     }
-    if (t.rem >= kTileElems) onepass_any_range<T, VEC, POL>(s_tab, N, t.k, t.begin, scale, kTileElems, zpos);
-    else onepass_any_range<T, VEC, POL>(s_tab, N, t.k, t.begin, scale, t.rem, zpos);
+    if (t.rem >= kTileElems) onepass_any_range<T, VEC, POL, OWNER>(s_tab, N, t.k, t.begin, scale, kTileElems, zpos);
+    else onepass_any_range<T, VEC, POL, OWNER>(s_tab, N, t.k, t.begin, scale, t.rem, zpos);
   }
 }
 
@@ -252,7 +262,7 @@ struct RingAllgather {
   }
 };
 
-template <typename T, int VEC>
+template <typename T, int VEC, bool OWNER>
 struct RingOnepass {
   const PtrTable& ring; int N; const SegTable& seg; float scale; unsigned long long zpos; hipStream_t stream;
   template <int POL> hipError_t operator()(unsigned blocks) const {
@@ -260,14 +270,14 @@ struct RingOnepass {
     const SegTable tiles = ring_tiles(seg, N, VEC, U);
     const dim3 grid(grid_x_for(tiles.begin[N], blocks)), block(kThreads);
     if (VEC == 1 || N > 16) {
-      launch(k_ring_onepass<T, VEC, 0, POL>, grid, block, stream, ring, seg, tiles, N, scale, zpos);
+      launch(k_ring_onepass<T, VEC, 0, POL, OWNER>, grid, block, stream, ring, seg, tiles, N, scale, zpos);
       return hipGetLastError();
     }
     switch (N) {
 #define FTAR_CASE(n)                                                                                       \
   case n:                                                                                                  \
-    launch(k_ring_onepass<T, VEC, (VEC == 1 ? 0 : n), POL>, grid, block, stream, ring, seg, tiles, N, scale, \
-           zpos);                                                                                          \
+    launch(k_ring_onepass<T, VEC, (VEC == 1 ? 0 : n), POL, OWNER>, grid, block, stream, ring, seg, tiles, N, \
+           scale, zpos);                                                                                   \
     break;
       FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7) FTAR_CASE(8)
       FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13) FTAR_CASE(14)
@@ -318,16 +328,26 @@ hipError_t launch_ring_allgather_all(const PtrTable& ring, int n_live, const Seg
 
 hipError_t launch_ring_onepass(const PtrTable& ring, int n_live, const SegTable& seg,
                                ftar_dtype_t dtype, bool vec, float scale, unsigned long long zpos,
-                               hipStream_t stream) {
+                               bool owner_only, hipStream_t stream) {
   // N reads and N writes per element, as many write streams as read streams: non-temporal
-  // stores and one workgroup per CU are best at every size measured
-  const LaunchCfg cfg = launch_cfg(1, 3);
-  if (dtype == FTAR_F32) {
-    if (vec) return with_policy(cfg, RingOnepass<float, 4>{ring, n_live, seg, scale, zpos, stream});
-    return with_policy(cfg, RingOnepass<float, 1>{ring, n_live, seg, scale, zpos, stream});
+  // stores and one workgroup per CU are best at every size measured.  Owner only: N reads and one
+  // write, the mix of the one-shot reduce, and its choices.
+  const LaunchCfg cfg = owner_only ? reduce_cfg(n_live, seg.begin[n_live] * (dtype == FTAR_F32 ? 4 : 2))
+                                   : launch_cfg(1, 3);
+  if (owner_only) {
+    if (dtype == FTAR_F32) {
+      if (vec) return with_policy(cfg, RingOnepass<float, 4, true>{ring, n_live, seg, scale, zpos, stream});
+      return with_policy(cfg, RingOnepass<float, 1, true>{ring, n_live, seg, scale, zpos, stream});
+    }
+    if (vec) return with_policy(cfg, RingOnepass<bf16, 8, true>{ring, n_live, seg, scale, zpos, stream});
+    return with_policy(cfg, RingOnepass<bf16, 1, true>{ring, n_live, seg, scale, zpos, stream});
   }
-  if (vec) return with_policy(cfg, RingOnepass<bf16, 8>{ring, n_live, seg, scale, zpos, stream});
-  return with_policy(cfg, RingOnepass<bf16, 1>{ring, n_live, seg, scale, zpos, stream});
+  if (dtype == FTAR_F32) {
+    if (vec) return with_policy(cfg, RingOnepass<float, 4, false>{ring, n_live, seg, scale, zpos, stream});
+    return with_policy(cfg, RingOnepass<float, 1, false>{ring, n_live, seg, scale, zpos, stream});
+  }
+  if (vec) return with_policy(cfg, RingOnepass<bf16, 8, false>{ring, n_live, seg, scale, zpos, stream});
+  return with_policy(cfg, RingOnepass<bf16, 1, false>{ring, n_live, seg, scale, zpos, stream});
 }
 
 }  // namespace ftar

@@ -123,7 +123,7 @@ def test_random_option_draw(B, oracle, seed):
     acc_store = torch.empty(count + 16, dtype=torch.float32, device="cuda")
     acc = acc_store[c["offset"]:c["offset"] + count]
     ctrl = B.ftar_ctrl_create()
-    for name in ("steps", "gather_all", "onepass", "persistent", "partitioned"):
+    for name in ("steps", "gather_all", "scatter_all+gather_all", "onepass", "persistent", "partitioned"):
         bufs = [s.clone()[c["offset"]:c["offset"] + count] for s in store]
         ref = want
         if name == "steps":
@@ -131,6 +131,9 @@ def test_random_option_draw(B, oracle, seed):
         elif name == "gather_all":
             for step in range(plan.n_steps):
                 B.ftar_reduce_step(plan, step, bufs, acc)
+            B.ftar_allgather_all(plan, bufs)
+        elif name == "scatter_all+gather_all":
+            B.ftar_reduce_scatter_all(plan, bufs)
             B.ftar_allgather_all(plan, bufs)
         elif name == "onepass":
             B.ftar_allreduce_onepass(plan, bufs)
