@@ -165,3 +165,19 @@ def test_ring_paths_deliver_the_sum(B, oracle, dtype, n, live, zmask):
     torch.cuda.synchronize()
     first = [r for r in range(n) if (live >> r) & 1][0]
     assert_same(host(bufs[first]), oracle.ring_closed_form(orig, live, count, chunk, code(dtype)), "mean again")
+
+
+def test_widening_of_every_bf16_pattern(B, oracle):
+    # one live bf16 replica, sum, fp32 result: x * 1.0f of the widened value, every one of the 2^16 patterns
+    x = torch.arange(0, 1 << 16, dtype=torch.int32, device="cuda").to(torch.int16).view(torch.bfloat16)
+    out = torch.empty(1 << 16, dtype=torch.float32, device="cuda")
+    say("bf16 -> fp32 widening, all 2^16 patterns")
+    B.ftar_reduce_masked_ex([x], 0b1, out, op=B.FTAR_SUM)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().view(np.uint32)
+    want = oracle.bf16_to_f32(np.arange(1 << 16, dtype=np.uint16)).view(np.uint32)
+    nan = (want & 0x7FFFFFFF) > 0x7F800000
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal((got & 0x7FFFFFFF) > 0x7F800000, nan)
+    # a NaN keeps sign and payload; a signalling one comes back quiet (x * 1.0f)
+    assert np.array_equal(got[nan] | 0x00400000, want[nan] | 0x00400000)
