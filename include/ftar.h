@@ -34,8 +34,7 @@
  *     caller errors and device errors are not retryable; the retryable class
  *     is reserved for a membership change while work is queued.
  *   - Host threads may call at the same time, each on a stream of its own: the library
- *     holds no lock, a plan is only read by the compute calls, the last error and the
- *     timing events are per thread, the tuning is process-wide.
+ *     holds no lock, a plan is only read by the compute calls, the last error is per thread.
  *   - Arithmetic: inputs are widened exactly to fp32; sums are fp32 additions
  *     in a fixed order; the mean is ONE multiplication by
  *     scale = 1.0f/(float)n_live (one correctly rounded fp32 division, done on
@@ -339,33 +338,6 @@ ftar_status_t ftar_ctrl_result(const void* ctrl, int* steps_done);
 ftar_status_t ftar_last_error(void);          /* status of this thread's last failing call */
 int ftar_status_is_retryable(ftar_status_t s);
 const char* ftar_status_str(ftar_status_t s); /* static string */
-
-/* Launch shape and cache policy, for measurement only (results never depend on it).
- * blocks_per_cu: workgroups launched per compute unit (0 = each kernel's default);
- * flags: 0 = each kernel's default policy; 0x10 | p = explicit policy p, where bit 0 of p
- * asks for non-temporal loads and bit 1 for non-temporal stores; 0x20 = wide tiles in the
- * one-shot reduce; 0x40 = never split a long one-shot reduce into several launches and never run big
- * buckets one by one;
- * bits 8..11 = vectors per lane and tile in the ring kernels (2, 4 or 8). */
-void ftar_set_tuning(int blocks_per_cu, int flags);
-
-/* Measurement only: arms two hipEvent_t (passed as void*, either may be NULL) for the NEXT kernel
- * this thread launches through the library.  That dispatch records them itself: `start` when the
- * kernel begins on the GPU, `stop` when it ends, so hipEventElapsedTime(start, stop) is the
- * kernel's own duration.  A one-shot or bucketed reduce that goes out as several launches records
- * `start` with its first and `stop` with its last launch.  The pair is consumed by that call and
- * cleared.  The caller owns the events. */
-void ftar_time_next_launch(void* start_event, void* stop_event);
-
-/* Measurement only: a bare streaming kernel over n_read + n_written device buffers of `bytes`
- * bytes each (bufs: HOST array, the read buffers first; 16-byte aligned; bytes a multiple of 32 KiB).
- * The first n_read are read, each of the others receives the xor of the read ones at the same
- * offset (or the 32-bit word `fill` when n_read == 0); with n_written == 0 nothing is stored.
- * It gives this GPU's own ceiling for a mix of streams, next to which the reduce and ring kernels
- * are judged.  Mixes offered: reads only 1/2/4/8/16, writes only 1/2/4/8, r+1 for r = 1,2,3,4,7,8,16,
- * 4+4, 8+8; anything else FTAR_ERR_INVALID_ARG.  Honours ftar_set_tuning and ftar_time_next_launch. */
-ftar_status_t ftar_probe_stream(void* const* bufs, int n_read, int n_written, size_t bytes, uint32_t fill,
-                                void* stream);
 
 #ifdef __cplusplus
 }

@@ -39,16 +39,23 @@ EXPORTS = [
     "ftar_plan_n_steps", "ftar_plan_acc_bytes", "ftar_plan_scale", "ftar_plan_segment",
     "ftar_reduce_step", "ftar_allgather_step", "ftar_reduce_masked",
     "ftar_reduce_masked_bucketed", "ftar_last_error", "ftar_status_is_retryable",
-    "ftar_status_str", "ftar_set_tuning", "ftar_time_next_launch",
+    "ftar_status_str",
     "ftar_ctrl_create", "ftar_ctrl_destroy", "ftar_ring_persistent", "ftar_ctrl_release",
     "ftar_ctrl_cancel", "ftar_ctrl_progress", "ftar_ctrl_result",
     "ftar_plan_set_partition", "ftar_plan_n_partitions", "ftar_plan_n_slots",
     "ftar_plan_partition_segment", "ftar_allreduce_onepass", "ftar_plan_set_zero_mask",
     "ftar_reduce_masked_zero", "ftar_plan_set_op", "ftar_reduce_masked_ex", "ftar_plan_lr_factors",
-    "ftar_probe_stream", "ftar_allgather_all", "ftar_reduce_scatter_all",
+    "ftar_allgather_all", "ftar_reduce_scatter_all",
 ]
 
+# every symbol include/ftar_measure.h declares: measurement hooks in libftar.so, probe kernels in
+# the bench-only libftar_measure.so
+MEASURE_HOOKS = ["ftar_set_tuning", "ftar_time_next_launch"]
+MEASURE_EXPORTS = ["ftar_probe_stream"]
+MEASURE_LIB_PATH = os.path.join(_PKG, "libftar_measure.so")
+
 _lib = None
+_measure_lib = None
 
 
 class FtarError(RuntimeError):
@@ -122,8 +129,6 @@ def lib():
     L.ftar_reduce_masked_ex.argtypes = [vp, ci, u64, u64, ci, sz, ci, ci, ci, vp, vp]
     L.ftar_plan_lr_factors.restype = ci
     L.ftar_plan_lr_factors.argtypes = [vp, vp, vp]
-    L.ftar_probe_stream.restype = ci
-    L.ftar_probe_stream.argtypes = [vp, ci, ci, sz, ctypes.c_uint32, vp]
     L.ftar_reduce_scatter_all.restype = ci
     L.ftar_reduce_scatter_all.argtypes = [vp, vp, vp]
     L.ftar_allgather_all.restype = ci
@@ -146,6 +151,22 @@ def lib():
     L.ftar_ctrl_result.argtypes = [vp, ctypes.POINTER(ci)]
     _lib = L
     return L
+
+
+def measure_lib():
+    """Loads the bench-only libftar_measure.so once (after libftar.so, which it links against)."""
+    global _measure_lib
+    if _measure_lib is not None:
+        return _measure_lib
+    lib()
+    if not os.path.exists(MEASURE_LIB_PATH):
+        raise ImportError("libftar_measure.so is not built: run `python -m paper_2602_00277_amd.build`")
+    M = ctypes.CDLL(MEASURE_LIB_PATH)
+    M.ftar_probe_stream.restype = ctypes.c_int
+    M.ftar_probe_stream.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_size_t,
+                                    ctypes.c_uint32, ctypes.c_void_p]
+    _measure_lib = M
+    return M
 
 
 def dtype_code(dtype: torch.dtype) -> int:
@@ -388,7 +409,8 @@ def ftar_probe_stream(read: Sequence[torch.Tensor], written: Sequence[torch.Tens
     for b in bufs:
         if not b.is_cuda or not b.is_contiguous() or b.numel() * b.element_size() != nbytes:
             raise ValueError("probe buffers must be contiguous GPU tensors of one size")
-    st = lib().ftar_probe_stream(_ptr_array(bufs), len(read), len(written), nbytes, fill, _stream_handle(stream))
+    st = measure_lib().ftar_probe_stream(_ptr_array(bufs), len(read), len(written), nbytes, fill,
+                                         _stream_handle(stream))
     if st != FTAR_OK:
         raise FtarError(st, "ftar_probe_stream")
 

@@ -12,6 +12,7 @@
 #include <new>
 
 #include "ftar_internal.h"
+#include "ftar_measure.h"
 
 namespace ftar {
 namespace {
@@ -28,15 +29,9 @@ ftar_status_t fail(ftar_status_t s) {
 thread_local hipEvent_t t_time_start = nullptr;
 thread_local hipEvent_t t_time_stop = nullptr;
 
+// measurement overrides (include/ftar_measure.h); zero = every kernel's own default
 std::atomic<int> g_blocks_per_cu{0};
 std::atomic<int> g_flags{0};
-std::atomic<bool> g_env_read{false};
-
-void read_env_once() {
-  if (g_env_read.exchange(true)) return;
-  if (const char* e = std::getenv("FTAR_BLOCKS_PER_CU")) g_blocks_per_cu = std::atoi(e);
-  if (const char* e = std::getenv("FTAR_FLAGS")) g_flags = std::atoi(e);
-}
 
 // Live replicas in ascending index order = ring positions 0..N-1.
 ftar_status_t resolve_mask(int n_replicas, uint64_t live_mask, int* ring, int* n_live) {
@@ -56,16 +51,18 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 
 }  // namespace
 
-Tuning current_tuning() {
-  read_env_once();
-  return Tuning{g_blocks_per_cu.load(), g_flags.load()};
-}
+Tuning current_tuning() { return Tuning{g_blocks_per_cu.load(), g_flags.load()}; }
 
 void take_timing_events(hipEvent_t* start, hipEvent_t* stop) {
   *start = t_time_start;
   *stop = t_time_stop;
   t_time_start = nullptr;
   t_time_stop = nullptr;
+}
+
+void set_timing_events(hipEvent_t start, hipEvent_t stop) {
+  t_time_start = start;
+  t_time_stop = stop;
 }
 
 int device_cu_count() {
@@ -609,29 +606,12 @@ const char* ftar_status_str(ftar_status_t s) {
   return "unknown status";
 }
 
-ftar_status_t ftar_probe_stream(void* const* bufs, int n_read, int n_written, size_t bytes, uint32_t fill,
-                                void* stream) {
-  if (!bufs || n_read < 0 || n_written < 0 || n_read + n_written < 1 || n_read + n_written > kMaxReplicas ||
-      bytes == 0 || bytes % (32 * 1024) != 0)
-    return fail(FTAR_ERR_INVALID_ARG);
-  PtrTable tab;
-  std::memset(&tab, 0, sizeof(tab));
-  for (int j = 0; j < n_read + n_written; ++j) {
-    if (!bufs[j] || !aligned(bufs[j], 16)) return fail(FTAR_ERR_INVALID_ARG);
-    tab.p[j] = bufs[j];
-  }
-  hipError_t e = launch_probe_stream(tab, n_read, n_written, bytes / 16, fill, static_cast<hipStream_t>(stream));
-  if (e == hipErrorInvalidValue) return fail(FTAR_ERR_INVALID_ARG);
-  return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
-}
-
+// ---- measurement hooks (declared in include/ftar_measure.h) ----
 void ftar_time_next_launch(void* start_event, void* stop_event) {
-  t_time_start = static_cast<hipEvent_t>(start_event);
-  t_time_stop = static_cast<hipEvent_t>(stop_event);
+  set_timing_events(static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event));
 }
 
 void ftar_set_tuning(int blocks_per_cu, int flags) {
-  read_env_once();
   g_blocks_per_cu = blocks_per_cu < 0 ? 0 : blocks_per_cu;
   g_flags = flags;
 }

@@ -76,6 +76,8 @@ Tuning current_tuning();
 
 // Hands over (and clears) the timing events armed for this thread's next launch; both null if none.
 void take_timing_events(hipEvent_t* start, hipEvent_t* stop);
+// Arms the pair for this thread's next launch (what the measurement hook does).
+void set_timing_events(hipEvent_t start, hipEvent_t stop);
 int device_cu_count();  // of the current device; cached
 
 // All launchers enqueue on `stream` and return hipGetLastError().

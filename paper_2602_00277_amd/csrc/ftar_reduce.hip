@@ -292,7 +292,7 @@ hipError_t launch_reduce_masked(const PtrTable& live, int n_src, size_t count, f
     for (int j = 0; j < n_src; ++j) part.p[j] = static_cast<char*>(live.p[j]) + first * es_in;
     void* o = static_cast<char*>(out) + first * es_out;
     if (chunk < count)  // the events of a timed call bracket the whole series
-      ftar_time_next_launch(first == 0 ? t_start : nullptr, first + len >= count ? t_stop : nullptr);
+      set_timing_events(first == 0 ? t_start : nullptr, first + len >= count ? t_stop : nullptr);
     hipError_t e;
     if (out_dtype != dtype && dtype == FTAR_BF16)
       e = reduce_masked_cvt<bf16, float>(part, n_src, len, vec, o, scale, zterm, count * es_out, stream);

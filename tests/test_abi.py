@@ -12,25 +12,45 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 @pytest.fixture(scope="module")
 def B():
     from paper_2602_00277_amd import binding, build
-    if not os.path.exists(binding.LIB_PATH):
+    if not os.path.exists(binding.LIB_PATH) or not os.path.exists(binding.MEASURE_LIB_PATH):
         build.build(verbose=False)
     binding.lib()
     return binding
 
 
-def test_exports_every_declared_symbol(B):
-    header = open(os.path.join(ROOT, "include", "ftar.h")).read()
+def _declared(header_name):
+    header = open(os.path.join(ROOT, "include", header_name)).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(ftar_[a-z_0-9]+)\s*\(", header))
+    return set(re.findall(r"\b(ftar_[a-z_0-9]+)\s*\(", header))
+
+
+def _exported(path):
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", path], capture_output=True, text=True, check=True).stdout
+    return {line.split()[-1] for line in out.splitlines() if re.search(r" [TW] ftar_[a-z_0-9]+$", line)}
+
+
+def test_exports_every_declared_symbol(B):
+    # the product header: exactly the method's calls, all in libftar.so
+    declared = _declared("ftar.h")
     assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
     raw = ctypes.CDLL(B.LIB_PATH)
     for name in declared:
         assert getattr(raw, name) is not None, name
+    # the measurement header: two hooks in libftar.so, the probe kernels in the bench-only library
+    measure = _declared("ftar_measure.h")
+    assert measure == set(B.MEASURE_HOOKS) | set(B.MEASURE_EXPORTS), measure
+    assert not (measure & declared)
+    for name in B.MEASURE_HOOKS:
+        assert getattr(raw, name) is not None, name
+    # libftar.so exports no C entry point that neither header declares; the probe is not in it
+    assert _exported(B.LIB_PATH) == declared | set(B.MEASURE_HOOKS)
+    assert _exported(B.MEASURE_LIB_PATH) == set(B.MEASURE_EXPORTS)
 
 
 def test_status_strings_and_classes(B):
     for s in (0, 1, 2, 3, 4, 16, 32):
-        assert B.ftar_status_str(s)
+        assert B.ftar_status_str(s) and B.ftar_status_str(s) != "unknown status"
     assert B.ftar_status_is_retryable(B.FTAR_ERR_STALE_PLAN)
     assert not any(B.ftar_status_is_retryable(s) for s in (0, 1, 2, 3, 4, 32))
 
