@@ -65,6 +65,7 @@ typedef enum {
   FTAR_ERR_NO_LIVE = 2,     /* live_mask has no bit set below n_replicas */
   FTAR_ERR_BAD_MASK = 3,    /* live_mask has a bit set at or above n_replicas */
   FTAR_ERR_BAD_STEP = 4,    /* step outside [0, n_live-2] */
+  FTAR_ERR_TOO_LARGE = 5,   /* ftar_ring_persistent_static: more partial sums than the static scratch holds */
   /* retryable: re-plan over the new group and restart the schedule */
   FTAR_ERR_STALE_PLAN = 16, /* the persistent ring was cancelled or timed out before finishing */
   /* fatal: the HIP runtime reported a failure */
@@ -325,6 +326,28 @@ void* ftar_ctrl_create(void);   /* NULL on failure */
 void ftar_ctrl_destroy(void* ctrl);
 ftar_status_t ftar_ring_persistent(const ftar_plan_t* plan, void* const* bufs, float* acc, void* ctrl,
                                    int n_blocks, unsigned timeout_us, unsigned flags, void* stream);
+/* ---------------------------------------------------------------------------
+ * ftar_ring_persistent_static - ftar_ring_persistent for callers that cannot allocate device memory
+ * and have none to spare for a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same kernel, same arguments, same results bit for bit, but the
+ * partial sums (`acc`) and the device mirror of the control block live in a static device array of
+ * the library (16 MiB + 8 KiB per GPU, held from the first use on that GPU until the process ends)
+ * instead of caller memory and the mirror made by ftar_ctrl_create.  The call itself allocates and
+ * frees nothing and calls no allocating routine; `ctrl` is still a block from ftar_ctrl_create
+ * (made at set-up), bufs are the caller's.
+ * Limit: one partition - ftar_plan_set_partition's partition_elems, or `count` for an unpartitioned
+ * plan - is at most FTAR_STATIC_ACC_ELEMS (4 Mi) elements; beyond that FTAR_ERR_TOO_LARGE and
+ * nothing is enqueued.  (Partitions of this size are the intended use: the partial sums then stay in
+ * the caches.)  The array's address is looked up once per GPU, at ftar_ctrl_create or else at the
+ * first call on that GPU, with that GPU current.
+ * All calls on one GPU share the array, and it keeps the last call's contents: the mirror is
+ * cleared on `stream` before every launch, the partial sums are always written before they are
+ * read.  Two calls that overlap in time on one GPU (different streams, or threads) race on it:
+ * keep them on one stream, or use ftar_ring_persistent with buffers of their own.
+ */
+#define FTAR_STATIC_ACC_ELEMS ((size_t)4 << 20)
+ftar_status_t ftar_ring_persistent_static(const ftar_plan_t* plan, void* const* bufs, void* ctrl,
+                                          int n_blocks, unsigned timeout_us, unsigned flags, void* stream);
 /* CPU side of the handshake (plain host stores/loads on the control block; callable from any
  * thread while the kernel runs). */
 void ftar_ctrl_release(void* ctrl, int n_steps); /* steps [0, n_steps) may run */

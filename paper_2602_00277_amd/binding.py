@@ -24,6 +24,7 @@ FTAR_ERR_INVALID_ARG = 1
 FTAR_ERR_NO_LIVE = 2
 FTAR_ERR_BAD_MASK = 3
 FTAR_ERR_BAD_STEP = 4
+FTAR_ERR_TOO_LARGE = 5
 FTAR_ERR_STALE_PLAN = 16
 FTAR_ERR_DEVICE = 32
 
@@ -46,6 +47,7 @@ EXPORTS = [
     "ftar_plan_partition_segment", "ftar_allreduce_onepass", "ftar_plan_set_zero_mask",
     "ftar_reduce_masked_zero", "ftar_plan_set_op", "ftar_reduce_masked_ex", "ftar_plan_lr_factors",
     "ftar_allgather_all", "ftar_reduce_scatter_all",
+    "ftar_ring_persistent_static",
 ]
 
 # every symbol include/ftar_measure.h declares: measurement hooks in libftar.so, probe kernels in
@@ -141,6 +143,8 @@ def lib():
     L.ftar_ctrl_destroy.argtypes = [vp]
     L.ftar_ring_persistent.restype = ci
     L.ftar_ring_persistent.argtypes = [vp, vp, vp, vp, ci, ctypes.c_uint, ctypes.c_uint, vp]
+    L.ftar_ring_persistent_static.restype = ci
+    L.ftar_ring_persistent_static.argtypes = [vp, vp, vp, ci, ctypes.c_uint, ctypes.c_uint, vp]
     L.ftar_ctrl_release.restype = None
     L.ftar_ctrl_release.argtypes = [vp, ci]
     L.ftar_ctrl_cancel.restype = None
@@ -535,6 +539,19 @@ def ftar_ring_persistent(plan: Plan, bufs: Sequence[Optional[torch.Tensor]],
                                     timeout_us, flags, _stream_handle(stream))
     if st != FTAR_OK:
         raise FtarError(st, "ftar_ring_persistent")
+
+
+def ftar_ring_persistent_static(plan: Plan, bufs: Sequence[Optional[torch.Tensor]], ctrl: Ctrl,
+                                n_blocks: int = 0, timeout_us: int = 2_000_000, flags: int = 0,
+                                stream=None) -> None:
+    """ftar_ring_persistent on the library's static scratch: no acc argument, nothing allocated."""
+    _check_bufs(bufs, plan.live_mask, plan.count, plan.dtype)
+    if len(bufs) != plan.n_replicas:
+        raise ValueError("bufs must have one entry per replica slot")
+    st = lib().ftar_ring_persistent_static(plan.handle, _ptr_array(bufs), ctrl.handle, n_blocks,
+                                           timeout_us, flags, _stream_handle(stream))
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_ring_persistent_static")
 
 
 def ring_allreduce(plan: Plan, bufs: Sequence[Optional[torch.Tensor]], acc: Optional[torch.Tensor],

@@ -503,6 +503,11 @@ void* ftar_ctrl_create(void) {
     return nullptr;
   }
   static_cast<Ctrl*>(p)->dev = static_cast<DevCtrl*>(mirror);
+  // set-up is also where the static scratch of ftar_ring_persistent_static is located on this
+  // device (that entry point looks it up itself if no control block was ever made here)
+  DevCtrl* sm = nullptr;
+  float* sa = nullptr;
+  (void)static_scratch(&sm, &sa);
   return p;
 }
 
@@ -512,14 +517,24 @@ void ftar_ctrl_destroy(void* ctrl) {
   (void)hipHostFree(ctrl);
 }
 
-ftar_status_t ftar_ring_persistent(const ftar_plan_t* plan, void* const* bufs, float* acc, void* ctrl,
-                                   int n_blocks, unsigned timeout_us, unsigned flags, void* stream) {
+// own_scratch: the partial sums and the mirror of the control block live in the library's static
+// device array instead of caller-provided / set-up-allocated memory (acc is then ignored).
+static ftar_status_t ring_persistent_common(const ftar_plan_t* plan, void* const* bufs, float* acc, void* ctrl,
+                                            int n_blocks, unsigned timeout_us, unsigned flags, bool own_scratch,
+                                            void* stream) {
   if (!plan_ok(plan) || !bufs || !ctrl || timeout_us == 0 || n_blocks < 0 ||
       n_blocks > kMaxPersistentBlocks || (flags & ~(FTAR_PERSIST_PUBLISH | FTAR_PERSIST_ALIGN)) != 0)
     return fail(FTAR_ERR_INVALID_ARG);
   const int N = plan->n_live;
   Ctrl* c = static_cast<Ctrl*>(ctrl);
-  if (!c->dev) return fail(FTAR_ERR_INVALID_ARG);
+  DevCtrl* mirror = c->dev;
+  if (own_scratch) {
+    static_assert(kStaticAccElems == FTAR_STATIC_ACC_ELEMS, "the header states the limit");
+    if (N >= 3 && (plan->part_elems ? plan->part_elems : plan->count) > kStaticAccElems)
+      return fail(FTAR_ERR_TOO_LARGE);  // rings of one or two keep no partial sums
+    if (static_scratch(&mirror, &acc) != hipSuccess) return fail(FTAR_ERR_DEVICE);
+  }
+  if (!mirror) return fail(FTAR_ERR_INVALID_ARG);
   PtrTable tab;
   std::memset(&tab, 0, sizeof(tab));
   bool vec = true;
@@ -553,10 +568,20 @@ ftar_status_t ftar_ring_persistent(const ftar_plan_t* plan, void* const* bufs, f
   if ((plan->part_elems ? plan->part_elems : plan->count) * 4 > (static_cast<size_t>(256) << 20))
     flags |= FTAR_PERSIST_ALIGN;
   hipError_t e = launch_ring_persistent(tab, N, geom, plan->dtype, vec, acc, plan->scale,
-                                        static_cast<Ctrl*>(dev), c->dev, blocks,
+                                        static_cast<Ctrl*>(dev), mirror, blocks,
                                         static_cast<unsigned long long>(timeout_us) * 100ull, flags,
                                         plan->zero_pos, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
+}
+
+ftar_status_t ftar_ring_persistent(const ftar_plan_t* plan, void* const* bufs, float* acc, void* ctrl,
+                                   int n_blocks, unsigned timeout_us, unsigned flags, void* stream) {
+  return ring_persistent_common(plan, bufs, acc, ctrl, n_blocks, timeout_us, flags, false, stream);
+}
+
+ftar_status_t ftar_ring_persistent_static(const ftar_plan_t* plan, void* const* bufs, void* ctrl, int n_blocks,
+                                          unsigned timeout_us, unsigned flags, void* stream) {
+  return ring_persistent_common(plan, bufs, nullptr, ctrl, n_blocks, timeout_us, flags, true, stream);
 }
 
 void ftar_ctrl_release(void* ctrl, int n_steps) {
@@ -600,6 +625,7 @@ const char* ftar_status_str(ftar_status_t s) {
     case FTAR_ERR_NO_LIVE: return "live mask selects no replica";
     case FTAR_ERR_BAD_MASK: return "live mask has a bit at or above n_replicas";
     case FTAR_ERR_BAD_STEP: return "step outside [0, n_live-2]";
+    case FTAR_ERR_TOO_LARGE: return "partition (or unpartitioned buffer) exceeds the library's static scratch";
     case FTAR_ERR_STALE_PLAN: return "plan is stale: re-plan over the new group and restart";
     case FTAR_ERR_DEVICE: return "HIP runtime error";
   }

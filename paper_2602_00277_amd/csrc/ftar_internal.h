@@ -130,6 +130,13 @@ hipError_t launch_ring_persistent(const PtrTable& ring, int n_live, const PartGe
                                   DevCtrl* mirror, unsigned n_blocks, unsigned long long timeout_ticks,
                                   unsigned flags, unsigned long long zpos, hipStream_t stream);
 
+// Static scratch of the entry point that allocates nothing (ftar_ring_persistent_static): the
+// mirror of the control block and room for the partial sums of one partition, in a file-scope
+// device array of the library.  Resolves the array's address on the current device (once per
+// device, kept afterwards) and hands out the two parts.  Every call on one GPU shares them.
+constexpr size_t kStaticAccElems = static_cast<size_t>(4) << 20;  // 4 Mi floats = 16 MiB
+hipError_t static_scratch(DevCtrl** mirror, float** acc);
+
 // Measurement only: n_read streams read and n_written streams written, n_vec 16-byte vectors each
 // (tab: the read streams first).  Written streams receive the xor of the read ones, or `fill`.
 hipError_t launch_probe_stream(const PtrTable& tab, int n_read, int n_written, size_t n_vec, uint32_t fill,

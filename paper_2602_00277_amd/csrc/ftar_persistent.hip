@@ -1,6 +1,23 @@
 // The whole ring all-reduce as one CPU-gated persistent kernel, and its launcher.
 
+#include <mutex>
+
 #include "ftar_device.h"
+
+// Scratch memory of ftar_ring_persistent_static, for callers that cannot allocate: the mirror of
+// the control block (cleared on the stream before every launch) followed by the partial sums of
+// one partition.  One copy per GPU, held until the process ends; all calls on a GPU share it.
+// In host code this name is only a handle for hipGetSymbolAddress: the device address it stands
+// for is looked up once per device (static_scratch below) and used from then on.
+namespace ftar {
+namespace {
+struct StaticScratch {
+  DevCtrl mirror;
+  alignas(256) float acc[kStaticAccElems];
+};
+}  // namespace
+}  // namespace ftar
+static __device__ __align__(256) unsigned char scratch[sizeof(ftar::StaticScratch)];
 
 namespace ftar {
 namespace {
@@ -292,7 +309,34 @@ struct RingPersistent {
   }
 };
 
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each GPU, once looked up
+
 }  // namespace
+
+hipError_t static_scratch(DevCtrl** mirror, float** acc) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* p = nullptr;
+  {
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (g_scratch_ptr[dev] == nullptr) {
+      void* looked_up = nullptr;
+      e = hipGetSymbolAddress(&looked_up, HIP_SYMBOL(scratch));
+      if (e != hipSuccess) return e;
+      if (looked_up == nullptr) return hipErrorInvalidSymbol;
+      g_scratch_ptr[dev] = looked_up;
+    }
+    p = g_scratch_ptr[dev];
+  }
+  StaticScratch* s = static_cast<StaticScratch*>(p);
+  *mirror = &s->mirror;
+  *acc = s->acc;
+  return hipSuccess;
+}
 
 hipError_t launch_ring_persistent(const PtrTable& ring, int n_live, const PartGeom& geom,
                                   ftar_dtype_t dtype, bool vec, float* acc, float scale, Ctrl* ctrl_dev,

@@ -49,10 +49,10 @@ def test_exports_every_declared_symbol(B):
 
 
 def test_status_strings_and_classes(B):
-    for s in (0, 1, 2, 3, 4, 16, 32):
+    for s in (0, 1, 2, 3, 4, 5, 16, 32):
         assert B.ftar_status_str(s) and B.ftar_status_str(s) != "unknown status"
     assert B.ftar_status_is_retryable(B.FTAR_ERR_STALE_PLAN)
-    assert not any(B.ftar_status_is_retryable(s) for s in (0, 1, 2, 3, 4, 32))
+    assert not any(B.ftar_status_is_retryable(s) for s in (0, 1, 2, 3, 4, 5, 32))
 
 
 def test_plan_rejects_bad_arguments(B):
