@@ -2,23 +2,28 @@
 """Benchmark of the FTAR GPU data path on one MI355X.
 
 One "step" is one pass of the whole hot path over one batch of synthetic gradients with the
-shape of the second benchmark workload (8 replicas x 64 Mi bf16 elements, replica 3 dead):
+shape of the largest single-GPU benchmark workload, cfg 4: one GPU's gradient shard, 8 replicas x
+2,000,000,000 bf16 elements (32 GB of inputs), all live:
 
   plan            ftar_plan over the live set                       (CPU)
-  masked reduce   ftar_reduce_masked -> out                         (1 kernel)
-  ring schedule   N-1 ftar_reduce_step + N-1 ftar_allgather_step    (12 kernels for N = 7)
+  masked reduce   ftar_reduce_masked -> out                         (36 GB per call)
+  ring schedule   N-1 ftar_reduce_step + N-1 ftar_allgather_step    (14 kernels for N = 8)
   bucketed        ftar_reduce_masked_bucketed, 25 Mi-element buckets with per-bucket
-                  live masks drawn inside the live set              (1 kernel)
+                  live masks                                        (1 kernel)
 
 `value` is the algorithmic bytes (read + written) of all those kernels divided by the wall time
 of the step, inputs resident in HBM.  Every kernel launch of the timed region carries a pair of
 HIP events that its own dispatch records on the stream it runs on (begin and end of the kernel);
 `roofline` reports the kernel kind that takes the largest share of the step, `kernels` reports
-all kinds.  `cpu_baseline` times the CPU oracle (plain
-single-threaded C++) on the same step on the host.
+all kinds (the first row is the masked reduce of cfg 4 itself).  Nothing of this workload fits
+the 256 MB Infinity Cache, so every fraction is an HBM figure.  `ring_cfg3a` adds the four ring
+kernel kinds on the third workload (16 x 256 Mi bf16, 15 + 15 steps), measured the same way after
+the timed region.  `cpu_baseline` times the CPU oracle (plain single-threaded C++) on a stated
+sample of the same step on the host.
 
 The ring runs in place, so later steps reduce already reduced buffers; kernel time does not
-depend on the values.  Parity is checked once, before timing, on fresh inputs.
+depend on the values.  Parity is checked once, before timing, on fresh inputs, on sampled slabs
+against the oracle.
 """
 import argparse
 import json
@@ -481,13 +486,122 @@ def full_size_launches(B, W, torch):
     print(json.dumps({"copy_bytes": 128 * W.M, "groups": groups}), flush=True)
 
 
+def diagnose_launches(B, W, torch):
+    """For runs under `rocprofv3 --pmc` that look at WHY a kernel runs at the rate it does: bare
+    streaming kernels over 1 GiB streams (8 read; 8 read + 1 written; 1 written; 8 written; 1 + 1)
+    next to the product kernels on streams of the same size (the one-shot reduce over 8 x 512 Mi
+    bf16; one clean 16-ring over 16 x 256 Mi bf16), every launch once, in this order.  Prints the
+    order and the algorithmic bytes as one JSON line."""
+    dev = "cuda:0"
+    GiB = 1 << 30
+    groups = []
+    pool = [torch.randint(-2**31, 2**31 - 1, (GiB // 4,), dtype=torch.int32, device=dev) for _ in range(9)]
+    torch.cuda.synchronize()
+    for n_read, n_written in ((8, 0), (8, 1), (0, 1), (0, 8), (1, 1)):
+        B.ftar_probe_stream(pool[:n_read], pool[n_read:n_read + n_written], fill=1)
+        torch.cuda.synchronize()
+        groups.append({"kernel": "k_probe_stream<%d,%d>" % (n_read, n_written), "dispatches": 1,
+                       "read": n_read * GiB, "written": n_written * GiB})
+    bufs = [p.view(torch.bfloat16) for p in pool[:8]]        # any bit pattern is a valid input
+    out = pool[8].view(torch.bfloat16)
+    B.ftar_reduce_masked(bufs, 0xFF, out)
+    torch.cuda.synchronize()
+    groups.append({"kernel": "k_reduce_masked<bf16,N=8>", "dispatches": "several (about 1 GiB of traffic each)",
+                   "read": 8 * GiB, "written": GiB})
+    del bufs, out, pool
+    torch.cuda.empty_cache()
+    w = W.configs()[2]
+    E = w.elem_bytes
+    bufs = W.draw_replicas(w, dev)
+    acc = torch.empty(w.count, dtype=torch.float32, device=dev)
+    plan = B.ftar_plan(w.n_replicas, 0xFFFF, w.count, w.chunk_elems, w.dtype)
+    torch.cuda.synchronize()
+    B.ring_allreduce(plan, bufs, acc)
+    torch.cuda.synchronize()
+    N = 16
+    groups.append({"kernel": "k_ring_reduce first/mid x13/last", "dispatches": 15,
+                   "read": (2 * E + (N - 3) * (4 + E) + (4 + E)) * w.count,
+                   "written": (4 + (N - 3) * 4 + E) * w.count})
+    groups.append({"kernel": "k_ring_allgather", "dispatches": 15, "read": (N - 1) * E * w.count,
+                   "written": (N - 1) * E * w.count})
+    print(json.dumps({"groups": groups}), flush=True)
+
+
+def _same(np, got, want):
+    nan_g = (got & 0x7FFF) > 0x7F80 if got.dtype == np.uint16 else np.isnan(got)
+    nan_w = (want & 0x7FFF) > 0x7F80 if want.dtype == np.uint16 else np.isnan(want)
+    bits = np.uint16 if got.dtype == np.uint16 else np.uint32
+    return bool(np.array_equal(nan_g, nan_w) and
+                np.array_equal(got.view(bits)[~nan_g], want.view(bits)[~nan_w]))
+
+
+KERNEL_NAME = {"reduce_masked": "k_reduce_masked", "rs_first": "k_ring_reduce<kRsFirst>",
+               "rs_mid": "k_ring_reduce<kRsMid>", "rs_last": "k_ring_reduce<kRsLast>",
+               "rs_only": "k_ring_reduce<kRsOnly>", "allgather": "k_ring_allgather",
+               "bucketed": "k_reduce_bucketed"}
+
+
+def _kernel_table(kinds, dur, bytes_of, wall_s):
+    rows = []
+    for kind in dict.fromkeys(kinds):
+        d = dur[kind]
+        avg = sum(d) / len(d)
+        ach = bytes_of[kind] / avg / 1e9
+        rows.append({"kind": kind, "kernel": KERNEL_NAME[kind], "launches_per_step": kinds.count(kind),
+                     "avg_us": round(avg * 1e6, 2), "bytes_per_launch": bytes_of[kind],
+                     "achieved_GBps": round(ach, 1), "frac_of_peak": round(ach / HBM_PEAK_GBS, 4),
+                     "share_of_step": round(avg * kinds.count(kind) / wall_s, 4)})
+    return rows
+
+
+def ring_cfg3a(B, W, torch, hip_events, reps=3):
+    """The four ring kernel kinds on the third workload (16 x 256 Mi bf16, clean 16-ring): average
+    dispatch-recorded duration per kind over `reps` whole schedules (one warm-up schedule first)."""
+    w = W.configs()[2]
+    dev = "cuda:0"
+    bufs = W.draw_replicas(w, dev)
+    acc = torch.empty(w.count, dtype=torch.float32, device=dev)
+    plan = B.ftar_plan(w.n_replicas, w.live_mask, w.count, w.chunk_elems, w.dtype)
+    N, E = plan.n_live, w.elem_bytes
+    kinds = ["rs_first"] + ["rs_mid"] * (N - 3) + ["rs_last"] + ["allgather"] * (N - 1)
+    bytes_of = {k: algorithmic_bytes(k, N, E, w.count) for k in set(kinds)}
+    B.ring_allreduce(plan, bufs, acc)
+    torch.cuda.synchronize()
+    events = [[(hip_events.create(), hip_events.create()) for _ in kinds] for _ in range(reps)]
+    t0 = time.perf_counter()
+    for ev in events:
+        for i in range(2 * (N - 1)):
+            B.ftar_time_next_launch(ev[i][0], ev[i][1])
+            if i < N - 1:
+                B.ftar_reduce_step(plan, i, bufs, acc)
+            else:
+                B.ftar_allgather_step(plan, i - (N - 1), bufs)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / reps
+    dur = {}
+    for ev in events:
+        for i, kind in enumerate(kinds):
+            dur.setdefault(kind, []).append(hip_events.elapsed_s(ev[i][0], ev[i][1]))
+    total = sum(bytes_of[k] for k in kinds)
+    plan.destroy()
+    return {"workload": w.name, "n_live": N, "count": w.count, "schedules_timed": reps,
+            "ms_per_schedule": round(wall * 1e3, 3), "bytes_per_schedule": total,
+            "schedule_GBps": round(total / wall / 1e9, 1),
+            "kernels": _kernel_table(kinds, dur, bytes_of, wall)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
+    ap.add_argument("--no-ring-cfg3a", action="store_true",
+                    help="skip the extra measurement of the ring kernel kinds on the third workload")
+    ap.add_argument("--count", type=int, default=None,
+                    help="development only: elements per replica instead of cfg 4's 2,000,000,000 "
+                         "(the workload name in the output then says so)")
     ap.add_argument("--all-configs", metavar="PATH", default=None,
                     help="instead of the step benchmark, run the five benchmark workloads at full "
                          "size (parity on sampled slabs, timing, oracle timing on a sample) and "
@@ -495,6 +609,11 @@ def main():
     ap.add_argument("--full-size-launches", action="store_true",
                     help="launch every product kernel of the full-size workloads once (for a run under "
                          "rocprofv3 --pmc) and print the bytes each group of dispatches should move")
+    ap.add_argument("--tuning", metavar="BLOCKS_PER_CU,FLAGS", default=None,
+                    help="development only: ftar_set_tuning before anything runs (the output says so)")
+    ap.add_argument("--diagnose-launches", action="store_true",
+                    help="bare streaming kernels and the product kernels on 1 GiB streams, each launched "
+                         "once (for runs under rocprofv3 --pmc with stall and request counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (simulated replicas are separate buffers on "
@@ -512,28 +631,37 @@ def main():
     B.lib()  # raises if libftar.so is not built: there is no fallback path
     torch.cuda.set_device(0)
     dev = "cuda:0"
+    if args.tuning:
+        bpc, flags = (int(x, 0) for x in args.tuning.split(","))
+        B.ftar_set_tuning(bpc, flags)
     if args.all_configs:
         all_configs_report(args.all_configs, B, W, torch, np)
         return
     if args.full_size_launches:
         full_size_launches(B, W, torch)
         return
+    if args.diagnose_launches:
+        diagnose_launches(B, W, torch)
+        return
 
-    w = W.configs()[1]
-    E = w.elem_bytes
-    count = w.count
-    n = w.n_replicas
-    mask = w.live_mask
-    bucket_elems = 25 * W.M
+    w = W.configs()[3]                      # cfg 4: the largest single-GPU workload
+    name = w.name + ("" if not args.tuning else "_with_tuning_" + args.tuning)
+    if args.count is not None:
+        w = w.scaled(args.count)
+        name = "%s_scaled_to_%d_elements" % (name, args.count)
+    E, count, n, mask = w.elem_bytes, w.count, w.n_replicas, w.live_mask
+    bucket_elems = min(25 * W.M, count)
     n_buckets = (count + bucket_elems - 1) // bucket_elems
-    bmasks = [m & mask for m in W.bucket_masks(n, n_buckets, 0.9, seed=w.seed)]
-    live_list = [r for r in range(n) if (mask >> r) & 1]
-    bmasks = [m if m else 1 << live_list[b % len(live_list)] for b, m in enumerate(bmasks)]
+    bmasks = W.bucket_masks(n, n_buckets, 0.9, seed=w.seed)
 
+    t_setup = time.perf_counter()
     bufs = W.draw_replicas(w, dev)
     out = torch.empty(count, dtype=w.dtype, device=dev)
     out_b = torch.empty(count, dtype=w.dtype, device=dev)
     acc = torch.empty(count, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    print("bench.py: %d x %d %s drawn in %.1f s" % (n, count, "bf16" if E == 2 else "f32",
+                                                    time.perf_counter() - t_setup), file=sys.stderr, flush=True)
     stream = torch.cuda.Stream()  # default priority
 
     plan0 = B.ftar_plan(n, mask, count, w.chunk_elems, w.dtype)
@@ -552,6 +680,7 @@ def main():
     bucket_len = [min(count, (b + 1) * bucket_elems) - b * bucket_elems for b in range(n_buckets)]
     bytes_of["bucketed"] = sum(L * E * (bin(m).count("1") + 1) for L, m in zip(bucket_len, bmasks))
     step_bytes = sum(bytes_of[k] for k in kinds)
+    per_elem_step = step_bytes / count
 
     def step(events=None):
         """events: one (start, stop) hipEvent_t pair per kernel of the step, or None."""
@@ -581,49 +710,75 @@ def main():
         sys.path.insert(0, os.path.join(ROOT, "oracle"))
         import ftar_oracle as oracle
         code = oracle.BF16 if w.dtype == torch.bfloat16 else oracle.F32
-        host_in = [W.to_numpy_bits(b) for b in bufs]
-
-        def same(got, want):
-            nan_g = (got & 0x7FFF) > 0x7F80 if got.dtype == np.uint16 else np.isnan(got)
-            nan_w = (want & 0x7FFF) > 0x7F80 if want.dtype == np.uint16 else np.isnan(want)
-            bits = np.uint16 if got.dtype == np.uint16 else np.uint32
-            return np.array_equal(nan_g, nan_w) and \
-                np.array_equal(got.view(bits)[~nan_g], want.view(bits)[~nan_w])
+        SLAB = min(1 << 18, count)
+        rng = np.random.default_rng(w.seed)
+        starts = {0, count - SLAB}
+        for x in [1 << 30, 1 << 31] + oracle.geometry(n, mask, count, w.chunk_elems)[1:-1] + \
+                [b * bucket_elems for b in (1, 2, n_buckets // 2, n_buckets - 1)]:
+            if 0 < x < count:
+                starts.add(min(max(0, x - SLAB // 2), count - SLAB))
+        for x in rng.integers(0, max(1, count - SLAB), 8):
+            starts.add(int(x))
+        starts = sorted(starts)
 
         if not args.no_parity:
+            orig = {st: [W.to_numpy_bits(b[st:st + SLAB]) for b in bufs] for st in starts}
             step()                       # one whole step on the fresh inputs
             torch.cuda.synchronize()
-            got_out = W.to_numpy_bits(out)
-            got_ring = [W.to_numpy_bits(b) for b in bufs]
-            got_b = W.to_numpy_bits(out_b)
-        # the oracle's step: one-shot reduce, message-passing ring, per-bucket reduce
-        # (the bucketed pass runs on the ring's output, as in the GPU step)
-        ring_ref = [h.copy() for h in host_in]
-        want_b = np.empty(count, dtype=host_in[live_list[0]].dtype)
-        t0 = time.perf_counter()
-        want_out = oracle.reduce_masked(host_in, mask, code)
-        oracle.ring_per_rank(ring_ref, mask, w.chunk_elems, code)
-        for b in range(n_buckets):
-            lo, hi = b * bucket_elems, min(count, (b + 1) * bucket_elems)
-            slabs = [ring_ref[r][lo:hi] if (bmasks[b] >> r) & 1 else None for r in range(n)]
-            want_b[lo:hi] = oracle.reduce_masked(slabs, bmasks[b], code)
-        cpu_s = time.perf_counter() - t0
-        if not args.no_cpu_baseline:
-            cpu_baseline = {"value": round(step_bytes / cpu_s / 1e9, 3), "unit": "GB/s", "cores": 1,
-                            "kind": "oracle", "seconds": round(cpu_s, 3),
-                            "host_cpus_visible": os.cpu_count(),
-                            "sample": "one full step of the workload (all %d elements per replica): "
-                                      "one-shot masked reduce + message-passing ring + per-bucket "
-                                      "reduce, same algorithmic bytes as the GPU step" % count}
-        if not args.no_parity:
-            ok = same(got_out, want_out) and same(got_b, want_b)
-            for r in range(n):
-                ok = ok and same(got_ring[r], ring_ref[r])
-            parity = "bit-exact vs oracle, every element of the step" if ok else "MISMATCH"
+            ok = True
+            for st in starts:
+                want_out = oracle.reduce_masked(orig[st], mask, code)
+                ok = ok and _same(np, W.to_numpy_bits(out[st:st + SLAB]), want_out)
+                want_ring = oracle.ring_closed_form(orig[st], mask, count, w.chunk_elems, code,
+                                                    begin=st, length=SLAB)
+                for r in range(n):
+                    got = W.to_numpy_bits(bufs[r][st:st + SLAB])
+                    ok = ok and _same(np, got, want_ring if (mask >> r) & 1 else orig[st][r])
+                # the bucketed pass runs on the ring's output: every live buffer holds want_ring
+                got_b = W.to_numpy_bits(out_b[st:st + SLAB])
+                lo = st
+                while lo < st + SLAB:
+                    b = lo // bucket_elems
+                    hi = min(st + SLAB, (b + 1) * bucket_elems)
+                    piece = want_ring[lo - st:hi - st]
+                    slabs = [piece if (bmasks[b] >> r) & 1 else None for r in range(n)]
+                    ok = ok and _same(np, got_b[lo - st:hi - st], oracle.reduce_masked(slabs, bmasks[b], code))
+                    lo = hi
+            parity = ("bit-exact vs oracle on %d slabs of %d elements (ends, 2^30, portion and bucket "
+                      "boundaries, random): masked reduce, all %d ring buffers, bucketed reduce"
+                      % (len(starts), SLAB, n)) if ok else "MISMATCH"
             if not ok:
                 print("bench.py: GPU step does not match the oracle", file=sys.stderr)
                 sys.exit(1)
-        del host_in, ring_ref
+            del orig
+        if not args.no_cpu_baseline:
+            # the oracle's step on a bounded sample: CS slabs of CL elements, each slab put through
+            # the one-shot reduce, the message-passing ring (the slab as a ring of its own: the same
+            # work per element as in the full ring) and the per-bucket reduce
+            CL = min(1 << 25, count)
+            CS = max(1, min(8, count // CL))
+            cpu_s = 0.0
+            for i in range(CS):
+                st = (count - CL) * i // max(1, CS - 1) if CS > 1 else 0
+                slab = [W.to_numpy_bits(b[st:st + CL]) for b in bufs]
+                t0 = time.perf_counter()
+                oracle.reduce_masked(slab, mask, code)
+                oracle.ring_per_rank(slab, mask, w.chunk_elems, code)
+                lo = 0
+                while lo < CL:
+                    b = (st + lo) // bucket_elems
+                    hi = min(CL, (b + 1) * bucket_elems - st)
+                    oracle.reduce_masked([x[lo:hi] if (bmasks[b] >> r) & 1 else None for r, x in enumerate(slab)],
+                                         bmasks[b], code)
+                    lo = hi
+                cpu_s += time.perf_counter() - t0
+                del slab
+            cpu_baseline = {"value": round(per_elem_step * CS * CL / cpu_s / 1e9, 3), "unit": "GB/s", "cores": 1,
+                            "kind": "oracle", "seconds": round(cpu_s, 3), "host_cpus_visible": os.cpu_count(),
+                            "sample": "%d slabs of %d elements per replica (%.2f %% of the workload), each put "
+                                      "through the whole step: one-shot masked reduce + message-passing ring "
+                                      "(the slab as a ring of its own) + per-bucket reduce; same algorithmic "
+                                      "bytes per element as the GPU step" % (CS, CL, 100.0 * CS * CL / count)}
 
     for _ in range(args.warmup):
         step()
@@ -642,49 +797,42 @@ def main():
     for ev in events:
         for i, kind in enumerate(kinds):
             dur.setdefault(kind, []).append(hip_events.elapsed_s(ev[i][0], ev[i][1]))
-    kernels = []
-    for kind in dict.fromkeys(kinds):
-        d = dur[kind]
-        avg = sum(d) / len(d)
-        ach = bytes_of[kind] / avg / 1e9
-        kernels.append({"kind": kind, "launches_per_step": kinds.count(kind),
-                        "avg_us": round(avg * 1e6, 2), "bytes_per_launch": bytes_of[kind],
-                        "achieved_GBps": round(ach, 1), "frac_of_peak": round(ach / HBM_PEAK_GBS, 4),
-                        "share_of_step": round(avg * kinds.count(kind) / (ms_per_step * 1e-3), 4)})
+    kernels = _kernel_table(kinds, dur, bytes_of, ms_per_step * 1e-3)
     dom = max(kernels, key=lambda k: k["share_of_step"])
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
-    kernel_name = {"reduce_masked": "k_reduce_masked", "rs_first": "k_ring_reduce<kRsFirst>",
-                   "rs_mid": "k_ring_reduce<kRsMid>", "rs_last": "k_ring_reduce<kRsLast>",
-                   "rs_only": "k_ring_reduce<kRsOnly>", "allgather": "k_ring_allgather",
-                   "bucketed": "k_reduce_bucketed"}
+    # HBM bytes per launch from the committed rocprofv3 --pmc summary: only if it was taken on this workload
+    traffic = None
+    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(traffic_file):
+        try:
+            traffic = json.load(open(traffic_file)).get(name, {}).get(dom["kind"])
+        except Exception:
+            traffic = None
     result = {
         "metric": "masked gradient all-reduce GB/s (read+write) and % of MI355X HBM peak",
         "value": round(value, 1), "unit": "GB/s", "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": w.name, "n_replicas": n, "live_mask": bin(mask), "n_live": N,
-                   "count": count, "storage_dtype": "bf16", "chunk_elems": w.chunk_elems,
+        "config": {"workload": name, "n_replicas": n, "live_mask": bin(mask), "n_live": N,
+                   "count": count, "storage_dtype": "bf16" if E == 2 else "f32", "chunk_elems": w.chunk_elems,
                    "bucket_elems": bucket_elems,
                    "step": "plan + masked reduce + %d RS + %d AG step kernels + bucketed reduce"
                            % (N - 1, N - 1),
                    "bytes_per_step": step_bytes},
-        "roofline": {"bound": "hbm", "kernel": kernel_name[dom["kind"]], "achieved": dom["achieved_GBps"],
+        "roofline": {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["achieved_GBps"],
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(dom["achieved_GBps"] / HBM_PEAK_GBS, 4),
-                     "traffic": None, "bytes_per_launch": dom["bytes_per_launch"],
+                     "traffic": traffic, "bytes_per_launch": dom["bytes_per_launch"],
                      "avg_us": dom["avg_us"]},
         "kernels": kernels,
         "cpu_baseline": cpu_baseline,
         "parity": parity,
     }
-    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(traffic_file):
-        try:
-            t = json.load(open(traffic_file))
-            result["roofline"]["traffic"] = t.get(dom["kind"])
-        except Exception:
-            pass
+    if not args.no_ring_cfg3a and args.count is None:
+        del bufs, out, out_b, acc
+        torch.cuda.empty_cache()
+        result["ring_cfg3a"] = ring_cfg3a(B, W, torch, hip_events)
     print(json.dumps(result), flush=True)
 
 

@@ -363,7 +363,7 @@ static ftar_status_t reduce_masked_common(const void* const* bufs, int n_replica
   const int divisor = contributors_only ? n_src : N;
   if (divisor <= 0) return fail(FTAR_ERR_NO_LIVE);
   const float scale = op == FTAR_SUM ? 1.0f : 1.0f / static_cast<float>(divisor);
-  hipError_t e = launch_reduce_masked(tab, n_src, count, dtype, out_dtype, vec, out, scale, n_src != N,
+  hipError_t e = launch_reduce_masked(tab, n_src, count, dtype, out_dtype, vec, out, scale, n_src != N, 0,
                                       static_cast<hipStream_t>(stream));
   return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
 }
@@ -444,7 +444,7 @@ ftar_status_t ftar_reduce_masked_bucketed(const void* const* bufs, int n_replica
         t_time_start = b == 0 ? t_start : nullptr;
         t_time_stop = b + 1 == n_buckets ? t_stop : nullptr;
         hipError_t e = launch_reduce_masked(live, N, len, dtype, dtype, vec, static_cast<char*>(out) + first * es,
-                                            scales.s[N], false, static_cast<hipStream_t>(stream));
+                                            scales.s[N], false, count, static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return fail(FTAR_ERR_DEVICE);
       }
       return FTAR_OK;

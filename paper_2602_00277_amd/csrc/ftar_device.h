@@ -159,12 +159,15 @@ template <typename T, int VEC, int NSRC, bool ACC_IN, int ACC_OUT, int U, int PO
 __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc_in, float* acc_out,
                                          T* out, float scale, size_t v, unsigned long long zm = 0,
                                          float zterm = 0.0f) {
-  static_assert(!(ACC_IN || ACC_OUT) || VEC <= 4, "fp32 partials are moved 4 at a time");
   static_assert(ACC_OUT != 3 || __is_same(T, float), "mode 3 narrows fp32 inputs");
+  static_assert((ACC_OUT != 2 && ACC_OUT != 3) || VEC <= 4, "results of the other type are moved 4 at a time");
   typedef typename Raw<T, VEC>::type R;
   typedef typename Raw<float, (VEC == 1 ? 1 : 4)>::type A;
+  // fp32 partial sums move as 16-byte vectors: a lane that takes 8 elements (one 16-byte bf16
+  // vector) takes two of them, at vector indices 2v and 2v + 1, so acc keeps its natural order
+  constexpr int AV = VEC == 8 ? 2 : 1;
   R raw[U][NSRC];
-  A ain[U];
+  A ain[U][AV];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
 #pragma unroll
@@ -175,20 +178,37 @@ __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc
   }
   if constexpr (ACC_IN) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) ain[u] = ld<POL>(reinterpret_cast<const A*>(acc_in) + v + u * kThreads);
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int q = 0; q < AV; ++q)
+        ain[u][q] = ld<POL>(reinterpret_cast<const A*>(acc_in) + (v + u * kThreads) * AV + q);
+    }
   }
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     float a[VEC], x[VEC];
-    if constexpr (ACC_IN) widen(ain[u], a);
-    else widen(raw[u][0], a);
+    if constexpr (ACC_IN && VEC == 8) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        a[e] = ain[u][0][e];
+        a[4 + e] = ain[u][1][e];
+      }
+    } else if constexpr (ACC_IN) {
+      widen(ain[u][0], a);
+    } else {
+      widen(raw[u][0], a);
+    }
 #pragma unroll
     for (int j = (ACC_IN ? 0 : 1); j < NSRC; ++j) {
       widen(raw[u][j], x);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) a[e] = a[e] + x[e];
     }
-    if constexpr (ACC_OUT == 1) {
+    if constexpr (ACC_OUT == 1 && VEC == 8) {
+      const f32x4 lo = {a[0], a[1], a[2], a[3]}, hi = {a[4], a[5], a[6], a[7]};
+      st<POL>(reinterpret_cast<f32x4*>(acc_out) + (v + u * kThreads) * 2, lo);
+      st<POL>(reinterpret_cast<f32x4*>(acc_out) + (v + u * kThreads) * 2 + 1, hi);
+    } else if constexpr (ACC_OUT == 1) {
       st<POL>(reinterpret_cast<A*>(acc_out) + v + u * kThreads, narrow<A, VEC>(a));
     } else {
       if constexpr (ZT) {
@@ -208,6 +228,67 @@ __device__ __forceinline__ void sum_tile(T* const (&src)[NSRC], const float* acc
     }
   }
 }
+
+// The result vector type of a tile for each store mode of sum_tile.
+template <typename T, int VEC, int ACC_OUT> struct OutVec { typedef typename Raw<T, VEC>::type type; };
+template <typename T, int VEC> struct OutVec<T, VEC, 2> { typedef typename Raw<float, (VEC == 1 ? 1 : 4)>::type type; };
+template <typename T, int VEC> struct OutVec<T, VEC, 3> { typedef typename Raw<bf16, VEC>::type type; };
+
+// sum_tile without the stores: the U finished result vectors of the tile (modes 0, 2 and 3), for
+// kernels that stage their results and write them out later.  Same loads, same arithmetic.
+template <typename T, int VEC, int NSRC, int ACC_OUT, int U, int POL, bool ZT>
+__device__ __forceinline__ void sum_tile_values(T* const (&src)[NSRC], float scale, size_t v, float zterm,
+                                                typename OutVec<T, VEC, ACC_OUT>::type (&res)[U]) {
+  static_assert(ACC_OUT == 0 || ACC_OUT == 2 || ACC_OUT == 3, "finished results only");
+  static_assert(ACC_OUT == 0 || VEC <= 4, "results of the other type are moved 4 at a time");
+  typedef typename Raw<T, VEC>::type R;
+  typedef typename OutVec<T, VEC, ACC_OUT>::type O;
+  R raw[U][NSRC];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+#pragma unroll
+    for (int j = 0; j < NSRC; ++j) raw[u][j] = ld<POL>(reinterpret_cast<const R*>(src[j]) + v + u * kThreads);
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    float a[VEC], x[VEC];
+    widen(raw[u][0], a);
+#pragma unroll
+    for (int j = 1; j < NSRC; ++j) {
+      widen(raw[u][j], x);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) a[e] = a[e] + x[e];
+    }
+    if constexpr (ZT) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) a[e] = a[e] + zterm;
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) a[e] = a[e] * scale;
+    res[u] = narrow<O, VEC>(a);
+  }
+}
+
+// ---- write windows ------------------------------------------------------------------------
+// A sum over many streams writes little (1/(N+1) of its bytes), but every write that lands among
+// the reads costs the memory more than its share: 8 streams read alone run at 6.9 TB/s, one
+// stream written alone at 6.4 TB/s, yet the plain 8 + 1 mix only reaches 5.6-5.7 TB/s.  Counters
+// show no stall in the L2 <-> fabric path and the loss does not respond to more loads in flight,
+// cache-policy bits, store bursts of a single workgroup or stream alignment; it does respond to
+// WHEN the chip writes.  So a workgroup stages its finished vectors in LDS and writes them out
+// only inside windows of the 100 MHz wall clock, which is the same for all compute units: the
+// whole chip then reads for tens of microseconds and writes in one short burst, with no
+// communication between workgroups (8 + 1 streams of 1 GiB: 5.7 -> 6.5 TB/s; of 3 GiB: 5.6 ->
+// 6.4).  It pays from four sources on; with a third or more of the bytes written the LDS cannot
+// hold a long enough period and nothing is gained.  A full stage is written out at once, whatever
+// the clock says, so progress never depends on the clock.
+struct WriteWindow {
+  unsigned period_mask;  // period - 1, period a power of two in 10 ns ticks; 0 = no staging at all
+  unsigned write_ticks;  // the window is [0, write_ticks) of every period
+  unsigned min_tiles;    // flush in a window only with at least this many tiles staged
+};
+
+constexpr int kStageBytes = 144 * 1024;  // of the 160 KiB of LDS a compute unit has
 
 // Persistent loop of block bx of gx over the `len` elements that start at the
 // given pointers: full tiles grid-strided, then one block finishes the whole
@@ -364,14 +445,17 @@ template <typename T, int VEC, int MODE, int U, int POL>
 __device__ __forceinline__ void ring_reduce_pass(T* const* s_tab, const unsigned long long* s_seg,
                                                  const unsigned long long* s_tile, int N, int step,
                                                  float* acc, float scale, unsigned bx, unsigned gx,
-                                                 size_t buf_off = 0, unsigned long long zpos = 0) {
+                                                 size_t buf_off = 0, unsigned long long zpos = 0,
+                                                 size_t g_begin = 0, size_t g_end = ~static_cast<size_t>(0)) {
   // zpos: bit p set = the replica at ring position p is a zero-gradient participant
   // buf_off: first element of the partition in the replica buffers (acc is partition-relative)
+  // [g_begin, g_end): the part of the flat tile sequence this launch covers (clipped to the whole)
   constexpr size_t kTileElems = static_cast<size_t>(kThreads) * U * VEC;
-  const size_t total = uniform_u64(s_tile[N]);
+  const size_t all = uniform_u64(s_tile[N]);
+  const size_t total = g_end < all ? g_end : all;
   int k = 0;
   size_t next = uniform_u64(s_tile[1]);
-  for (size_t g = bx; g < total; g += gx) {
+  for (size_t g = g_begin + bx; g < total; g += gx) {
     const RingTile t = ring_tile_of<kTileElems>(g, k, next, s_seg, s_tile);
     float* a = acc + t.begin;  // never dereferenced in the N == 2 mode
     const size_t b0 = buf_off + t.begin;
@@ -401,15 +485,17 @@ __device__ __forceinline__ void ring_reduce_pass(T* const* s_tab, const unsigned
 template <typename T, int VEC, int U, int POL>
 __device__ __forceinline__ void ring_allgather_pass(T* const* s_tab, const unsigned long long* s_seg,
                                                     const unsigned long long* s_tile, int N, int step,
-                                                    unsigned bx, unsigned gx, size_t buf_off = 0) {
+                                                    unsigned bx, unsigned gx, size_t buf_off = 0,
+                                                    size_t g_begin = 0, size_t g_end = ~static_cast<size_t>(0)) {
   typedef typename Raw<T, VEC>::type R;
   typedef typename Raw<T, 1>::type R1;
   constexpr size_t kTileElems = static_cast<size_t>(kThreads) * U * VEC;
   const unsigned tid = threadIdx.x;
-  const size_t total = uniform_u64(s_tile[N]);
+  const size_t all = uniform_u64(s_tile[N]);
+  const size_t total = g_end < all ? g_end : all;
   int k = 0;
   size_t next = uniform_u64(s_tile[1]);
-  for (size_t g = bx; g < total; g += gx) {
+  for (size_t g = g_begin + bx; g < total; g += gx) {
     const RingTile t = ring_tile_of<kTileElems>(g, k, next, s_seg, s_tile);
     const T* from = uniform_ptr(s_tab[(t.k + step + N - 1) % N]) + buf_off + t.begin;
     T* to = uniform_ptr(s_tab[(t.k + step) % N]) + buf_off + t.begin;
@@ -486,7 +572,11 @@ inline LaunchCfg bucketed_cfg(int n_replicas, size_t out_bytes) {
 
 inline LaunchCfg ring_reduce_cfg(RingMode mode, size_t count) {
   if (mode == kRsMid) return launch_cfg(1, count * 4 <= 256 * kMiB ? 1 : 3);
-  return launch_cfg(2, 1);
+  // First and last step: ordinary stores while the next step can find them in the cache.  Beyond
+  // that non-temporal stores, and the last step (three quarters of its bytes are reads) with one
+  // workgroup per CU (16 x 256 Mi bf16: last step 4.97 -> 6.43 TB/s, first step 5.69 -> 6.04).
+  if (count * 4 <= 512 * kMiB) return launch_cfg(2, 1);
+  return launch_cfg(mode == kRsLast ? 1 : 2, 3);
 }
 
 inline LaunchCfg ring_allgather_cfg(size_t count, size_t elem_bytes) {
@@ -523,10 +613,11 @@ hipError_t with_policy(const LaunchCfg& cfg, F f) {
   }
 }
 
-// Vectors per lane per tile in the ring kernels: tuning flag bits 8..11 (2, 4 or 8), default 4.
-inline int ring_unroll() {
+// Vectors per lane per tile in the ring kernels: tuning flag bits 8..11 (2, 4 or 8); default 4, or 2
+// when a lane's vector is 8 elements wide (the same bytes in flight).
+inline int ring_unroll(int vec) {
   const int u = (current_tuning().flags >> 8) & 0xf;
-  return (u == 2 || u == 8) ? u : 4;
+  return (u == 2 || u == 4 || u == 8) ? u : vec == 8 ? 2 : 4;
 }
 
 // Tiles before each portion (tile = kThreads*U*vec elements; the last tile of a portion may be short).

@@ -87,9 +87,11 @@ int device_cu_count();  // of the current device; cached
 // live: the n_src buffers that are read, in summation order (zero-gradient participants already
 // left out: zero_participants says whether there were any; n_src may then be 0).
 // dtype: element type of the inputs; out_dtype: of the result (any of the four pairs).
+// whole_count: elements of the whole output when this call writes one part of it (the store policy
+// follows the whole output's size); 0 = this call is the whole.
 hipError_t launch_reduce_masked(const PtrTable& live, int n_src, size_t count, ftar_dtype_t dtype,
                                 ftar_dtype_t out_dtype, bool vec, void* out, float scale,
-                                bool zero_participants, hipStream_t stream);
+                                bool zero_participants, size_t whole_count, hipStream_t stream);
 
 hipError_t launch_reduce_bucketed(const PtrTable& all, int n_replicas, const BucketTable& masks,
                                   int n_buckets, size_t first_elem, size_t bucket_elems,

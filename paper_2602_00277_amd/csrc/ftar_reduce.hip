@@ -22,6 +22,67 @@ k_reduce_masked(PtrTable live, T* out, float scale, size_t count, float zterm) {
                                                             blockIdx.x, gridDim.x, 0, zterm);
 }
 
+// One-shot masked mean with write windows: results are staged in LDS (a lane only ever reads back
+// what it staged itself, so no barrier is involved) and written out inside the clock windows or
+// when the stage is full.  MODE 0: result of the input type; 2: fp32 from bf16; 3: bf16 from fp32.
+// One workgroup per compute unit (the stage takes most of its LDS).
+template <typename T, int VEC, int N, int U, int POL, int MODE>
+__global__ void __launch_bounds__(kThreads)
+k_reduce_masked_win(PtrTable live, void* out_, float scale, size_t count, float zterm, WriteWindow win) {
+  typedef typename OutVec<T, VEC, MODE>::type O;
+  constexpr int kCap = kStageBytes / (kThreads * static_cast<int>(sizeof(O)));  // vectors per lane
+  static_assert(kCap >= 2 * U, "room for two tiles at least");
+  __shared__ O stage[kCap][kThreads];
+  __shared__ T* s_tab[kMaxReplicas];
+  const unsigned tid = threadIdx.x;
+  if (tid < static_cast<unsigned>(N)) s_tab[tid] = static_cast<T*>(live.p[tid]);
+  __syncthreads();
+  T* src[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) src[j] = uniform_ptr(s_tab[j]);
+  O* out = static_cast<O*>(out_);
+  const size_t n_vec = count / VEC;
+  constexpr size_t kTile = static_cast<size_t>(kThreads) * U;
+  const size_t n_tiles = n_vec / kTile;
+  const size_t gx = gridDim.x;
+  unsigned pending = 0;  // tiles staged, U vectors each
+  size_t first = 0;      // tile of stage[0]; the staged tiles are first, first + gx, ...
+  for (size_t t = blockIdx.x; t < n_tiles; t += gx) {
+    const unsigned now = static_cast<unsigned>(wall_clock64());
+    O res[U];
+    sum_tile_values<T, VEC, N, MODE, U, POL, true>(src, scale, t * kTile + tid, zterm, res);
+    if (pending == 0) first = t;
+#pragma unroll
+    for (int u = 0; u < U; ++u) stage[pending * U + u][tid] = res[u];
+    ++pending;
+    const bool window = (now & win.period_mask) < win.write_ticks && pending >= win.min_tiles;
+    if ((pending + 1) * U > static_cast<unsigned>(kCap) || window) {
+      for (unsigned k = 0; k < pending; ++k) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          st<POL>(out + (first + k * gx) * kTile + tid + u * kThreads, stage[k * U + u][tid]);
+      }
+      pending = 0;
+    }
+  }
+  for (unsigned k = 0; k < pending; ++k) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) st<POL>(out + (first + k * gx) * kTile + tid + u * kThreads, stage[k * U + u][tid]);
+  }
+  // whole vectors past the last full tile and the last count % VEC elements: one workgroup, directly
+  if (blockIdx.x == n_tiles % gx) {
+    constexpr int kMode = MODE;
+    float* fo = static_cast<float*>(out_);
+    T* to = static_cast<T*>(out_);
+    for (size_t v = n_tiles * kTile + tid; v < n_vec; v += kThreads)
+      sum_tile<T, VEC, N, false, kMode, 1, POL, false, true>(src, nullptr, fo, to, scale, v, 0, zterm);
+    if constexpr (VEC > 1) {
+      const size_t e = n_vec * VEC + tid;
+      if (e < count) sum_tile<T, 1, N, false, kMode, 1, POL, false, true>(src, nullptr, fo, to, scale, e, 0, zterm);
+    }
+  }
+}
+
 // The same with a result of the other element type, 4 elements per lane and vector: an fp32 result
 // from bf16 inputs (8-byte loads, 16-byte stores) or a bf16 result from fp32 inputs (16-byte loads,
 // 8-byte stores).  TI = input type; out is float* for bf16 inputs and bf16* for fp32 inputs.
@@ -62,6 +123,8 @@ k_fill_zero(uint16_t* head16, uint32_t* out32, size_t n32, uint16_t* tail16) {
 }
 
 constexpr int kBucketUnroll = 4;  // vectors per lane in one tile of the bucketed kernel
+
+WriteWindow reduce_window(int n_src, size_t traffic_bytes);
 
 template <typename T, int VEC, int N, int POL>
 __device__ __forceinline__ void bucket_tile_n(T* const* s_tab, T* out, float scale, size_t begin,
@@ -125,6 +188,109 @@ k_reduce_bucketed(PtrTable all, int n_replicas, BucketTable masks, ScaleTable sc
     if (!done) {
       if (rem >= kTileElems) sum_any_range<T, VEC, POL>(s_tab, begin, N, out + begin, scale, kTileElems, 0u, 1u, -0.0f);
       else sum_any_range<T, VEC, POL>(s_tab, begin, N, out + begin, scale, rem, 0u, 1u, -0.0f);
+    }
+  }
+}
+
+// The same tile with its results left in the LDS stage instead of memory: lane_stage points at this
+// lane's slot of the first of the tile's kBucketUnroll result vectors; slots are kThreads apart.
+template <typename T, int VEC, int N, int POL>
+__device__ __forceinline__ void bucket_tile_n_staged(T* const* s_tab, float scale, size_t begin,
+                                                     typename Raw<T, VEC>::type* lane_stage) {
+  constexpr int UN = unroll_narrow(N) < kBucketUnroll ? unroll_narrow(N) : kBucketUnroll;
+  typedef typename Raw<T, VEC>::type R;
+  T* src[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) src[j] = uniform_ptr(s_tab[j]) + begin;
+#pragma unroll
+  for (int it = 0; it < kBucketUnroll / UN; ++it) {
+    R res[UN];
+    sum_tile_values<T, VEC, N, 0, UN, POL, false>(src, scale, static_cast<size_t>(it) * kThreads * UN + threadIdx.x,
+                                                  0.0f, res);
+#pragma unroll
+    for (int u = 0; u < UN; ++u) lane_stage[(it * UN + u) * kThreads] = res[u];
+  }
+}
+
+// k_reduce_bucketed with write windows (see WriteWindow): whole tiles of buckets with up to 16 live
+// replicas leave their results in the LDS stage; they are written out inside the clock windows or
+// when the stage is full.  Short tiles (the end of a bucket) and buckets with more live replicas are
+// written directly, as in the plain kernel.  One workgroup per compute unit.
+template <typename T, int VEC, int POL>
+__global__ void __launch_bounds__(kThreads)
+k_reduce_bucketed_win(PtrTable all, int n_replicas, BucketTable masks, ScaleTable scales,
+                      size_t first_elem, size_t bucket_elems, size_t last_len, int n_buckets,
+                      size_t tiles_per_bucket, size_t total_tiles, T* out, WriteWindow win) {
+  typedef typename Raw<T, VEC>::type R;
+  constexpr int kCapTiles = kStageBytes / (kThreads * static_cast<int>(sizeof(R)) * kBucketUnroll);
+  __shared__ R stage[kCapTiles * kBucketUnroll][kThreads];
+  __shared__ T* s_tab[kMaxReplicas];
+  constexpr size_t kTileElems = static_cast<size_t>(kThreads) * kBucketUnroll * VEC;
+  const unsigned tid = threadIdx.x;
+  const size_t gx = gridDim.x;
+  int cur = -1, N = 0;
+  float scale = 0.0f;
+  unsigned pending = 0;  // tiles staged
+  size_t first = 0;      // flat index of the first staged tile; the others follow at distance gx,
+                         // except that directly written tiles are skipped: `skipped` marks them
+  unsigned skipped = 0;  // bit k: the k-th tile since `first` was written directly
+  unsigned span = 0;     // tiles since `first`, staged or skipped
+  for (size_t g = blockIdx.x; g < total_tiles; g += gx) {
+    const unsigned now = static_cast<unsigned>(wall_clock64());
+    const int b = static_cast<int>(g / tiles_per_bucket);
+    const size_t in_bucket = (g - b * tiles_per_bucket) * kTileElems;
+    const size_t begin = first_elem + b * bucket_elems + in_bucket;
+    const size_t rem = (b == n_buckets - 1 ? last_len : bucket_elems) - in_bucket;
+    if (b != cur) {
+      __syncthreads();
+      const unsigned long long mask = masks.mask[b];
+      if (tid < static_cast<unsigned>(n_replicas) && ((mask >> tid) & 1ull))
+        s_tab[__popcll(mask & ((1ull << tid) - 1ull))] = static_cast<T*>(all.p[tid]);
+      __syncthreads();
+      cur = b;
+      N = __popcll(mask);
+      scale = scales.s[N];
+    }
+    if (pending == 0) {
+      first = g;
+      skipped = 0;
+      span = 0;
+    }
+    bool staged = false;
+    if (rem >= kTileElems) {
+      R* lane_stage = &stage[pending * kBucketUnroll][tid];
+      staged = true;
+      switch (N) {
+#define FTAR_CASE(n) case n: bucket_tile_n_staged<T, VEC, n, POL>(s_tab, scale, begin, lane_stage); break;
+        FTAR_CASE(1) FTAR_CASE(2) FTAR_CASE(3) FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7)
+        FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
+        FTAR_CASE(14) FTAR_CASE(15) FTAR_CASE(16)
+#undef FTAR_CASE
+        default: staged = false; break;
+      }
+    }
+    if (staged) {
+      ++pending;
+    } else {
+      skipped |= 1u << span;
+      if (rem >= kTileElems) sum_any_range<T, VEC, POL>(s_tab, begin, N, out + begin, scale, kTileElems, 0u, 1u, -0.0f);
+      else sum_any_range<T, VEC, POL>(s_tab, begin, N, out + begin, scale, rem, 0u, 1u, -0.0f);
+    }
+    ++span;
+    const bool window = (now & win.period_mask) < win.write_ticks && pending >= win.min_tiles;
+    const bool last_iter = g + gx >= total_tiles;
+    if (pending == static_cast<unsigned>(kCapTiles) || span == 32u || window || last_iter) {
+      unsigned k = 0;
+      for (unsigned i = 0; i < span; ++i) {
+        if ((skipped >> i) & 1u) continue;
+        const size_t gi = first + i * gx;
+        const size_t bi = gi / tiles_per_bucket;
+        R* o = reinterpret_cast<R*>(out + first_elem + bi * bucket_elems + (gi - bi * tiles_per_bucket) * kTileElems);
+#pragma unroll
+        for (int u = 0; u < kBucketUnroll; ++u) st<POL>(o + tid + u * kThreads, stage[k * kBucketUnroll + u][tid]);
+        ++k;
+      }
+      pending = 0;
     }
   }
 }
@@ -198,12 +364,62 @@ struct ReduceFixedCvt {
   }
 };
 
+// When the write windows are used and with which period (tuning flags for measurement: 0x80 never,
+// 0x100000 at any size; bits 12..15 = log2 of the period in ticks, bits 16..19 = log2 of period / window).
+// From four sources on, and only when the call moves enough bytes for several periods.  The period
+// grows with the number of sources: the stage must hold what one period produces.
+WriteWindow reduce_window(int n_src, size_t traffic_bytes) {
+  const int flags = current_tuning().flags;
+  WriteWindow w{0u, 0u, 0u};
+  if (n_src < 4 || n_src > 16 || (flags & 0x80) != 0) return w;
+  if (traffic_bytes < (static_cast<size_t>(256) << 20) && (flags & 0x100000) == 0) return w;
+  int lg = n_src >= 6 ? 12 : 11;  // 41 us, 20 us
+  int div = n_src >= 6 ? 3 : 2;   // window = period / 8, period / 4
+  if ((flags >> 12) & 0xf) lg = (flags >> 12) & 0xf;
+  if ((flags >> 16) & 0xf) div = (flags >> 16) & 0xf;
+  w.period_mask = (1u << lg) - 1u;
+  w.write_ticks = (1u << lg) >> div;
+  w.min_tiles = 4;
+  return w;
+}
+
+// MODE as in k_reduce_masked_win.  One workgroup per compute unit.
+template <typename T, int VEC, int MODE>
+struct ReduceWin {
+  const PtrTable& live; int N; size_t count; void* out; float scale; float zterm; WriteWindow win; hipStream_t stream;
+  template <int POL> hipError_t operator()(unsigned) const {
+    // 8-byte loads (fp32 from bf16): twice the vectors for the same bytes in flight; tuning flag 0x20 too
+    const bool wide = MODE == 2 || wide_tiles();
+    const int U = wide ? unroll_wide(N) : unroll_narrow(N);
+    const size_t tiles = count / VEC / (static_cast<size_t>(kThreads) * U);
+    const dim3 grid(grid_x_for(tiles, static_cast<unsigned>(device_cu_count()))), block(kThreads);
+    switch (N) {
+#define FTAR_CASE(n)                                                                                        \
+  case n:                                                                                                   \
+    if (wide)                                                                                               \
+      launch(k_reduce_masked_win<T, VEC, n, unroll_wide(n), POL, MODE>, grid, block, stream, live, out, scale, \
+             count, zterm, win);                                                                            \
+    else                                                                                                    \
+      launch(k_reduce_masked_win<T, VEC, n, unroll_narrow(n), POL, MODE>, grid, block, stream, live, out,    \
+             scale, count, zterm, win);                                                                     \
+    break;
+      FTAR_CASE(4) FTAR_CASE(5) FTAR_CASE(6) FTAR_CASE(7) FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10)
+      FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13) FTAR_CASE(14) FTAR_CASE(15) FTAR_CASE(16)
+#undef FTAR_CASE
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
+};
+
 // whole_out_bytes: output size of the whole call (a long call goes out as several launches)
 template <typename TI, typename TO>
 hipError_t reduce_masked_cvt(const PtrTable& live, int N, size_t count, bool vec, void* out, float scale,
-                             float zterm, size_t whole_out_bytes, hipStream_t stream) {
+                             float zterm, size_t whole_out_bytes, const WriteWindow& win, hipStream_t stream) {
   const LaunchCfg cfg = reduce_cfg(N, whole_out_bytes);
   TO* o = static_cast<TO*>(out);
+  if (vec && win.period_mask != 0)
+    return with_policy(cfg, ReduceWin<TI, 4, (__is_same(TI, float) ? 3 : 2)>{live, N, count, out, scale, zterm, win, stream});
   if (vec && N <= 16) return with_policy(cfg, ReduceFixedCvt<TI>{live, N, count, out, scale, zterm, stream});
   if (vec) return with_policy(cfg, ReduceAny<TI, 4, TO>{live, N, count, o, scale, zterm, stream});
   return with_policy(cfg, ReduceAny<TI, 1, TO>{live, N, count, o, scale, zterm, stream});
@@ -211,9 +427,12 @@ hipError_t reduce_masked_cvt(const PtrTable& live, int N, size_t count, bool vec
 
 template <typename T, int VECW>
 hipError_t reduce_masked_typed(const PtrTable& live, int N, size_t count, bool vec, void* out,
-                               float scale, float zterm, size_t whole_out_bytes, hipStream_t stream) {
+                               float scale, float zterm, size_t whole_out_bytes, const WriteWindow& win,
+                               hipStream_t stream) {
   T* o = static_cast<T*>(out);
   const LaunchCfg cfg = reduce_cfg(N, whole_out_bytes);
+  if (vec && win.period_mask != 0)
+    return with_policy(cfg, ReduceWin<T, VECW, 0>{live, N, count, out, scale, zterm, win, stream});
   if (vec && N <= 16) return with_policy(cfg, ReduceFixed<T, VECW>{live, N, count, o, scale, zterm, stream});
   if (vec) return with_policy(cfg, ReduceAny<T, VECW>{live, N, count, o, scale, zterm, stream});
   return with_policy(cfg, ReduceAny<T, 1>{live, N, count, o, scale, zterm, stream});
@@ -222,7 +441,7 @@ hipError_t reduce_masked_typed(const PtrTable& live, int N, size_t count, bool v
 template <typename T, int VEC>
 struct Bucketed {
   const PtrTable& all; int n_replicas; const BucketTable& masks; int n_buckets; size_t first_elem;
-  size_t bucket_elems; size_t count; const ScaleTable& scales; T* out; hipStream_t stream;
+  size_t bucket_elems; size_t count; const ScaleTable& scales; T* out; WriteWindow win; hipStream_t stream;
   template <int POL> hipError_t operator()(unsigned blocks) const {
     const size_t tile_elems = static_cast<size_t>(kThreads) * kBucketUnroll * VEC;
     const size_t tiles_per_bucket = (bucket_elems + tile_elems - 1) / tile_elems;
@@ -230,6 +449,14 @@ struct Bucketed {
     const size_t last_len = count - last_begin < bucket_elems ? count - last_begin : bucket_elems;
     const size_t tiles = static_cast<size_t>(n_buckets - 1) * tiles_per_bucket +
                          (last_len + tile_elems - 1) / tile_elems;
+    if constexpr (VEC > 1) {
+      if (win.period_mask != 0) {  // staged results, one workgroup per compute unit
+        const dim3 grid(grid_x_for(tiles, static_cast<unsigned>(device_cu_count()))), block(kThreads);
+        launch(k_reduce_bucketed_win<T, VEC, POL>, grid, block, stream, all, n_replicas, masks, scales, first_elem,
+               bucket_elems, last_len, n_buckets, tiles_per_bucket, tiles, out, win);
+        return hipGetLastError();
+      }
+    }
     const dim3 grid(grid_x_for(tiles, blocks)), block(kThreads);
     launch(k_reduce_bucketed<T, VEC, POL>, grid, block, stream, all, n_replicas, masks, scales,
                                                                first_elem, bucket_elems, last_len,
@@ -244,18 +471,22 @@ hipError_t bucketed_typed(const PtrTable& all, int n_replicas, const BucketTable
                           const ScaleTable& scales, bool vec, void* out, hipStream_t stream) {
   T* o = static_cast<T*>(out);
   const LaunchCfg cfg = bucketed_cfg(n_replicas, count * sizeof(T));
+  // write windows: judged as a reduce over all replica slots of the bytes this launch covers
+  const size_t covered = std::min(count - first_elem, static_cast<size_t>(n_buckets) * bucket_elems);
+  const WriteWindow win = reduce_window(n_replicas, covered * sizeof(T) * (static_cast<size_t>(n_replicas) + 1));
   if (vec)
     return with_policy(cfg, Bucketed<T, VECW>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems, count,
-                                              scales, o, stream});
+                                              scales, o, win, stream});
   return with_policy(cfg, Bucketed<T, 1>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems, count,
-                                         scales, o, stream});
+                                         scales, o, WriteWindow{0u, 0u, 0u}, stream});
 }
 
 }  // namespace
 
 hipError_t launch_reduce_masked(const PtrTable& live, int n_src, size_t count, ftar_dtype_t dtype,
                                 ftar_dtype_t out_dtype, bool vec, void* out, float scale,
-                                bool zero_participants, hipStream_t stream) {
+                                bool zero_participants, size_t whole_count, hipStream_t stream) {
+  if (whole_count < count) whole_count = count;
   if (n_src == 0) {  // nothing to read; bf16 buffers are only 2-byte aligned: head/tail by halves
     if (!zero_participants) return hipErrorInvalidValue;
     const size_t bytes = count * (out_dtype == FTAR_F32 ? 4 : 2);
@@ -281,9 +512,11 @@ hipError_t launch_reduce_masked(const PtrTable& live, int n_src, size_t count, f
   // locality (8 x 2e9 bf16: 5.14 TB/s as one launch, 5.65 TB/s in launches of 128 MiB per stream).
   // Tuning flag 0x40 forces one launch.
   const size_t es_in = dtype == FTAR_F32 ? 4 : 2, es_out = out_dtype == FTAR_F32 ? 4 : 2;
+  const WriteWindow win = reduce_window(n_src, count * (static_cast<size_t>(n_src) * es_in + es_out));
   size_t chunk = (static_cast<size_t>(1) << 30) / (static_cast<size_t>(n_src) * es_in + es_out);
   chunk &= ~static_cast<size_t>(0xffff);  // whole tiles of every shape, 16-byte aligned in both types
-  if ((current_tuning().flags & 0x40) != 0 || count <= chunk + chunk / 2) chunk = count;
+  // (with write windows the workgroups meet at every window: one launch is then best, 6.4 -> 6.6 TB/s)
+  if ((current_tuning().flags & 0x40) != 0 || count <= chunk + chunk / 2 || win.period_mask != 0) chunk = count;
   hipEvent_t t_start = nullptr, t_stop = nullptr;
   if (chunk < count) take_timing_events(&t_start, &t_stop);
   for (size_t first = 0; first < count; first += chunk) {
@@ -295,13 +528,13 @@ hipError_t launch_reduce_masked(const PtrTable& live, int n_src, size_t count, f
       set_timing_events(first == 0 ? t_start : nullptr, first + len >= count ? t_stop : nullptr);
     hipError_t e;
     if (out_dtype != dtype && dtype == FTAR_BF16)
-      e = reduce_masked_cvt<bf16, float>(part, n_src, len, vec, o, scale, zterm, count * es_out, stream);
+      e = reduce_masked_cvt<bf16, float>(part, n_src, len, vec, o, scale, zterm, whole_count * es_out, win, stream);
     else if (out_dtype != dtype)
-      e = reduce_masked_cvt<float, bf16>(part, n_src, len, vec, o, scale, zterm, count * es_out, stream);
+      e = reduce_masked_cvt<float, bf16>(part, n_src, len, vec, o, scale, zterm, whole_count * es_out, win, stream);
     else if (dtype == FTAR_F32)
-      e = reduce_masked_typed<float, 4>(part, n_src, len, vec, o, scale, zterm, count * es_out, stream);
+      e = reduce_masked_typed<float, 4>(part, n_src, len, vec, o, scale, zterm, whole_count * es_out, win, stream);
     else
-      e = reduce_masked_typed<bf16, 8>(part, n_src, len, vec, o, scale, zterm, count * es_out, stream);
+      e = reduce_masked_typed<bf16, 8>(part, n_src, len, vec, o, scale, zterm, whole_count * es_out, win, stream);
     if (e != hipSuccess) return e;
     if (len != chunk) break;
   }

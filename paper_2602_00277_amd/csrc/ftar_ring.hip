@@ -10,22 +10,22 @@ namespace {
 template <typename T, int VEC, int MODE, int U, int POL>
 __global__ void __launch_bounds__(kThreads)
 k_ring_reduce(PtrTable ring, SegTable seg, SegTable tile0, int N, int step, float* acc, float scale,
-              unsigned long long zpos) {
+              unsigned long long zpos, size_t g_begin, size_t g_end) {
   __shared__ T* s_tab[kMaxReplicas];
   __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
   stage_ring_tables<T>(ring, seg, tile0, N, s_tab, s_seg, s_tile);
   ring_reduce_pass<T, VEC, MODE, U, POL>(s_tab, s_seg, s_tile, N, step, acc, scale, blockIdx.x, gridDim.x, 0,
-                                         zpos);
+                                         zpos, g_begin, g_end);
 }
 
 // One AllGather step over all N portions.
 template <typename T, int VEC, int U, int POL>
 __global__ void __launch_bounds__(kThreads)
-k_ring_allgather(PtrTable ring, SegTable seg, SegTable tile0, int N, int step) {
+k_ring_allgather(PtrTable ring, SegTable seg, SegTable tile0, int N, int step, size_t g_begin, size_t g_end) {
   __shared__ T* s_tab[kMaxReplicas];
   __shared__ unsigned long long s_seg[kMaxReplicas + 1], s_tile[kMaxReplicas + 1];
   stage_ring_tables<T>(ring, seg, tile0, N, s_tab, s_seg, s_tile);
-  ring_allgather_pass<T, VEC, U, POL>(s_tab, s_seg, s_tile, N, step, blockIdx.x, gridDim.x);
+  ring_allgather_pass<T, VEC, U, POL>(s_tab, s_seg, s_tile, N, step, blockIdx.x, gridDim.x, 0, g_begin, g_end);
 }
 
 // ---- the ring's result in one pass ------------------------------------------------
@@ -219,17 +219,44 @@ struct RingAllgatherAll {
   }
 };
 
+// A long step goes out as several launches, each over a run of the flat tile sequence of about
+// kRingLaunchBytes of traffic: the workgroups of a launch never wait for each other and drift apart
+// over gigabytes (as in the one-shot reduce); the end of a launch brings them together again.
+// Tuning flag 0x40 forces one launch.  A timed call brackets the whole series.
+constexpr size_t kRingLaunchBytes = static_cast<size_t>(2) << 30;
+
+template <typename F>
+void for_tile_runs(size_t n_tiles, size_t tile_bytes, F f) {
+  size_t per = kRingLaunchBytes / tile_bytes;
+  if (per < 1) per = 1;
+  if ((current_tuning().flags & 0x40) != 0 || n_tiles <= per + per / 2) per = n_tiles;
+  hipEvent_t t_start = nullptr, t_stop = nullptr;
+  if (per < n_tiles) take_timing_events(&t_start, &t_stop);
+  for (size_t g0 = 0; g0 < n_tiles;) {
+    const size_t g1 = n_tiles - g0 < per + per / 2 ? n_tiles : g0 + per;  // no short last launch
+    if (per < n_tiles) set_timing_events(g0 == 0 ? t_start : nullptr, g1 == n_tiles ? t_stop : nullptr);
+    f(g0, g1);
+    g0 = g1;
+  }
+}
+
 template <typename T, int VEC>
 struct RingReduce {
   RingMode mode; const PtrTable& ring; int N; int step; const SegTable& seg; float* acc; float scale;
   unsigned long long zpos; hipStream_t stream;
   template <int MODE, int U, int POL> void go(unsigned blocks) const {
     const SegTable tiles = ring_tiles(seg, N, VEC, U);
-    const dim3 grid(grid_x_for(tiles.begin[N], blocks)), block(kThreads);
-    launch(k_ring_reduce<T, VEC, MODE, U, POL>, grid, block, stream, ring, seg, tiles, N, step, acc, scale, zpos);
+    // bytes one tile moves: the replica stream(s) plus the fp32 partial sums, read and written
+    const size_t E = sizeof(T), elems = static_cast<size_t>(kThreads) * U * VEC;
+    const size_t per_elem = MODE == kRsFirst ? 2 * E + 4 : MODE == kRsMid ? 8 + E : MODE == kRsLast ? 4 + 2 * E : 3 * E;
+    for_tile_runs(tiles.begin[N], elems * per_elem, [&](size_t g0, size_t g1) {
+      const dim3 grid(grid_x_for(g1 - g0, blocks)), block(kThreads);
+      launch(k_ring_reduce<T, VEC, MODE, U, POL>, grid, block, stream, ring, seg, tiles, N, step, acc, scale, zpos,
+             g0, g1);
+    });
   }
   template <int MODE, int POL> void pick_unroll(unsigned blocks) const {
-    const int U = ring_unroll();
+    const int U = ring_unroll(VEC);
     if (U == 2) go<MODE, 2, POL>(blocks);
     else if (U == 8) go<MODE, 8, POL>(blocks);
     else go<MODE, 4, POL>(blocks);
@@ -250,11 +277,14 @@ struct RingAllgather {
   const PtrTable& ring; int N; int step; const SegTable& seg; hipStream_t stream;
   template <int U, int POL> void go(unsigned blocks) const {
     const SegTable tiles = ring_tiles(seg, N, VEC, U);
-    const dim3 grid(grid_x_for(tiles.begin[N], blocks)), block(kThreads);
-    launch(k_ring_allgather<T, VEC, U, POL>, grid, block, stream, ring, seg, tiles, N, step);
+    const size_t elems = static_cast<size_t>(kThreads) * U * VEC;
+    for_tile_runs(tiles.begin[N], elems * 2 * sizeof(T), [&](size_t g0, size_t g1) {
+      const dim3 grid(grid_x_for(g1 - g0, blocks)), block(kThreads);
+      launch(k_ring_allgather<T, VEC, U, POL>, grid, block, stream, ring, seg, tiles, N, step, g0, g1);
+    });
   }
   template <int POL> hipError_t operator()(unsigned blocks) const {
-    const int U = ring_unroll();
+    const int U = ring_unroll(4);
     if (U == 2) go<2, POL>(blocks);
     else if (U == 8) go<8, POL>(blocks);
     else go<4, POL>(blocks);
@@ -299,6 +329,13 @@ hipError_t launch_ring_reduce(RingMode mode, const PtrTable& ring, int n_live, i
     if (vec) return with_policy(cfg, RingReduce<float, 4>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
     return with_policy(cfg, RingReduce<float, 1>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
   }
+  // bf16 lanes take 4 elements: an 8-byte load of the replica stream next to one 16-byte vector of
+  // partial sums, so every instruction of a wave covers one contiguous run of memory.  The other
+  // shape - 8 elements per lane, a 16-byte bf16 load and TWO partial-sum vectors 32 bytes apart per
+  // lane - is kept behind tuning flag 0x200000 for measurement: it is 14 % slower in the middle step
+  // (16 x 256 Mi bf16: 5.34 against 6.19 TB/s) and 15 % in the first.
+  if (vec && (current_tuning().flags & 0x200000) != 0)
+    return with_policy(cfg, RingReduce<bf16, 8>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
   if (vec) return with_policy(cfg, RingReduce<bf16, 4>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
   return with_policy(cfg, RingReduce<bf16, 1>{mode, ring, n_live, step, seg, acc, scale, zpos, stream});
 }

@@ -18,7 +18,8 @@ def B():
 
 
 TUNINGS = [(1, 0x10 | 0), (8, 0x10 | 1), (3, 0x10 | 2), (2, 0x10 | 3), (1, 0x20), (4, 0x10 | 3 | 0x20),
-           (1, 2 << 8), (2, 8 << 8), (16, (8 << 8) | 0x10), (0, 0)]
+           (1, 2 << 8), (2, 8 << 8), (16, (8 << 8) | 0x10), (0, 0x80), (0, 0x100000), (3, 0x100000 | (9 << 12) | (1 << 16)),
+           (0, 0)]
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
@@ -130,3 +131,59 @@ def test_long_reduce_goes_out_in_several_launches_with_the_same_bits_and_one_bra
         assert_same(host(split[lo:lo + 4096]), want, "slab at %d" % lo)
     hip.hipEventDestroy(a)
     hip.hipEventDestroy(b)
+
+
+@pytest.mark.parametrize("n,mask", [(4, 0xF), (6, 0b110111), (8, 0xFF), (16, 0xFFFF), (16, 0xBFFD)])
+def test_write_windows_give_the_same_bits(B, oracle, n, mask):
+    # the staged kernel (results held in LDS, written out in windows of the wall clock) against the plain
+    # one and the oracle: several tiles per workgroup, a ragged tail, every pair of element types
+    from paper_2602_00277_amd import workloads as W  # noqa: F401
+    count = 8 * 256 * 256 * 5 + 8 * 300 + 5
+    for in_dt, out_dt in ((torch.bfloat16, torch.bfloat16), (torch.float32, torch.float32),
+                          (torch.bfloat16, torch.float32), (torch.float32, torch.bfloat16)):
+        bufs = rand_bufs(n, count, in_dt, seed=40 + n, dist="student_t3", mask=mask)
+        hb = [host(b) for b in bufs]
+        want = oracle.reduce_masked_ex(hb, mask, code(in_dt), code(out_dt))
+        outs = []
+        # plain; windows at the default period (here: one flush at the end); short periods with a wide and
+        # a narrow window, so that flushes happen inside windows, on a full stage and at the end
+        for flags in (0x80, 0x100000, 0x100000 | (8 << 12) | (1 << 16), 0x100000 | (10 << 12) | (4 << 16)):
+            say("write windows", n, hex(mask), in_dt, out_dt, hex(flags))
+            B.ftar_set_tuning(0, flags)
+            out = torch.empty(count, dtype=out_dt, device="cuda")
+            B.ftar_reduce_masked_ex(bufs, mask, out)
+            torch.cuda.synchronize()
+            assert_same(host(out), want, "flags %#x" % flags)
+            outs.append(out)
+        for o in outs[1:]:
+            assert torch.equal(o.view(torch.uint8), outs[0].view(torch.uint8))
+    B.ftar_set_tuning(0, 0)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("n", [5, 8, 20])
+def test_write_windows_in_the_bucketed_reduce(B, oracle, dtype, n):
+    # per-bucket masks: whole tiles are staged, bucket ends and buckets with more than 16 live replicas are
+    # written directly; every flush reason (window, full stage, 32 tiles, end) with short periods
+    from paper_2602_00277_amd import workloads as W
+    tile = 256 * 4 * (4 if dtype == torch.float32 else 8)
+    for bucket in (tile * 3 + 8 * 7, tile, tile * 40):
+        count = 256 * tile * 3 + 8 * 11 + 3 if bucket != tile * 40 else tile * 40 * 7 + 5
+        masks = W.bucket_masks(n, (count + bucket - 1) // bucket, 0.85, seed=n + bucket % 97)
+        bufs = rand_bufs(n, count, dtype, seed=50 + n, dist="student_t3")
+        hb = [host(b) for b in bufs]
+        outs = []
+        for flags in (0x80, 0x100000, 0x100000 | (8 << 12) | (1 << 16), 0x100000 | (10 << 12) | (4 << 16)):
+            say("bucketed write windows", dtype, n, bucket, count, hex(flags))
+            B.ftar_set_tuning(0, flags)
+            out = torch.empty(count, dtype=dtype, device="cuda")
+            B.ftar_reduce_masked_bucketed(bufs, masks, bucket, out)
+            torch.cuda.synchronize()
+            outs.append(out)
+        got = host(outs[0])
+        for b, m in enumerate(masks):
+            lo, hi = b * bucket, min(count, (b + 1) * bucket)
+            assert_same(got[lo:hi], oracle.reduce_masked([h[lo:hi].copy() for h in hb], m, code(dtype)), "bucket %d" % b)
+        for o in outs[1:]:
+            assert torch.equal(o.view(torch.uint8), outs[0].view(torch.uint8))
+    B.ftar_set_tuning(0, 0)
