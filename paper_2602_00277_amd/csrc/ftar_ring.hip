@@ -220,14 +220,17 @@ struct RingAllgatherAll {
 };
 
 // A long step goes out as several launches, each over a run of the flat tile sequence of about
-// kRingLaunchBytes of traffic: the workgroups of a launch never wait for each other and drift apart
+// 1 GiB of traffic (half of that for the AllGather copy; 8 x 2e9 bf16: middle step 5.7 -> 6.4 TB/s,
+// AllGather 5.1 -> 5.9): the workgroups of a launch never wait for each other and drift apart
 // over gigabytes (as in the one-shot reduce); the end of a launch brings them together again.
-// Tuning flag 0x40 forces one launch.  A timed call brackets the whole series.
-constexpr size_t kRingLaunchBytes = static_cast<size_t>(2) << 30;
+// Tuning flag 0x40 forces one launch; bits 24..27 = log2 of the MiB per launch, for measurement.
+// A timed call brackets the whole series.
+constexpr size_t kRingLaunchBytes = static_cast<size_t>(1) << 30;
 
 template <typename F>
-void for_tile_runs(size_t n_tiles, size_t tile_bytes, F f) {
-  size_t per = kRingLaunchBytes / tile_bytes;
+void for_tile_runs(size_t n_tiles, size_t tile_bytes, size_t launch_bytes, F f) {
+  const int lg = (current_tuning().flags >> 24) & 0xf;
+  size_t per = (lg ? (static_cast<size_t>(1) << (20 + lg)) : launch_bytes) / tile_bytes;
   if (per < 1) per = 1;
   if ((current_tuning().flags & 0x40) != 0 || n_tiles <= per + per / 2) per = n_tiles;
   hipEvent_t t_start = nullptr, t_stop = nullptr;
@@ -249,7 +252,7 @@ struct RingReduce {
     // bytes one tile moves: the replica stream(s) plus the fp32 partial sums, read and written
     const size_t E = sizeof(T), elems = static_cast<size_t>(kThreads) * U * VEC;
     const size_t per_elem = MODE == kRsFirst ? 2 * E + 4 : MODE == kRsMid ? 8 + E : MODE == kRsLast ? 4 + 2 * E : 3 * E;
-    for_tile_runs(tiles.begin[N], elems * per_elem, [&](size_t g0, size_t g1) {
+    for_tile_runs(tiles.begin[N], elems * per_elem, kRingLaunchBytes, [&](size_t g0, size_t g1) {
       const dim3 grid(grid_x_for(g1 - g0, blocks)), block(kThreads);
       launch(k_ring_reduce<T, VEC, MODE, U, POL>, grid, block, stream, ring, seg, tiles, N, step, acc, scale, zpos,
              g0, g1);
@@ -278,7 +281,7 @@ struct RingAllgather {
   template <int U, int POL> void go(unsigned blocks) const {
     const SegTable tiles = ring_tiles(seg, N, VEC, U);
     const size_t elems = static_cast<size_t>(kThreads) * U * VEC;
-    for_tile_runs(tiles.begin[N], elems * 2 * sizeof(T), [&](size_t g0, size_t g1) {
+    for_tile_runs(tiles.begin[N], elems * 2 * sizeof(T), kRingLaunchBytes / 2, [&](size_t g0, size_t g1) {
       const dim3 grid(grid_x_for(g1 - g0, blocks)), block(kThreads);
       launch(k_ring_allgather<T, VEC, U, POL>, grid, block, stream, ring, seg, tiles, N, step, g0, g1);
     });
