@@ -134,8 +134,8 @@ def all_configs_report(path, B, W, torch, np):
         return ts[len(ts) // 2], ts[0]
 
     def add_row(name, what, gbytes, med, mn, ok, cpu_gbs, cpu_note):
-        verdict = ("bit-exact" if ok else "MISMATCH") if cpu_note != "-" else ("completed" if ok else "MISMATCH")
-        cpu = "-" if cpu_note == "-" else "%.2f (%s)" % (cpu_gbs, cpu_note)
+        verdict = "bit-exact" if ok else "MISMATCH"   # every row is a real comparison with the oracle on slabs
+        cpu = "-" if cpu_note in ("-", "slabs") else "%.2f (%s)" % (cpu_gbs, cpu_note)
         rows.append("| %s | %s | %.3f | %.1f | %.0f | %.1f | %.0f | %s | %s |" % (
             name, what, gbytes, med * 1e6, gbytes / med, 100 * gbytes / med / HBM_PEAK_GBS,
             gbytes / mn, verdict, cpu))
@@ -186,7 +186,8 @@ def all_configs_report(path, B, W, torch, np):
         N = bin(w.live_mask).count("1")
         gb = (N + 1) * w.elem_bytes * w.count / 1e9
         med, mn = time_schedule(lambda: B.ftar_reduce_masked(bufs, w.live_mask, out), 20)
-        add_row(w.name, "ftar_reduce_masked, N=%d" % N, gb, med, mn, ok,
+        add_row(w.name, "ftar_reduce_masked, N=%d%s" % (N, " (20 MiB in all, cache-resident: NOT an HBM fraction)" if idx == 0 else ""),
+                gb, med, mn, ok,
                 (N + 1) * w.elem_bytes * cpu_elems / cpu_s / 1e9, "%d elems" % cpu_elems)
         if idx == 1:
             # the same buffers through the delivery variants of the one-shot reduce
@@ -264,10 +265,48 @@ def all_configs_report(path, B, W, torch, np):
                 "closed form, %d elems, (N+1)E bytes/elem" % cpu_elems)
         for plan, _ in plans:
             B.ftar_plan_destroy(plan)
-        del orig
+        if len(schedule) != 1:
+            del orig
         if len(schedule) == 1:
-            # the same ring as ONE CPU-gated persistent kernel (values differ from the first run,
-            # timing does not depend on them); parity of this path is covered by the GPU tests
+            # the other ways to the same result, each checked on fresh inputs against the oracle's closed
+            # form on slabs (the buffers are restored from the saved slabs' source: a pristine copy), then timed
+            PART = 4 * W.M
+            pristine = W.draw_replicas(w, dev)
+            pstarts = [st for st in starts if st // PART == (st + SLAB - 1) // PART]
+            ring_pos = oracle.live_ring(w.n_replicas, final_mask)
+
+            def restore():
+                for d, src in zip(bufs, pristine):
+                    d.copy_(src)
+
+            def check(part=0, owner_only=False):
+                """The buffers against the closed form on the slabs; part: partition size (a partition is a
+                ring of its own); owner_only: the state after the ReduceScatter phase."""
+                torch.cuda.synchronize()
+                good = True
+                Nl = len(ring_pos)
+                for st in (pstarts if part else starts):
+                    if part:
+                        p0 = (st // part) * part
+                        L = min(part, w.count - p0)
+                        want = oracle.ring_closed_form(orig[st], final_mask, L, w.chunk_elems, code(w.dtype),
+                                                       begin=st - p0, length=SLAB)
+                    else:
+                        want = oracle.ring_closed_form(orig[st], final_mask, w.count, w.chunk_elems, code(w.dtype),
+                                                       begin=st, length=SLAB)
+                        sb = oracle.geometry(w.n_replicas, final_mask, w.count, w.chunk_elems)
+                    for r in range(w.n_replicas):
+                        got = W.to_numpy_bits(bufs[r][st:st + SLAB])
+                        exp = want
+                        if owner_only:
+                            exp = orig[st][r].copy()
+                            for k in range(Nl):
+                                if ring_pos[(k + Nl - 1) % Nl] == r:
+                                    lo, hi = max(st, sb[k]), min(st + SLAB, sb[k + 1])
+                                    if lo < hi:
+                                        exp[lo - st:hi - st] = want[lo - st:hi - st]
+                        good = good and same(got, exp)
+                return good
             plan = B.ftar_plan(w.n_replicas, final_mask, w.count, w.chunk_elems, w.dtype)
             ctrl = B.ftar_ctrl_create()
             n_steps = 2 * plan.n_live - 2
@@ -284,9 +323,12 @@ def all_configs_report(path, B, W, torch, np):
             for label2, fn in (("persistent kernel, all steps released at once", lambda: persistent()),
                                ("persistent kernel, PUBLISH|ALIGN, CPU releases step by step",
                                 lambda: persistent(flags=3, gate=True))):
+                restore()
+                fn()
+                good = check()
                 med, mn = time_schedule(fn, 5)
                 st, done = ctrl.result()
-                add_row(w.name, "3a " + label2, gb, med, mn, st == 0 and done == n_steps, float("nan"), "-")
+                add_row(w.name, "3a " + label2, gb, med, mn, good and st == 0 and done == n_steps, float("nan"), "slabs")
             for nb in (2, 4, 8, 16, 32, 64, 128):
                 med, mn = time_schedule(lambda: persistent(nb=nb), 1 if nb < 16 else 3)
                 curve.append((nb, gb / med))
@@ -328,12 +370,18 @@ def all_configs_report(path, B, W, torch, np):
                 share.append("| %s | %.3f | %s |" % (name, alone * 1e3, " | ".join(cells)))
             del g1, o1, g2, o2, ew
             # partitions of 4 Mi elements: acc (16 MiB) and the partition's slices stay in the caches
-            plan.set_partition(4 * W.M)
+            plan.set_partition(PART)
             n_steps = plan.n_slots
+            part_acc = acc[:PART]
+            restore()
+            B.ftar_ring_persistent(plan, bufs, part_acc, ctrl, timeout_us=10_000_000)
+            ctrl.release(n_steps)
+            good = check(part=PART)
             med, mn = time_schedule(lambda: persistent(), 5)
             st, done = ctrl.result()
-            add_row(w.name, "3a persistent kernel, partitions of 4 Mi elements (%d slots)" % n_steps, gb, med, mn,
-                    st == 0 and done == n_steps, float("nan"), "-")
+            add_row(w.name, "3a persistent kernel, partitions of 4 Mi elements (%d slots; the partial sums of a "
+                    "partition stay in the caches: NOT an HBM fraction)" % n_steps, gb, med, mn,
+                    good and st == 0 and done == n_steps, float("nan"), "slabs")
             plan.set_partition(0)
             # the ReduceScatter steps as they are, the AllGather phase in one pass
             Np = plan.n_live
@@ -343,30 +391,43 @@ def all_configs_report(path, B, W, torch, np):
                     B.ftar_reduce_step(plan, st_, bufs, acc)
                 B.ftar_allgather_all(plan, bufs)
             own_gb = ((2 * E + 4) + (Np - 3) * (8 + E) + (4 + 2 * E) + Np * E) * w.count / 1e9
+            restore()
+            rs_then_gather_all()
+            good = check()
             med, mn = time_schedule(rs_then_gather_all, 5)
             add_row(w.name, "3a 15 RS steps + ftar_allgather_all (own bytes: E + (N-1)E for the gather)", own_gb, med, mn,
-                    True, float("nan"), "-")
+                    good, float("nan"), "slabs")
             # the ReduceScatter phase in one pass (the reduce-scatter of a sharded optimizer), alone and
             # completed by the one-pass gather
             own_gb = (Np * E + E) * w.count / 1e9
+            restore()
+            B.ftar_reduce_scatter_all(plan, bufs)
+            good = check(owner_only=True)
             med, mn = time_schedule(lambda: B.ftar_reduce_scatter_all(plan, bufs), 5)
-            add_row(w.name, "3a ftar_reduce_scatter_all (own bytes: NE + E per element)", own_gb, med, mn, True,
-                    float("nan"), "-")
+            add_row(w.name, "3a ftar_reduce_scatter_all (own bytes: NE + E per element)", own_gb, med, mn, good,
+                    float("nan"), "slabs")
 
             def scatter_gather():
                 B.ftar_reduce_scatter_all(plan, bufs)
                 B.ftar_allgather_all(plan, bufs)
             own_gb = ((Np * E + E) + Np * E) * w.count / 1e9
+            restore()
+            scatter_gather()
+            good = check()
             med, mn = time_schedule(scatter_gather, 5)
             add_row(w.name, "3a ftar_reduce_scatter_all + ftar_allgather_all (own bytes: (2N+1)E)", own_gb, med, mn,
-                    True, float("nan"), "-")
+                    good, float("nan"), "slabs")
             # the same result in one pass: its own algorithmic bytes are 2*N*E per element
             own_gb = 2 * plan.n_live * E * w.count / 1e9
+            restore()
+            B.ftar_allreduce_onepass(plan, bufs)
+            good = check()
             med, mn = time_schedule(lambda: B.ftar_allreduce_onepass(plan, bufs), 5)
-            add_row(w.name, "3a ftar_allreduce_onepass (own bytes: 2NE per element)", own_gb, med, mn, True,
-                    float("nan"), "-")
+            add_row(w.name, "3a ftar_allreduce_onepass (own bytes: 2NE per element)", own_gb, med, mn, good,
+                    float("nan"), "slabs")
             ctrl.destroy()
             B.ftar_plan_destroy(plan)
+            del pristine, orig
         del bufs, acc
         torch.cuda.empty_cache()
     # ---- cfg 5: per-bucket live masks ---------------------------------------------------

@@ -68,6 +68,7 @@ typedef enum {
   FTAR_ERR_TOO_LARGE = 5,   /* ftar_ring_persistent_static: more partial sums than the static scratch holds */
   /* retryable: re-plan over the new group and restart the schedule */
   FTAR_ERR_STALE_PLAN = 16, /* the persistent ring was cancelled or timed out before finishing */
+  FTAR_ERR_SKIPPED = 17,    /* a queued persistent ring never started: a call before it was cancelled or timed out */
   /* fatal: the HIP runtime reported a failure */
   FTAR_ERR_DEVICE = 32
 } ftar_status_t;
@@ -288,18 +289,41 @@ ftar_status_t ftar_allreduce_onepass(const ftar_plan_t* plan, void* const* bufs,
  *
  * The kernel runs the 2N-2 steps of the plan in order (ReduceScatter 0..N-2, then AllGather
  * N-1..2N-3), partition after partition if the plan is partitioned, with the arithmetic of
- * ftar_reduce_step / ftar_allgather_step.  Before slot s (one step of one partition) every
- * workgroup waits until the CPU has released it (ftar_ctrl_release(ctrl, r) with r > s);
- * after slot s it publishes its progress.  A wait ends without the release when the CPU
+ * ftar_reduce_step / ftar_allgather_step.  Before gate unit u (by default one step of one
+ * partition) every workgroup waits until the CPU has released it (ftar_ctrl_release(ctrl, r) with
+ * r > u); after it, it publishes its progress.  A wait ends without the release when the CPU
  * cancels (ftar_ctrl_cancel) or when timeout_us microseconds have passed: the workgroup then
  * records why and exits, so the kernel always terminates.  No user buffer is written before
  * the last ReduceScatter step (s = N-2) is released: a cancel or timeout before that leaves every
  * bufs[r] untouched and the caller re-plans and restarts.
  *
  * ctrl is a control block made by ftar_ctrl_create(): coherent host-pinned memory plus a mirror
- * of 4 KiB in device memory (both allocated at set-up, not on the hot path).  One control block
- * serves one call at a time; ftar_ring_persistent re-arms it (released = 0, no cancel) before
- * launching.  With a partitioned plan whose last partition is shorter, the workgroups also wait
+ * of 4 KiB in device memory (both allocated at set-up, not on the hot path).
+ *
+ * Gate units.  What the CPU releases, and what progress counts, is the gate unit.  By default a unit
+ * is a slot (one step of one partition): ftar_plan_n_slots units per call.  With
+ * FTAR_PERSIST_CHUNKS a unit is one ROW OF CHUNKS of a slot - chunk c of every portion, i.e. the
+ * c-th chunk of every rank's work in that step (section 4.2: every step of a partition is pipelined
+ * over the chunks of a portion, chunk_elems of ftar_plan being the chunk).  Units are ordered
+ * partition, step, row; releasing n lets units [0, n) run; ftar_plan_n_gate_units tells how many a
+ * call has (rows per step = the largest number of chunks a portion of that partition has).  A
+ * workgroup looks at the gate whenever its next tile lies in a later row and reports when it moves
+ * on to one.  Results never depend on the unit.  A tile never crosses a chunk's end: chunk_elems
+ * should be a multiple of 8192 elements (fp32: 4096) for full speed.
+ *
+ * Several calls on one control block.  Calls may be queued one behind the other on ONE stream
+ * against one control block (section 4.1: one all-reduce per gradient bucket, overlapped with the
+ * backward pass); at most 64 may be in flight.  Every call gets a ticket (ftar_ctrl_last_ticket,
+ * right after the call, from the enqueueing thread) and is released, observed and judged by it
+ * (ftar_ctrl_*_call); the forms without a ticket mean the call enqueued last.  ftar_ctrl_cancel
+ * ends EVERY call enqueued so far at its next wait and lets calls enqueued afterwards run; a
+ * timeout inside one call does the same to the calls queued behind it (section 4.2: queued
+ * operations are cancelled and marked skipped).  ftar_ctrl_result_call then tells them apart:
+ * FTAR_OK (finished before), FTAR_ERR_STALE_PLAN (the call that was stopped: units_done units are
+ * complete), FTAR_ERR_SKIPPED (queued behind it: it left at its first wait, nothing was read or
+ * written).  After a timeout the caller acknowledges with ftar_ctrl_cancel before re-planning:
+ * until then newly enqueued calls count as "queued behind" and are skipped too.
+ * With a partitioned plan whose last partition is shorter, the workgroups also wait
  * for each other once (bounded by timeout_us like every wait), before that partition's first slot.
  * Every workgroup must be resident at once: on a stream that is restricted to some of the
  * compute units the caller chooses n_blocks to fit them.
@@ -308,7 +332,7 @@ ftar_status_t ftar_allreduce_onepass(const ftar_plan_t* plan, void* const* bufs,
  *               clamped to what the GPU can keep resident at once (a waiting workgroup keeps
  *               its place, so all of them must fit)
  *   timeout_us  per-wait limit in microseconds (> 0)
- *   flags       FTAR_PERSIST_PUBLISH: a step counts as done (ftar_ctrl_progress) only after its
+ *   flags       FTAR_PERSIST_PUBLISH: a unit counts as done (ftar_ctrl_progress) only after its
  *               data has been written back from the GPU's L2, as a NIC reading the buffers on
  *               the CPU's signal would need; without it progress means "computed", and the data
  *               is guaranteed visible off the GPU once the stream has been synchronised.
@@ -316,16 +340,20 @@ ftar_status_t ftar_allreduce_onepass(const ftar_plan_t* plan, void* const* bufs,
  *               every step; a performance hint for long steps, never needed for correctness.
  *               The library sets it by itself when the partial sums of one partition exceed
  *               256 MiB (steps of hundreds of microseconds: +5..9 %; below that it costs).
- * Returns at once like every other compute call.  After the stream has been synchronised,
- * ftar_ctrl_result tells how it ended: FTAR_OK (all steps done), or FTAR_ERR_STALE_PLAN
- * (retryable: cancelled or timed out); *steps_done = steps completed by every workgroup.
+ *               FTAR_PERSIST_CHUNKS: the gate unit is a row of chunks (above).
+ * Returns at once like every other compute call; on an error nothing was enqueued and the control
+ * block is unchanged (FTAR_ERR_INVALID_ARG also when 64 earlier calls on it are still in flight).
+ * After the stream has been synchronised, ftar_ctrl_result tells how it ended; *units_done = units
+ * completed by every workgroup.
  */
 #define FTAR_PERSIST_PUBLISH 1u
 #define FTAR_PERSIST_ALIGN 2u
+#define FTAR_PERSIST_CHUNKS 4u
 void* ftar_ctrl_create(void);   /* NULL on failure */
-void ftar_ctrl_destroy(void* ctrl);
+void ftar_ctrl_destroy(void* ctrl); /* only when no call on it is in flight */
 ftar_status_t ftar_ring_persistent(const ftar_plan_t* plan, void* const* bufs, float* acc, void* ctrl,
                                    int n_blocks, unsigned timeout_us, unsigned flags, void* stream);
+int ftar_plan_n_gate_units(const ftar_plan_t* plan, unsigned flags); /* 0: plan or flags not usable */
 /* ---------------------------------------------------------------------------
  * ftar_ring_persistent_static - ftar_ring_persistent for callers that cannot allocate device memory
  * and have none to spare for a workspace: code under HIP graph capture, tight serving loops,
@@ -348,14 +376,19 @@ ftar_status_t ftar_ring_persistent(const ftar_plan_t* plan, void* const* bufs, f
 #define FTAR_STATIC_ACC_ELEMS ((size_t)4 << 20)
 ftar_status_t ftar_ring_persistent_static(const ftar_plan_t* plan, void* const* bufs, void* ctrl,
                                           int n_blocks, unsigned timeout_us, unsigned flags, void* stream);
-/* CPU side of the handshake (plain host stores/loads on the control block; callable from any
- * thread while the kernel runs). */
-void ftar_ctrl_release(void* ctrl, int n_steps); /* steps [0, n_steps) may run */
-void ftar_ctrl_cancel(void* ctrl);               /* stop at the next wait */
-int ftar_ctrl_progress(const void* ctrl);        /* slots completed by EVERY workgroup: a lower bound
+/* CPU side of the handshake (atomic host stores/loads on the control block; release, cancel, progress
+ * and result are callable from any thread while kernels run; enqueueing calls on one control block
+ * and ftar_ctrl_last_ticket belong to one thread at a time). */
+int ftar_ctrl_last_ticket(const void* ctrl);                        /* ticket of the call enqueued last; -1: none */
+void ftar_ctrl_release_call(void* ctrl, int ticket, int n_units);   /* units [0, n_units) of that call may run */
+void ftar_ctrl_release(void* ctrl, int n_units);                    /* the same for the call enqueued last */
+void ftar_ctrl_cancel(void* ctrl);               /* every call enqueued so far stops at its next wait */
+int ftar_ctrl_progress_call(const void* ctrl, int ticket);
+int ftar_ctrl_progress(const void* ctrl);        /* units completed by EVERY workgroup: a lower bound
                                                     while the kernel runs ahead of it, exact
                                                     whenever the kernel waits for a release */
-ftar_status_t ftar_ctrl_result(const void* ctrl, int* steps_done);
+ftar_status_t ftar_ctrl_result_call(const void* ctrl, int ticket, int* units_done);
+ftar_status_t ftar_ctrl_result(const void* ctrl, int* units_done);
 
 /* --------------------------------------------------------------------------- */
 ftar_status_t ftar_last_error(void);          /* status of this thread's last failing call */

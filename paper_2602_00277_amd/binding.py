@@ -26,6 +26,7 @@ FTAR_ERR_BAD_MASK = 3
 FTAR_ERR_BAD_STEP = 4
 FTAR_ERR_TOO_LARGE = 5
 FTAR_ERR_STALE_PLAN = 16
+FTAR_ERR_SKIPPED = 17
 FTAR_ERR_DEVICE = 32
 
 FTAR_MEAN = 0
@@ -33,6 +34,7 @@ FTAR_SUM = 1
 
 FTAR_PERSIST_PUBLISH = 1
 FTAR_PERSIST_ALIGN = 2
+FTAR_PERSIST_CHUNKS = 4
 
 # every symbol include/ftar.h declares
 EXPORTS = [
@@ -47,7 +49,8 @@ EXPORTS = [
     "ftar_plan_partition_segment", "ftar_allreduce_onepass", "ftar_plan_set_zero_mask",
     "ftar_reduce_masked_zero", "ftar_plan_set_op", "ftar_reduce_masked_ex", "ftar_plan_lr_factors",
     "ftar_allgather_all", "ftar_reduce_scatter_all",
-    "ftar_ring_persistent_static",
+    "ftar_ring_persistent_static", "ftar_plan_n_gate_units", "ftar_ctrl_last_ticket",
+    "ftar_ctrl_release_call", "ftar_ctrl_progress_call", "ftar_ctrl_result_call",
 ]
 
 # every symbol include/ftar_measure.h declares: measurement hooks in libftar.so, probe kernels in
@@ -145,6 +148,16 @@ def lib():
     L.ftar_ring_persistent.argtypes = [vp, vp, vp, vp, ci, ctypes.c_uint, ctypes.c_uint, vp]
     L.ftar_ring_persistent_static.restype = ci
     L.ftar_ring_persistent_static.argtypes = [vp, vp, vp, ci, ctypes.c_uint, ctypes.c_uint, vp]
+    L.ftar_plan_n_gate_units.restype = ci
+    L.ftar_plan_n_gate_units.argtypes = [vp, ctypes.c_uint]
+    L.ftar_ctrl_last_ticket.restype = ci
+    L.ftar_ctrl_last_ticket.argtypes = [vp]
+    L.ftar_ctrl_release_call.restype = None
+    L.ftar_ctrl_release_call.argtypes = [vp, ci, ci]
+    L.ftar_ctrl_progress_call.restype = ci
+    L.ftar_ctrl_progress_call.argtypes = [vp, ci]
+    L.ftar_ctrl_result_call.restype = ci
+    L.ftar_ctrl_result_call.argtypes = [vp, ci, ctypes.POINTER(ci)]
     L.ftar_ctrl_release.restype = None
     L.ftar_ctrl_release.argtypes = [vp, ci]
     L.ftar_ctrl_cancel.restype = None
@@ -248,6 +261,9 @@ class Plan:
     @property
     def n_slots(self) -> int:
         return lib().ftar_plan_n_slots(self.handle)
+
+    def n_gate_units(self, flags: int = 0) -> int:
+        return lib().ftar_plan_n_gate_units(self.handle, flags)
 
     def set_partition(self, partition_elems: int) -> None:
         st = lib().ftar_plan_set_partition(self.handle, partition_elems)
@@ -475,19 +491,31 @@ class Ctrl:
         if not self.handle:
             raise FtarError(lib().ftar_last_error(), "ftar_ctrl_create")
 
-    def release(self, n_steps: int) -> None:
-        lib().ftar_ctrl_release(self.handle, n_steps)
+    def last_ticket(self) -> int:
+        """Ticket of the call enqueued last on this control block (-1: none)."""
+        return lib().ftar_ctrl_last_ticket(self.handle)
+
+    def release(self, n_units: int, ticket: Optional[int] = None) -> None:
+        if ticket is None:
+            lib().ftar_ctrl_release(self.handle, n_units)
+        else:
+            lib().ftar_ctrl_release_call(self.handle, ticket, n_units)
 
     def cancel(self) -> None:
         lib().ftar_ctrl_cancel(self.handle)
 
-    def progress(self) -> int:
-        return lib().ftar_ctrl_progress(self.handle)
+    def progress(self, ticket: Optional[int] = None) -> int:
+        if ticket is None:
+            return lib().ftar_ctrl_progress(self.handle)
+        return lib().ftar_ctrl_progress_call(self.handle, ticket)
 
-    def result(self):
-        """(status, steps_done); call after the stream has been synchronised."""
+    def result(self, ticket: Optional[int] = None):
+        """(status, units_done); call after the stream has been synchronised."""
         done = ctypes.c_int()
-        st = lib().ftar_ctrl_result(self.handle, ctypes.byref(done))
+        if ticket is None:
+            st = lib().ftar_ctrl_result(self.handle, ctypes.byref(done))
+        else:
+            st = lib().ftar_ctrl_result_call(self.handle, ticket, ctypes.byref(done))
         return st, done.value
 
     def destroy(self) -> None:
@@ -510,8 +538,28 @@ def ftar_ctrl_destroy(ctrl: Ctrl) -> None:
     ctrl.destroy()
 
 
-def ftar_ctrl_release(ctrl: Ctrl, n_steps: int) -> None:
-    ctrl.release(n_steps)
+def ftar_ctrl_release(ctrl: Ctrl, n_units: int) -> None:
+    ctrl.release(n_units)
+
+
+def ftar_ctrl_last_ticket(ctrl: Ctrl) -> int:
+    return ctrl.last_ticket()
+
+
+def ftar_ctrl_release_call(ctrl: Ctrl, ticket: int, n_units: int) -> None:
+    ctrl.release(n_units, ticket)
+
+
+def ftar_ctrl_progress_call(ctrl: Ctrl, ticket: int) -> int:
+    return ctrl.progress(ticket)
+
+
+def ftar_ctrl_result_call(ctrl: Ctrl, ticket: int):
+    return ctrl.result(ticket)
+
+
+def ftar_plan_n_gate_units(plan: Plan, flags: int = 0) -> int:
+    return plan.n_gate_units(flags)
 
 
 def ftar_ctrl_cancel(ctrl: Ctrl) -> None:

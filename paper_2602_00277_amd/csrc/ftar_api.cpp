@@ -18,6 +18,7 @@ namespace ftar {
 namespace {
 
 constexpr uint32_t kPlanMagic = 0x46544152u;  // "FTAR"
+constexpr unsigned long long kRecLaunchFailed = 255;  // CallRec::status of a call whose launch failed (host only)
 
 thread_local ftar_status_t t_last_error = FTAR_OK;
 
@@ -496,13 +497,16 @@ void* ftar_ctrl_create(void) {
     return nullptr;
   }
   std::memset(p, 0, sizeof(Ctrl));
+  Ctrl* c = static_cast<Ctrl*>(p);
+  c->cur_epoch = 1;
+  for (int i = 0; i < kCtrlCalls; ++i) c->call[i].ticket = -1;
   void* mirror = nullptr;
   if (hipMalloc(&mirror, sizeof(DevCtrl)) != hipSuccess || !mirror) {
     (void)hipHostFree(p);
     fail(FTAR_ERR_DEVICE);
     return nullptr;
   }
-  static_cast<Ctrl*>(p)->dev = static_cast<DevCtrl*>(mirror);
+  c->dev = static_cast<DevCtrl*>(mirror);
   // set-up is also where the static scratch of ftar_ring_persistent_static is located on this
   // device (that entry point looks it up itself if no control block was ever made here)
   DevCtrl* sm = nullptr;
@@ -517,13 +521,59 @@ void ftar_ctrl_destroy(void* ctrl) {
   (void)hipHostFree(ctrl);
 }
 
+// Rows of chunks per step for one partition shape (the gate units of a step with
+// FTAR_PERSIST_CHUNKS): the largest number of chunks any portion has.  *ok = false if the shape
+// is not what the kernel's row tables assume (all rows but the last two hold N full chunks).
+static unsigned chunk_rows(const SegTable& seg, int N, size_t chunk, bool* ok) {
+  unsigned long long c_min = ~0ull, c_max = 0;
+  for (int k = 0; k < N; ++k) {
+    const unsigned long long len = seg.begin[k + 1] - seg.begin[k];
+    const unsigned long long c = (len + chunk - 1) / chunk;
+    c_min = c < c_min ? c : c_min;
+    c_max = c > c_max ? c : c_max;
+    // every chunk of a portion but its last must be whole
+    if (len > 0 && seg.begin[k] % chunk != 0 && k > 0) *ok = false;
+  }
+  const unsigned long long uni = c_min > 0 ? c_min - 1 : 0;
+  if (c_max - uni > 2 || c_max > 0x7fffffffull) *ok = false;
+  return static_cast<unsigned>(c_max);
+}
+
+// Gate units of a call: slots, or rows of chunks summed over all slots.
+static bool gate_units(const ftar_plan_t* plan, unsigned flags, unsigned* rows_full, unsigned* rows_last,
+                       unsigned long long* units) {
+  const unsigned long long steps = static_cast<unsigned long long>(2 * plan->n_live - 2);
+  if ((flags & FTAR_PERSIST_CHUNKS) == 0) {
+    *rows_full = *rows_last = 1;
+    *units = plan->n_parts * steps;
+    return true;
+  }
+  bool ok = true;
+  *rows_full = chunk_rows(plan->part_seg_full, plan->n_live, plan->chunk_elems, &ok);
+  *rows_last = chunk_rows(plan->part_seg_last, plan->n_live, plan->chunk_elems, &ok);
+  *units = steps * ((plan->n_parts - 1) * static_cast<unsigned long long>(*rows_full) + *rows_last);
+  return ok && *units <= 0x7fffffffull;
+}
+
+int ftar_plan_n_gate_units(const ftar_plan_t* plan, unsigned flags) {
+  if (!plan_ok(plan)) return 0;
+  unsigned rf = 0, rl = 0;
+  unsigned long long units = 0;
+  if (!gate_units(plan, flags, &rf, &rl, &units)) return 0;
+  return static_cast<int>(units);
+}
+
+static bool call_over(const CallRec& r) {
+  return r.ticket < 0 || r.n_blocks == 0 || __atomic_load_n(&r.ended, __ATOMIC_ACQUIRE) != 0;
+}
+
 // own_scratch: the partial sums and the mirror of the control block live in the library's static
 // device array instead of caller-provided / set-up-allocated memory (acc is then ignored).
 static ftar_status_t ring_persistent_common(const ftar_plan_t* plan, void* const* bufs, float* acc, void* ctrl,
                                             int n_blocks, unsigned timeout_us, unsigned flags, bool own_scratch,
                                             void* stream) {
-  if (!plan_ok(plan) || !bufs || !ctrl || timeout_us == 0 || n_blocks < 0 ||
-      n_blocks > kMaxPersistentBlocks || (flags & ~(FTAR_PERSIST_PUBLISH | FTAR_PERSIST_ALIGN)) != 0)
+  if (!plan_ok(plan) || !bufs || !ctrl || timeout_us == 0 || n_blocks < 0 || n_blocks > kMaxPersistentBlocks ||
+      (flags & ~(FTAR_PERSIST_PUBLISH | FTAR_PERSIST_ALIGN | FTAR_PERSIST_CHUNKS)) != 0)
     return fail(FTAR_ERR_INVALID_ARG);
   const int N = plan->n_live;
   Ctrl* c = static_cast<Ctrl*>(ctrl);
@@ -544,34 +594,52 @@ static ftar_status_t ring_persistent_common(const ftar_plan_t* plan, void* const
     if (!acc || !aligned(acc, 4)) return fail(FTAR_ERR_INVALID_ARG);
     if (!aligned(acc, 16)) vec = false;
   }
+  PartGeom geom;
+  unsigned long long units = 0;
+  if (!gate_units(plan, flags, &geom.rows_full, &geom.rows_last, &units)) return fail(FTAR_ERR_INVALID_ARG);
   // default: one worker per compute unit; two when the slots are short (partitioned)
   unsigned blocks = n_blocks > 0 ? static_cast<unsigned>(n_blocks)
                                  : static_cast<unsigned>(device_cu_count()) * (plan->n_parts > 1 ? 2u : 1u);
   if (blocks > static_cast<unsigned>(kMaxPersistentBlocks)) blocks = kMaxPersistentBlocks;
-  // re-arm the control block; the launch below orders these stores before the kernel's loads
-  c->gate = 0;
-  c->status = 0;
-  c->blocked_step = 0;
-  c->progress = 0;
-  c->n_blocks = N >= 2 ? blocks : 0;
-  c->n_steps = static_cast<unsigned>(plan->n_parts) * static_cast<unsigned>(2 * N - 2);
+  void* dev = nullptr;
+  if (N >= 2 && (hipHostGetDevicePointer(&dev, ctrl, 0) != hipSuccess || !dev)) return fail(FTAR_ERR_INVALID_ARG);
+  // the call's record: free only if the call that used it last is over (at most kCtrlCalls in flight)
+  const long long ticket = c->next_ticket;
+  CallRec* rec = &c->call[ticket % kCtrlCalls];
+  if (!call_over(*rec)) return fail(FTAR_ERR_INVALID_ARG);
+  // everything has been checked: from here on the control block changes
+  rec->gate = 0;
+  rec->status = 0;
+  rec->blocked_unit = 0;
+  rec->progress = 0;
+  rec->ended = 0;
+  rec->epoch = c->cur_epoch;
+  rec->n_blocks = N >= 2 ? blocks : 0;
+  rec->n_units = N >= 2 ? static_cast<unsigned>(units) : 0;
+  rec->ticket = ticket;
+  c->next_ticket = ticket + 1;
   std::atomic_thread_fence(std::memory_order_seq_cst);
   if (N < 2) return FTAR_OK;  // a ring of one has no steps: nothing to launch
-  void* dev = nullptr;
-  if (hipHostGetDevicePointer(&dev, ctrl, 0) != hipSuccess || !dev) return fail(FTAR_ERR_INVALID_ARG);
-  PartGeom geom;
   geom.n_parts = static_cast<unsigned>(plan->n_parts);
   geom.part_elems = plan->part_elems;
   geom.seg_full = plan->part_seg_full;
   geom.seg_last = plan->part_seg_last;
+  geom.chunk_elems = (flags & FTAR_PERSIST_CHUNKS) ? plan->chunk_elems : 0;
   // long slots: keep the workers in step (measured: pays from 128 Mi elements per partition on)
   if ((plan->part_elems ? plan->part_elems : plan->count) * 4 > (static_cast<size_t>(256) << 20))
     flags |= FTAR_PERSIST_ALIGN;
-  hipError_t e = launch_ring_persistent(tab, N, geom, plan->dtype, vec, acc, plan->scale,
-                                        static_cast<Ctrl*>(dev), mirror, blocks,
+  Ctrl* ctrl_dev = static_cast<Ctrl*>(dev);
+  CallRec* rec_dev = &ctrl_dev->call[ticket % kCtrlCalls];
+  hipError_t e = launch_ring_persistent(tab, N, geom, plan->dtype, vec, acc, plan->scale, ctrl_dev, rec_dev,
+                                        rec->epoch, mirror, blocks,
                                         static_cast<unsigned long long>(timeout_us) * 100ull, flags,
                                         plan->zero_pos, static_cast<hipStream_t>(stream));
-  return e == hipSuccess ? FTAR_OK : fail(FTAR_ERR_DEVICE);
+  if (e != hipSuccess) {
+    rec->n_blocks = 0;  // nothing runs: the record reads as a call that is over, with nothing done
+    rec->status = kRecLaunchFailed;
+    return fail(FTAR_ERR_DEVICE);
+  }
+  return FTAR_OK;
 }
 
 ftar_status_t ftar_ring_persistent(const ftar_plan_t* plan, void* const* bufs, float* acc, void* ctrl,
@@ -584,39 +652,69 @@ ftar_status_t ftar_ring_persistent_static(const ftar_plan_t* plan, void* const* 
   return ring_persistent_common(plan, bufs, nullptr, ctrl, n_blocks, timeout_us, flags, true, stream);
 }
 
-void ftar_ctrl_release(void* ctrl, int n_steps) {
-  if (!ctrl || n_steps < 0) return;
-  Ctrl* c = static_cast<Ctrl*>(ctrl);
-  const unsigned long long keep = __atomic_load_n(&c->gate, __ATOMIC_RELAXED) & kGateCancel;
-  __atomic_store_n(&c->gate, keep | static_cast<unsigned long long>(n_steps), __ATOMIC_RELEASE);
+int ftar_ctrl_last_ticket(const void* ctrl) {
+  if (!ctrl) return -1;
+  return static_cast<int>(static_cast<const Ctrl*>(ctrl)->next_ticket - 1);
 }
+
+// The record of a ticket, or null if the ticket was never issued or its record has been reused.
+static CallRec* record_of(void* ctrl, int ticket) {
+  if (!ctrl || ticket < 0) return nullptr;
+  Ctrl* c = static_cast<Ctrl*>(ctrl);
+  CallRec* r = &c->call[ticket % kCtrlCalls];
+  return r->ticket == ticket ? r : nullptr;
+}
+
+void ftar_ctrl_release_call(void* ctrl, int ticket, int n_units) {
+  CallRec* r = record_of(ctrl, ticket);
+  if (!r || n_units < 0) return;
+  // one plain store: the cancel lives in a word of its own, so a release can never undo it
+  __atomic_store_n(&r->gate, static_cast<unsigned long long>(n_units), __ATOMIC_RELEASE);
+}
+
+void ftar_ctrl_release(void* ctrl, int n_units) { ftar_ctrl_release_call(ctrl, ftar_ctrl_last_ticket(ctrl), n_units); }
 
 void ftar_ctrl_cancel(void* ctrl) {
   if (!ctrl) return;
-  __atomic_fetch_or(&static_cast<Ctrl*>(ctrl)->gate, kGateCancel, __ATOMIC_RELEASE);
+  Ctrl* c = static_cast<Ctrl*>(ctrl);
+  // everything enqueued so far belongs to epochs <= cur_epoch: kill them, open the next epoch
+  const unsigned long long e = __atomic_fetch_add(&c->cur_epoch, 1ull, __ATOMIC_ACQ_REL);
+  unsigned long long seen = __atomic_load_n(&c->dead_epoch, __ATOMIC_RELAXED);
+  while (seen < e && !__atomic_compare_exchange_n(&c->dead_epoch, &seen, e, false, __ATOMIC_RELEASE, __ATOMIC_RELAXED)) {
+  }
 }
 
-int ftar_ctrl_progress(const void* ctrl) {
-  if (!ctrl) return 0;
-  const Ctrl* c = static_cast<const Ctrl*>(ctrl);
-  if (c->n_blocks == 0) return static_cast<int>(c->n_steps);
-  return static_cast<int>(__atomic_load_n(&c->progress, __ATOMIC_ACQUIRE));
+int ftar_ctrl_progress_call(const void* ctrl, int ticket) {
+  const CallRec* r = record_of(const_cast<void*>(ctrl), ticket);
+  if (!r) return 0;
+  if (r->n_blocks == 0) return static_cast<int>(r->n_units);
+  return static_cast<int>(__atomic_load_n(&r->progress, __ATOMIC_ACQUIRE));
 }
 
-ftar_status_t ftar_ctrl_result(const void* ctrl, int* steps_done) {
-  if (!ctrl) return fail(FTAR_ERR_INVALID_ARG);
-  const Ctrl* c = static_cast<const Ctrl*>(ctrl);
-  const int done = ftar_ctrl_progress(ctrl);
-  if (steps_done) *steps_done = done;
-  const unsigned long long status = __atomic_load_n(&c->status, __ATOMIC_ACQUIRE);
+int ftar_ctrl_progress(const void* ctrl) { return ftar_ctrl_progress_call(ctrl, ftar_ctrl_last_ticket(ctrl)); }
+
+ftar_status_t ftar_ctrl_result_call(const void* ctrl, int ticket, int* units_done) {
+  const CallRec* r = record_of(const_cast<void*>(ctrl), ticket);
+  if (!r) return fail(FTAR_ERR_INVALID_ARG);
+  const int done = ftar_ctrl_progress_call(ctrl, ticket);
+  if (units_done) *units_done = done;
+  const unsigned long long status = __atomic_load_n(&r->status, __ATOMIC_ACQUIRE);
+  if (status == kRecLaunchFailed) return fail(FTAR_ERR_DEVICE);
+  if (status == 3) return fail(FTAR_ERR_SKIPPED);  // queued behind a cancel or a timeout: nothing ran
   if (status != 0) return fail(FTAR_ERR_STALE_PLAN);  // timed out or cancelled: re-plan and restart
-  if (done != static_cast<int>(c->n_steps)) return fail(FTAR_ERR_INVALID_ARG);  // still running
+  if (r->n_blocks != 0 && __atomic_load_n(&r->ended, __ATOMIC_ACQUIRE) == 0)
+    return fail(FTAR_ERR_INVALID_ARG);  // still running
+  if (done != static_cast<int>(r->n_units)) return fail(FTAR_ERR_INVALID_ARG);
   return FTAR_OK;
+}
+
+ftar_status_t ftar_ctrl_result(const void* ctrl, int* units_done) {
+  return ftar_ctrl_result_call(ctrl, ftar_ctrl_last_ticket(ctrl), units_done);
 }
 
 ftar_status_t ftar_last_error(void) { return t_last_error; }
 
-int ftar_status_is_retryable(ftar_status_t s) { return s == FTAR_ERR_STALE_PLAN ? 1 : 0; }
+int ftar_status_is_retryable(ftar_status_t s) { return (s == FTAR_ERR_STALE_PLAN || s == FTAR_ERR_SKIPPED) ? 1 : 0; }
 
 const char* ftar_status_str(ftar_status_t s) {
   switch (s) {
@@ -627,6 +725,7 @@ const char* ftar_status_str(ftar_status_t s) {
     case FTAR_ERR_BAD_STEP: return "step outside [0, n_live-2]";
     case FTAR_ERR_TOO_LARGE: return "partition (or unpartitioned buffer) exceeds the library's static scratch";
     case FTAR_ERR_STALE_PLAN: return "plan is stale: re-plan over the new group and restart";
+    case FTAR_ERR_SKIPPED: return "skipped: queued behind a call that was cancelled or timed out; nothing ran";
     case FTAR_ERR_DEVICE: return "HIP runtime error";
   }
   return "unknown status";

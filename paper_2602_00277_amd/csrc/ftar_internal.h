@@ -35,29 +35,50 @@ struct ScaleTable {
   float s[kMaxReplicas + 1];
 };
 
-// Control block of the persistent ring.  The CPU side lives in coherent host-pinned memory; each
-// word the two sides exchange sits on its own 64-byte line.  Only ONE workgroup (the relay) ever
-// reads it: 256 workgroups polling host memory over PCIe cost tens of microseconds per step.
-// The relay copies the gate into a small mirror in device memory, which the workers poll.
+// Control block of the persistent ring.  The CPU side lives in coherent host-pinned memory; words
+// that one side writes and the other polls sit on 64-byte lines of their own.  Only ONE workgroup
+// (the relay) ever reads it: 256 workgroups polling host memory over PCIe cost tens of microseconds
+// per step.  The relay copies the gate into a small mirror in device memory, which the workers poll.
+//
+// Several calls may be queued on one stream against one control block (paper section 4.1: one
+// all-reduce per gradient bucket, overlapped with the backward pass).  Each call gets a ticket and
+// a record of its own in the block; a cancel, or a timeout inside any call, ends every call queued
+// so far at its first wait (section 4.2, "Timeout and error handling": queued operations are
+// cancelled and marked skipped).  This works through epochs: every call carries the epoch it was
+// enqueued in; the CPU kills an epoch by storing it into dead_epoch (and opens the next one), a
+// workgroup whose wait times out stores it into gpu_dead_epoch; the relay of every later kernel of
+// a dead epoch sees that before it passes on anything and tells its workers to leave.
 constexpr int kMaxPersistentBlocks = 1024;
-constexpr unsigned long long kGateCancel = 1ull << 63;
+constexpr int kCtrlCalls = 64;  // records in a control block: calls that may be in flight at once
+constexpr unsigned long long kGateCancel = 1ull << 63;  // in the mirror's gate word only
 
 struct DevCtrl {  // device memory, zeroed on the stream before every launch
-  unsigned long long gate;      // copy of Ctrl::gate, written by the relay
-  unsigned int verdict;         // 0 run, 1 a wait timed out, 2 cancelled: everybody leaves
+  unsigned long long gate;      // units released (copy of the call's gate) | kGateCancel, written by the relay
+  unsigned int verdict;         // 0 run, 1 a wait timed out, 2 cancelled, 3 skipped: everybody leaves
   unsigned int exited;          // workers that have left the kernel
-  unsigned int min_slot;        // slots finished by EVERY worker, maintained by the relay
-  unsigned int worker_slot[kMaxPersistentBlocks];  // slots finished by worker b
+  unsigned int min_unit;        // gate units finished by EVERY worker, maintained by the relay
+  unsigned int worker_unit[kMaxPersistentBlocks];  // gate units finished by worker b
+};
+
+struct alignas(64) CallRec {  // one queued call
+  alignas(64) unsigned long long gate;      // CPU -> GPU: gate units released
+  alignas(64) unsigned long long status;    // GPU -> CPU: 0 ok so far, 1 a wait timed out, 2 cancelled, 3 skipped
+  unsigned long long blocked_unit;          // GPU -> CPU: unit a workgroup gave up at
+  unsigned long long progress;              // GPU -> CPU: units finished by EVERY worker
+  unsigned long long ended;                 // GPU -> CPU: 1 once the kernel has left
+  alignas(64) unsigned long long epoch;     // host only from here on
+  long long ticket;                         // -1: never used
+  unsigned int n_blocks;                    // workers; 0: nothing was launched (ring of one)
+  unsigned int n_units;                     // gate units of the call
 };
 
 struct alignas(64) Ctrl {
-  alignas(64) unsigned long long gate;      // CPU -> GPU: low 32 bits = steps released, bit 63 = cancel
-  alignas(64) unsigned long long status;    // GPU -> CPU: 0 ok, 1 a wait timed out, 2 cancelled
-  unsigned long long blocked_step;          // GPU -> CPU: step a workgroup gave up at
-  alignas(64) unsigned long long progress;  // GPU -> CPU: slots finished by EVERY worker
-  alignas(64) unsigned int n_blocks;        // workers; set by the launcher
-  unsigned int n_steps;                     // slots = partitions * (2N-2); set by the launcher
-  DevCtrl* dev;                             // the mirror, allocated with the control block
+  alignas(64) unsigned long long dead_epoch;      // CPU -> GPU: calls of epochs <= this are cancelled
+  alignas(64) unsigned long long gpu_dead_epoch;  // GPU -> GPU and CPU: a call of this epoch timed out
+  alignas(64) unsigned long long cur_epoch;       // host only: epoch of the next call (starts at 1)
+  long long next_ticket;                          // host only
+  DevCtrl* dev;                                   // the mirror, allocated with the control block
+  CallRec call[kCtrlCalls];
 };
 
 enum RingMode {
@@ -119,18 +140,25 @@ hipError_t launch_ring_onepass(const PtrTable& ring, int n_live, const SegTable&
 
 // Geometry of a partitioned ring: n_parts partitions of part_elems elements (the last one may be
 // shorter); portion boundaries are relative to the partition's first element.
+// chunk_elems != 0: the gate unit is a ROW of chunks - chunk c of every portion - of one step of one
+// partition instead of the whole step (paper section 4.2: each step is pipelined over the chunks of
+// a portion); rows_full / rows_last = rows per step in a full / in the last partition.
 struct PartGeom {
   unsigned n_parts;
   unsigned long long part_elems;
   SegTable seg_full;  // portions of a full partition
   SegTable seg_last;  // portions of the last partition
+  unsigned long long chunk_elems;
+  unsigned rows_full, rows_last;
 };
 
 // n_blocks workers plus one relay workgroup; clears *mirror on the stream first.
+// ctrl_dev / rec_dev: device views of the control block and of this call's record.
 hipError_t launch_ring_persistent(const PtrTable& ring, int n_live, const PartGeom& geom,
                                   ftar_dtype_t dtype, bool vec, float* acc, float scale, Ctrl* ctrl_dev,
-                                  DevCtrl* mirror, unsigned n_blocks, unsigned long long timeout_ticks,
-                                  unsigned flags, unsigned long long zpos, hipStream_t stream);
+                                  CallRec* rec_dev, unsigned long long epoch, DevCtrl* mirror, unsigned n_blocks,
+                                  unsigned long long timeout_ticks, unsigned flags, unsigned long long zpos,
+                                  hipStream_t stream);
 
 // Static scratch of the entry point that allocates nothing (ftar_ring_persistent_static): the
 // mirror of the control block and room for the partial sums of one partition, in a file-scope

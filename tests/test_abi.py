@@ -49,9 +49,9 @@ def test_exports_every_declared_symbol(B):
 
 
 def test_status_strings_and_classes(B):
-    for s in (0, 1, 2, 3, 4, 5, 16, 32):
+    for s in (0, 1, 2, 3, 4, 5, 16, 17, 32):
         assert B.ftar_status_str(s) and B.ftar_status_str(s) != "unknown status"
-    assert B.ftar_status_is_retryable(B.FTAR_ERR_STALE_PLAN)
+    assert B.ftar_status_is_retryable(B.FTAR_ERR_STALE_PLAN) and B.ftar_status_is_retryable(B.FTAR_ERR_SKIPPED)
     assert not any(B.ftar_status_is_retryable(s) for s in (0, 1, 2, 3, 4, 5, 32))
 
 
@@ -118,3 +118,27 @@ def test_lr_factors_match_the_oracle(B, oracle):
         assert L.ftar_plan_lr_factors(plan, None, None) == 0
         L.ftar_plan_destroy(plan)
     assert L.ftar_plan_lr_factors(None, None, None) == B.FTAR_ERR_INVALID_ARG
+
+
+def test_gate_units_match_the_definition(B, oracle):
+    # host-only: slots without the flag; with rows of chunks, per partition (2N-2) x the largest number of
+    # chunks any portion has (paper section 4.2: a step is pipelined over the chunks of a portion)
+    L = B.lib()
+    for n, mask, count, chunk, part in [(8, 0xFF, 8 * 8192 * 6, 8192, 0), (8, 0xF7, 7 * 4096 * 5 + 4096 * 3 + 100, 4096, 0),
+                                        (16, 0xFFFF, 1 << 28, 16384, 0), (16, 0xFDFF, 1 << 28, 16384, 4 << 20),
+                                        (6, 0x3F, 6 * 8192 * 10 + 8192 * 2, 8192, 6 * 8192 * 4), (12, 0xFFF, 4096 * 5, 4096, 0),
+                                        (2, 3, 1000, 7, 0), (1, 1, 1000, 7, 0)]:
+        plan = L.ftar_plan(n, mask, count, chunk)
+        assert plan
+        if part:
+            assert L.ftar_plan_set_partition(plan, part) == 0
+        N = bin(mask).count("1")
+        want = 0
+        P = part if part else count
+        for p0 in range(0, count, P):
+            sb = oracle.geometry(n, mask, min(P, count - p0), chunk)
+            want += (2 * N - 2) * max(-(-(sb[k + 1] - sb[k]) // chunk) for k in range(N))
+        assert L.ftar_plan_n_gate_units(plan, B.FTAR_PERSIST_CHUNKS) == want, (n, hex(mask), count, chunk, part)
+        assert L.ftar_plan_n_gate_units(plan, 0) == L.ftar_plan_n_slots(plan)
+        L.ftar_plan_destroy(plan)
+    assert L.ftar_plan_n_gate_units(None, 0) == 0

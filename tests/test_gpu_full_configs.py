@@ -140,6 +140,117 @@ def test_cfg3b_through_the_persistent_kernel(B, oracle):
         assert torch.equal(bufs[r].view(torch.int16), bufs[live[0]].view(torch.int16)), r
 
 
+def _cfg3a_check(oracle, w, bufs, orig, starts, part, what, owner_only=False):
+    """bufs against the oracle's closed form on the sampled slabs.  part: partition size in elements
+    (a partition is a ring of its own over its own length) or 0.  owner_only: only the owner of each
+    portion holds the result, everything else is as it was (the state after the ReduceScatter phase)."""
+    n, count, chunk = w.n_replicas, w.count, w.chunk_elems
+    mask = w.live_mask
+    ring = oracle.live_ring(n, mask)
+    N = len(ring)
+    for s in starts:
+        if part:
+            p0 = (s // part) * part
+            assert s + SLAB <= min(count, p0 + part), "slabs are drawn inside one partition"
+            L = min(part, count - p0)
+            want = oracle.ring_closed_form(orig[s], mask, L, chunk, code(w.dtype), begin=s - p0, length=SLAB)
+            sb = [p0 + x for x in oracle.geometry(n, mask, L, chunk)]
+        else:
+            want = oracle.ring_closed_form(orig[s], mask, count, chunk, code(w.dtype), begin=s, length=SLAB)
+            sb = oracle.geometry(n, mask, count, chunk)
+        for r in range(n):
+            got = host_slab(bufs[r], s, s + SLAB)
+            if not owner_only:
+                assert_same(got, want, "%s slab %d replica %d" % (what, s, r))
+                continue
+            exp = orig[s][r].copy()
+            for k in range(N):                      # portion k belongs to ring position k-1
+                if ring[(k + N - 1) % N] != r:
+                    continue
+                lo, hi = max(s, sb[k]), min(s + SLAB, sb[k + 1])
+                if lo < hi:
+                    exp[lo - s:hi - s] = want[lo - s:hi - s]
+            assert_same(got, exp, "%s slab %d replica %d" % (what, s, r))
+
+
+def test_cfg3a_every_other_ring_path_at_full_size(B, oracle):
+    # the paths that deliver the ring's result differently, each on fresh 16 x 256 Mi inputs at full size:
+    # the partitioned persistent ring (4 Mi-element partitions, 1920 slots), the one-pass all-reduce, the
+    # one-pass ReduceScatter phase (owners only) completed by the one-pass AllGather phase
+    w = W.configs()[2]
+    n, count, chunk = w.n_replicas, w.count, w.chunk_elems
+    mask = w.live_mask
+    part = 4 * W.M
+    sb = oracle.geometry(n, mask, count, chunk)
+    psb = oracle.geometry(n, mask, part, chunk)
+    special = sb[1:-1] + [1 << 30 // 1, (1 << 31) // w.elem_bytes]
+    starts = set(_slab_starts(count, special, 10, seed=w.seed + 7))
+    # slabs around portion boundaries INSIDE partitions (first, one in the middle, the last) and next to
+    # partition boundaries; every slab lies inside one partition
+    for p in (0, 17, count // part - 1):
+        for b in psb[1:-1:5]:
+            starts.add(p * part + max(0, b - SLAB // 2))
+        starts.add(p * part)
+        starts.add((p + 1) * part - SLAB)
+    starts = sorted(x for x in starts if x // part == (x + SLAB - 1) // part and x + SLAB <= count)
+    pristine = W.draw_replicas(w, "cuda")
+    orig = {s: [host_slab(b, s, s + SLAB) for b in pristine] for s in starts}
+    bufs = [torch.empty_like(b) for b in pristine]
+
+    def fresh():
+        for d, src in zip(bufs, pristine):
+            d.copy_(src)
+
+    live0 = bufs[0]
+    # (a) partitioned persistent ring
+    say(w.name, "persistent ring in partitions of 4 Mi elements")
+    fresh()
+    plan = B.ftar_plan(n, mask, count, chunk, w.dtype)
+    plan.set_partition(part)
+    acc = torch.empty(part, dtype=torch.float32, device="cuda")
+    ctrl = B.ftar_ctrl_create()
+    B.ftar_ring_persistent(plan, bufs, acc, ctrl, timeout_us=20_000_000)
+    ctrl.release(plan.n_slots)
+    torch.cuda.synchronize()
+    assert ctrl.result() == (B.FTAR_OK, plan.n_slots) and plan.n_slots == 64 * 30
+    _cfg3a_check(oracle, w, bufs, orig, starts, part, "partitioned persistent ring")
+    for r in range(1, n):
+        assert torch.equal(bufs[r].view(torch.int16), live0.view(torch.int16)), r
+    ctrl.destroy()
+    plan.set_partition(0)
+    del acc
+    # (b) one-pass all-reduce
+    say(w.name, "ftar_allreduce_onepass")
+    fresh()
+    B.ftar_allreduce_onepass(plan, bufs)
+    torch.cuda.synchronize()
+    _cfg3a_check(oracle, w, bufs, orig, starts, 0, "one-pass all-reduce")
+    for r in range(1, n):
+        assert torch.equal(bufs[r].view(torch.int16), live0.view(torch.int16)), r
+    # (c) one-pass ReduceScatter phase: owners only ...
+    say(w.name, "ftar_reduce_scatter_all, then ftar_allgather_all")
+    fresh()
+    B.ftar_reduce_scatter_all(plan, bufs)
+    torch.cuda.synchronize()
+    _cfg3a_check(oracle, w, bufs, orig, starts, 0, "reduce-scatter-all", owner_only=True)
+    # ... completed by the one-pass AllGather phase
+    B.ftar_allgather_all(plan, bufs)
+    torch.cuda.synchronize()
+    _cfg3a_check(oracle, w, bufs, orig, starts, 0, "reduce-scatter-all + allgather-all")
+    for r in range(1, n):
+        assert torch.equal(bufs[r].view(torch.int16), live0.view(torch.int16)), r
+    # (d) the step kernels' ReduceScatter phase completed by the one-pass AllGather phase
+    say(w.name, "15 ReduceScatter steps, then ftar_allgather_all")
+    fresh()
+    acc = torch.empty(count, dtype=torch.float32, device="cuda")
+    for st in range(plan.n_steps):
+        B.ftar_reduce_step(plan, st, bufs, acc)
+    B.ftar_allgather_all(plan, bufs)
+    torch.cuda.synchronize()
+    _cfg3a_check(oracle, w, bufs, orig, starts, 0, "RS steps + allgather-all")
+    plan.destroy()
+
+
 def test_cfg4_two_billion_elements(B, oracle):
     w = W.configs()[3]
     say(w.name)

@@ -117,7 +117,9 @@ def test_unreleased_step_times_out_and_leaves_inputs_intact(B, oracle, dtype):
     for r in range(n):
         assert_same(host(bufs[r]), orig[r], "buf %d untouched" % r)
     assert_same(host(acc), oracle.ring_partial(orig, mask, count, chunk, code(dtype), 3), "in-flight partials")
-    # retry: a fresh call on the same control block completes
+    # retry: the CPU acknowledges the failure (until then anything it enqueues counts as queued behind
+    # the call that timed out); then a fresh call on the same control block completes
+    ctrl.cancel()
     B.ftar_ring_persistent(plan, bufs, acc, ctrl, timeout_us=5_000_000)
     ctrl.release(14)
     torch.cuda.synchronize()
