@@ -149,7 +149,7 @@ def all_configs_report(path, B, W, torch, np):
     for mib in (128, 1024):
         words = mib * W.M // 4
         pool = [torch.randint(-2**31, 2**31 - 1, (words,), dtype=torch.int32, device=dev) for _ in range(9)]
-        for n_read, n_written in ((8, 0), (1, 0), (0, 1), (0, 8), (1, 1), (7, 1), (8, 1), (4, 4)):
+        for n_read, n_written in ((8, 0), (1, 0), (0, 1), (0, 8), (1, 1), (2, 1), (4, 1), (7, 1), (8, 1), (4, 4)):
             if n_read + n_written > len(pool):
                 continue
             rd, wr = pool[:n_read], pool[n_read:n_read + n_written]
@@ -164,6 +164,23 @@ def all_configs_report(path, B, W, torch, np):
             gbs = (n_read + n_written) * mib * W.M / 1e9 / t
             ceil_rows.append("| %d MiB | %d | %d | %.1f | %.0f | %.1f |" % (mib, n_read, n_written, t * 1e6, gbs,
                                                                         100 * gbs / HBM_PEAK_GBS))
+            print(ceil_rows[-1], file=sys.stderr, flush=True)
+        # the same mixes of many read streams and one written one, the writes placed in windows of the clock
+        for n_read in (4, 7, 8):
+            rd, wr = pool[:n_read], pool[n_read]
+            period = 4096 if n_read >= 6 else 2048
+            window = period // 8 if n_read >= 6 else period // 4
+            for _ in range(2):
+                B.ftar_probe_stream_windows(rd, wr, period, window)
+            for a, b in pairs:
+                B.ftar_time_next_launch(a, b)
+                B.ftar_probe_stream_windows(rd, wr, period, window)
+            torch.cuda.synchronize()
+            ts = sorted(ev.elapsed_s(a, b) for a, b in pairs)
+            t = ts[len(ts) // 2]
+            gbs = (n_read + 1) * mib * W.M / 1e9 / t
+            ceil_rows.append("| %d MiB | %d | 1, in write windows (%d us period, %d us window) | %.1f | %.0f | %.1f |" % (
+                mib, n_read, period // 100, window // 100, t * 1e6, gbs, 100 * gbs / HBM_PEAK_GBS))
             print(ceil_rows[-1], file=sys.stderr, flush=True)
         del pool
         torch.cuda.empty_cache()
@@ -563,12 +580,20 @@ def diagnose_launches(B, W, torch):
         torch.cuda.synchronize()
         groups.append({"kernel": "k_probe_stream<%d,%d>" % (n_read, n_written), "dispatches": 1,
                        "read": n_read * GiB, "written": n_written * GiB})
+    B.ftar_probe_stream_windows(pool[:8], pool[8], 4096, 512)
+    torch.cuda.synchronize()
+    groups.append({"kernel": "k_probe_stream_win<8>", "dispatches": 1, "read": 8 * GiB, "written": GiB})
     bufs = [p.view(torch.bfloat16) for p in pool[:8]]        # any bit pattern is a valid input
     out = pool[8].view(torch.bfloat16)
+    B.ftar_set_tuning(0, 0x80)                               # the plain kernel: no write windows
     B.ftar_reduce_masked(bufs, 0xFF, out)
     torch.cuda.synchronize()
-    groups.append({"kernel": "k_reduce_masked<bf16,N=8>", "dispatches": "several (about 1 GiB of traffic each)",
+    B.ftar_set_tuning(0, 0)
+    groups.append({"kernel": "k_reduce_masked<bf16,N=8> (plain)", "dispatches": "several (about 1 GiB of traffic each)",
                    "read": 8 * GiB, "written": GiB})
+    B.ftar_reduce_masked(bufs, 0xFF, out)                    # the default at this size: write windows, one launch
+    torch.cuda.synchronize()
+    groups.append({"kernel": "k_reduce_masked_win<bf16,N=8>", "dispatches": 1, "read": 8 * GiB, "written": GiB})
     del bufs, out, pool
     torch.cuda.empty_cache()
     w = W.configs()[2]
@@ -586,6 +611,196 @@ def diagnose_launches(B, W, torch):
     groups.append({"kernel": "k_ring_allgather", "dispatches": 15, "read": (N - 1) * E * w.count,
                    "written": (N - 1) * E * w.count})
     print(json.dumps({"groups": groups}), flush=True)
+
+
+def cu_budget_report(path, B, W, torch):
+    """The persistent ring on a small compute-unit budget (paper section 4.2, "Optimizations": few
+    units, so that the training compute keeps the chip), three ways: n worker workgroups anywhere on
+    the chip; the same on a stream restricted to n compute units; several workgroups on each of the
+    reserved units.  And what a GEMM on a second stream loses next to each.  16 x 64 Mi bf16."""
+    import ctypes
+    dev = "cuda:0"
+    hip = HipEvents().hip
+    hip.hipExtStreamCreateWithCUMask.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint32,
+                                                 ctypes.POINTER(ctypes.c_uint32)]
+    hip.hipStreamDestroy.argtypes = [ctypes.c_void_p]
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    words = (n_cu + 31) // 32
+
+    def masked_stream(cus):
+        m = (ctypes.c_uint32 * words)()
+        for c in cus:
+            m[c // 32] |= 1 << (c % 32)
+        s = ctypes.c_void_p()
+        rc = hip.hipExtStreamCreateWithCUMask(ctypes.byref(s), words, m)
+        if rc != 0:
+            hip.hipGetLastError()          # leave no sticky error behind
+            return None
+        return s
+
+    # is a stream with a compute-unit mask to be had here at all?  (all units, then a few)
+    mask_note = ""
+    probe = masked_stream(range(n_cu))
+    if probe is None:
+        mask_note = ("`hipExtStreamCreateWithCUMask` returns an error on this machine even for the mask of all "
+                     "compute units: the reserved-unit columns could not be measured.")
+    else:
+        hip.hipStreamDestroy(probe)
+        probe = masked_stream([i * 32 for i in range(n_cu // 32)])   # the same unit in every group of 32
+        if probe is None:
+            mask_note = ("`hipExtStreamCreateWithCUMask` accepts the mask of all compute units but no partial "
+                         "one on this machine (tried: two units; one unit in every group of 32): the reserved-unit "
+                         "columns could not be measured.")
+        else:
+            hip.hipStreamDestroy(probe)
+    hip.hipGetLastError.restype = ctypes.c_int
+
+    n, count = 16, 64 * W.M
+    E = 2
+    w = W.configs()[2].scaled(count)
+    bufs = W.draw_replicas(w, dev)
+    acc = torch.empty(count, dtype=torch.float32, device=dev)
+    plan = B.ftar_plan(n, 0xFFFF, count, w.chunk_elems, w.dtype)
+    ctrl = B.ftar_ctrl_create()
+    n_steps = 2 * n - 2
+    gb = ((2 * E + 4) + (n - 3) * (8 + E) + (4 + 2 * E) + (n - 1) * 2 * E) * count / 1e9
+
+    def ring(stream, nb, release=True):
+        B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=nb, timeout_us=60_000_000, stream=stream)
+        if release:
+            ctrl.release(n_steps)
+
+    def timed(stream, nb):
+        ring(stream, nb)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ring(stream, nb)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    rows = []
+    for k in (2, 4, 8, 16, 32):
+        groups = n_cu // 32
+        cus = [g * 32 + j * (32 // max(1, k // groups)) for g in range(groups) for j in range(max(1, k // groups))]
+        ms = None if (mask_note or k < groups) else masked_stream(cus)   # the same units in every group of 32
+        line = ["%d" % k, "%.0f" % (gb / timed(None, k))]
+        B.ftar_set_tuning(0, 0x400000)                          # small tiles: several workgroups fit a unit
+        line.append("%.0f" % (gb / timed(None, k)))
+        for per in (1, 2, 4):
+            line.append("-" if ms is None else "%.0f" % (gb / timed(ms.value, k * per)))
+        B.ftar_set_tuning(0, 0)
+        line.append("-" if ms is None else "%.0f" % (gb / timed(ms.value, k)))
+        for per in (2, 4):                                      # more workgroups than the budget, anywhere on the chip
+            B.ftar_set_tuning(0, 0x400000)
+            line.append("%.0f" % (gb / timed(None, k * per)))
+            B.ftar_set_tuning(0, 0)
+        rows.append("| " + " | ".join(line) + " |")
+        print(rows[-1], file=sys.stderr, flush=True)
+        torch.cuda.synchronize()
+        if ms is not None:
+            hip.hipStreamDestroy(ms)
+    # the neighbour: a GEMM on a second stream
+    side = torch.cuda.Stream()
+    a = torch.randn(8192, 8192, device=dev, dtype=torch.bfloat16)
+    b = torch.randn(8192, 8192, device=dev, dtype=torch.bfloat16)
+    o = torch.empty(8192, 8192, device=dev, dtype=torch.bfloat16)
+
+    def gemm_loop(reps=40):
+        with torch.cuda.stream(side):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.matmul(a, b, out=o)
+            e0.record(side)
+            for _ in range(reps):
+                torch.matmul(a, b, out=o)
+            e1.record(side)
+        side.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+    alone = gemm_loop()
+    share = []
+    k = 8
+    cus = [i * (n_cu // k) for i in range(k)]
+    ms = None if mask_note else masked_stream(cus)
+    cases = [("8 workers anywhere, waiting only", None, 8, 0, False),
+             ("8 workers anywhere, running", None, 8, 0, True),
+             ("2 workers anywhere, waiting only", None, 2, 0, False),
+             ("2 workers anywhere, running", None, 2, 0, True)]
+    if ms is not None:
+        cases += [("8 reserved units x 1 workgroup, waiting only", ms.value, 8, 0x400000, False),
+                  ("8 reserved units x 1 workgroup, running", ms.value, 8, 0x400000, True),
+                  ("8 reserved units x 4 workgroups, running", ms.value, 32, 0x400000, True)]
+    for label, stream, nb, flags, release in cases:
+        B.ftar_set_tuning(0, flags)
+        ring(stream, nb, release)
+        t = gemm_loop()
+        still = ctrl.progress() < n_steps
+        ctrl.cancel()
+        torch.cuda.synchronize()
+        B.ftar_set_tuning(0, 0)
+        share.append("| %s | %.3f | %+.1f %%%s |" % (label, t * 1e3, 100 * (t / alone - 1),
+                                                     "" if still or not release else " (ring ended before the loop)"))
+        print(share[-1], file=sys.stderr, flush=True)
+    if ms is not None:
+        hip.hipStreamDestroy(ms)
+    ctrl.destroy()
+    out = ["# The persistent ring on a compute-unit budget (one MI355X, %d compute units)" % n_cu, "",
+           "Command: `python3 bench.py --cu-budget %s`. 16 x 64 Mi bf16, clean 16-ring as ONE persistent kernel, all "
+           "steps released at once; GB/s of algorithmic bytes (%.1f GB per all-reduce), wall time of one call. "
+           "\"Reserved units\": the ring's stream is created with `hipExtStreamCreateWithCUMask` over that many "
+           "compute units, spread evenly over the chip; its workgroups can only run there. " % (path, gb) + mask_note, "",
+           "| budget n | n workgroups anywhere, big tiles (default) | anywhere, small tiles | n reserved units x 1 workgroup, small tiles | x 2 | x 4 | n reserved units x 1, big tiles | 2n workgroups anywhere, small tiles | 4n anywhere, small tiles |",
+           "|---|---|---|---|---|---|---|---|---|"] + rows + [
+           "", "## A GEMM next to it", "",
+           "bf16 8192 x 8192 x 8192 (`torch.matmul`) 40 times on a second stream of the same priority; alone: %.3f ms." % (alone * 1e3), "",
+           "| the ring | GEMM ms | change |", "|---|---|---|"] + share
+    # ---- the chunk pipeline at the paper's chunk size ---------------------------------------
+    del bufs, acc, a, b, o
+    torch.cuda.empty_cache()
+    S = 4 * W.M                      # 8 MB of bf16: the paper's chunk
+    n, count = 16, 1024 * W.M
+    bufs = [torch.empty(count, dtype=torch.bfloat16, device=dev).normal_(0, 1e-3) for _ in range(n)]
+    ctrl = B.ftar_ctrl_create()
+    gb2 = ((2 * E + 4) + (n - 3) * (8 + E) + (4 + 2 * E) + (n - 1) * 2 * E) * count / 1e9
+    pipe = []
+    for C in (1, 4, 16):
+        part = S * C * n
+        plan = B.ftar_plan(n, 0xFFFF, count, S, torch.bfloat16)
+        plan.set_partition(part)
+        acc = torch.empty(plan.acc_bytes // 4, dtype=torch.float32, device=dev)
+        cells = []
+        for flags, stepwise in ((0, False), (B.FTAR_PERSIST_CHUNKS, False), (B.FTAR_PERSIST_CHUNKS | B.FTAR_PERSIST_PUBLISH, True)):
+            units = plan.n_gate_units(flags)
+
+            def run():
+                B.ftar_ring_persistent(plan, bufs, acc, ctrl, timeout_us=60_000_000, flags=flags)
+                if not stepwise:
+                    ctrl.release(units)
+                else:
+                    for u in range(units):
+                        ctrl.release(u + 1)
+                        while ctrl.progress() < u + 1:
+                            pass
+            run()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            run()
+            torch.cuda.synchronize()
+            t = time.perf_counter() - t0
+            ok = ctrl.result() == (0, units)
+            cells.append("%d units, %.0f GB/s%s" % (units, gb2 / t, "" if ok else " (FAILED)"))
+        pipe.append("| %d | %d Mi elements (%d partitions) | %s |" % (C, part // W.M, plan.n_partitions, " | ".join(cells)))
+        print(pipe[-1], file=sys.stderr, flush=True)
+        plan.destroy()
+        del acc
+    ctrl.destroy()
+    out += ["", "## The chunk pipeline at the paper's chunk size", "",
+            "16 x 1 Gi bf16 (%.0f GB per all-reduce), chunk S = 8 MB (4 Mi bf16 elements), partitions of S x C x N bytes "
+            "(paper section 4.2), one persistent kernel, one workgroup per compute unit (two with partitions). Gate units: "
+            "slots (a whole step of a partition), or rows of chunks (FTAR_PERSIST_CHUNKS: C rows per step). Last column: a "
+            "CPU thread releases row u + 1 only after every workgroup has reported row u written back (PUBLISH)." % gb2, "",
+            "| C | partition | gated by slots, all released | gated by rows of chunks, all released | rows released one by one by the CPU |",
+            "|---|---|---|---|---|"] + pipe
+    with open(path, "w") as f:
+        f.write("\n".join(out) + "\n")
 
 
 def _same(np, got, want):
@@ -672,6 +887,9 @@ def main():
                          "rocprofv3 --pmc) and print the bytes each group of dispatches should move")
     ap.add_argument("--tuning", metavar="BLOCKS_PER_CU,FLAGS", default=None,
                     help="development only: ftar_set_tuning before anything runs (the output says so)")
+    ap.add_argument("--cu-budget", metavar="PATH", default=None,
+                    help="the persistent ring on few compute units (anywhere / on reserved units of a CU-masked "
+                         "stream) and a GEMM next to it; writes a markdown report to PATH")
     ap.add_argument("--diagnose-launches", action="store_true",
                     help="bare streaming kernels and the product kernels on 1 GiB streams, each launched "
                          "once (for runs under rocprofv3 --pmc with stall and request counters)")
@@ -703,6 +921,9 @@ def main():
         return
     if args.diagnose_launches:
         diagnose_launches(B, W, torch)
+        return
+    if args.cu_budget:
+        cu_budget_report(args.cu_budget, B, W, torch)
         return
 
     w = W.configs()[3]                      # cfg 4: the largest single-GPU workload

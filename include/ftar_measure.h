@@ -8,8 +8,8 @@
  *
  * Two libraries export them:
  *   libftar.so          ftar_set_tuning, ftar_time_next_launch  (hooks in the product's launch path)
- *   libftar_measure.so  ftar_probe_stream                       (bench-only; links against libftar.so
- *                                                                and honours both hooks)
+ *   libftar_measure.so  ftar_probe_stream, ftar_probe_stream_windows   (bench-only; links against
+ *                                                                libftar.so and honours both hooks)
  */
 #ifndef FTAR_MEASURE_H_
 #define FTAR_MEASURE_H_
@@ -25,11 +25,17 @@ extern "C" {
 
 /* Launch shape and cache policy, for measurement only (results never depend on it).
  * blocks_per_cu: workgroups launched per compute unit (0 = each kernel's default);
- * flags: 0 = each kernel's default policy; 0x10 | p = explicit policy p, where bit 0 of p
- * asks for non-temporal loads and bit 1 for non-temporal stores; 0x20 = wide tiles in the
- * one-shot reduce; 0x40 = never split a long one-shot reduce into several launches and never run big
- * buckets one by one;
- * bits 8..11 = vectors per lane and tile in the ring kernels (2, 4 or 8). */
+ * flags: 0 = each kernel's defaults.
+ *   0x10 | p      explicit cache policy p: bit 0 non-temporal loads, bit 1 non-temporal stores
+ *   0x20          wide tiles in the one-shot reduce
+ *   0x40          one launch, however long the call (one-shot reduce, big buckets, ring steps)
+ *   0x80          no write windows in the many-source reductions
+ *   bits 8..11    vectors per lane and tile in the ring step kernels (2, 4 or 8)
+ *   bits 12..15   log2 of the write-window period in 10 ns ticks; bits 16..19: log2(period / window)
+ *   0x100000      write windows at any output size
+ *   0x200000      bf16 ReduceScatter lanes take 8 elements (16-byte loads, two partial-sum vectors)
+ *   0x400000      the persistent ring keeps its small tile also with few workgroups
+ *   bits 24..27   log2 of the MiB of traffic per launch of a long ring step */
 void ftar_set_tuning(int blocks_per_cu, int flags);
 
 /* Measurement only: arms two hipEvent_t (passed as void*, either may be NULL) for the NEXT kernel
@@ -49,6 +55,15 @@ void ftar_time_next_launch(void* start_event, void* stop_event);
  * 4+4, 8+8; anything else FTAR_ERR_INVALID_ARG.  Honours ftar_set_tuning and ftar_time_next_launch. */
 ftar_status_t ftar_probe_stream(void* const* bufs, int n_read, int n_written, size_t bytes, uint32_t fill,
                                 void* stream);
+
+/* Measurement only: n_read buffers read, ONE written (bufs: the read buffers first, then the written
+ * one; sizes and alignment as above), the written vectors staged in LDS and written out only inside
+ * windows [0, window_ticks) of every period_ticks of the 100 MHz wall clock (10 ns ticks; the period
+ * a power of two), or when the stage is full: the bare-stream form of the write windows that the
+ * many-source reductions use, next to ftar_probe_stream(n_read, 1) for the plain mix.
+ * n_read in 1, 2, 4, 7, 8, 16; anything else FTAR_ERR_INVALID_ARG.  One workgroup per compute unit. */
+ftar_status_t ftar_probe_stream_windows(void* const* bufs, int n_read, size_t bytes, unsigned period_ticks,
+                                        unsigned window_ticks, void* stream);
 
 #ifdef __cplusplus
 }

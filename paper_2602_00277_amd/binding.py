@@ -56,7 +56,7 @@ EXPORTS = [
 # every symbol include/ftar_measure.h declares: measurement hooks in libftar.so, probe kernels in
 # the bench-only libftar_measure.so
 MEASURE_HOOKS = ["ftar_set_tuning", "ftar_time_next_launch"]
-MEASURE_EXPORTS = ["ftar_probe_stream"]
+MEASURE_EXPORTS = ["ftar_probe_stream", "ftar_probe_stream_windows"]
 MEASURE_LIB_PATH = os.path.join(_PKG, "libftar_measure.so")
 
 _lib = None
@@ -182,6 +182,9 @@ def measure_lib():
     M.ftar_probe_stream.restype = ctypes.c_int
     M.ftar_probe_stream.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_size_t,
                                     ctypes.c_uint32, ctypes.c_void_p]
+    M.ftar_probe_stream_windows.restype = ctypes.c_int
+    M.ftar_probe_stream_windows.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_uint,
+                                            ctypes.c_uint, ctypes.c_void_p]
     _measure_lib = M
     return M
 
@@ -433,6 +436,20 @@ def ftar_probe_stream(read: Sequence[torch.Tensor], written: Sequence[torch.Tens
                                          _stream_handle(stream))
     if st != FTAR_OK:
         raise FtarError(st, "ftar_probe_stream")
+
+
+def ftar_probe_stream_windows(read: Sequence[torch.Tensor], written: torch.Tensor, period_ticks: int = 4096,
+                              window_ticks: int = 512, stream=None) -> None:
+    """Measurement only: the bare streaming kernel with its writes placed in windows of the wall clock."""
+    bufs = list(read) + [written]
+    nbytes = bufs[0].numel() * bufs[0].element_size()
+    for b in bufs:
+        if not b.is_cuda or not b.is_contiguous() or b.numel() * b.element_size() != nbytes:
+            raise ValueError("probe buffers must be contiguous GPU tensors of one size")
+    st = measure_lib().ftar_probe_stream_windows(_ptr_array(bufs), len(read), nbytes, period_ticks, window_ticks,
+                                                 _stream_handle(stream))
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_probe_stream_windows")
 
 
 def ftar_set_tuning(blocks_per_cu: int = 0, flags: int = 0) -> None:

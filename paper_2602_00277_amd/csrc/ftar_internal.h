@@ -172,6 +172,11 @@ hipError_t static_scratch(DevCtrl** mirror, float** acc);
 hipError_t launch_probe_stream(const PtrTable& tab, int n_read, int n_written, size_t n_vec, uint32_t fill,
                                hipStream_t stream);
 
+// Measurement only: n_read streams read, one written through the LDS stage in windows of the wall
+// clock (period and window in 10 ns ticks, period a power of two).
+hipError_t launch_probe_stream_win(const PtrTable& tab, int n_read, size_t n_vec, unsigned period_ticks,
+                                   unsigned window_ticks, hipStream_t stream);
+
 }  // namespace ftar
 
 #endif  // FTAR_INTERNAL_H_

@@ -27,4 +27,21 @@ ftar_status_t ftar_probe_stream(void* const* bufs, int n_read, int n_written, si
   return e == hipSuccess ? FTAR_OK : FTAR_ERR_DEVICE;
 }
 
+ftar_status_t ftar_probe_stream_windows(void* const* bufs, int n_read, size_t bytes, unsigned period_ticks,
+                                        unsigned window_ticks, void* stream) {
+  if (!bufs || n_read < 1 || n_read + 1 > kMaxReplicas || bytes == 0 || bytes % (32 * 1024) != 0 ||
+      period_ticks < 2 || (period_ticks & (period_ticks - 1)) != 0 || window_ticks == 0 || window_ticks > period_ticks)
+    return FTAR_ERR_INVALID_ARG;
+  PtrTable tab;
+  std::memset(&tab, 0, sizeof(tab));
+  for (int j = 0; j < n_read + 1; ++j) {
+    if (!bufs[j] || reinterpret_cast<uintptr_t>(bufs[j]) % 16 != 0) return FTAR_ERR_INVALID_ARG;
+    tab.p[j] = bufs[j];
+  }
+  hipError_t e = launch_probe_stream_win(tab, n_read, bytes / 16, period_ticks, window_ticks,
+                                         static_cast<hipStream_t>(stream));
+  if (e == hipErrorInvalidValue) return FTAR_ERR_INVALID_ARG;
+  return e == hipSuccess ? FTAR_OK : FTAR_ERR_DEVICE;
+}
+
 }  // extern "C"

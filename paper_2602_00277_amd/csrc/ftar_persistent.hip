@@ -492,7 +492,9 @@ struct RingPersistent {
   template <int POL> hipError_t operator()(unsigned) const {
     // few workers and enough tiles for all of them even at four times the tile size: big tiles
     const SegTable big = ring_tiles(geom.seg_full, N, VEC, kPersistentUnrollFew);
-    const bool few = n_blocks <= 128 && big.begin[N] >= 2ull * n_blocks;
+    // (tuning flag 0x400000 keeps the small tile: several workgroups then fit one compute unit, which is
+    // what a stream restricted to a few compute units wants)
+    const bool few = n_blocks <= 128 && big.begin[N] >= 2ull * n_blocks && (current_tuning().flags & 0x400000) == 0;
     if (geom.chunk_elems != 0) {
       // rows of chunks: a tile never crosses the end of a chunk, so the big tile only if it fits one
       const size_t big_tile = static_cast<size_t>(kThreads) * kPersistentUnrollFew * VEC;

@@ -44,6 +44,56 @@ k_probe_stream(PtrTable tab, size_t n_vec, uint32_t fill, uint32_t never) {
   }
 }
 
+// NR read streams and one written stream, the written vectors staged in LDS and written out in
+// windows of the wall clock (struct WriteWindow): what the write windows of the many-source
+// reductions give on bare streams.  One vector per lane and tile; one workgroup per compute unit.
+template <int NR, int POL>
+__global__ void __launch_bounds__(kThreads)
+k_probe_stream_win(PtrTable tab, size_t n_vec, WriteWindow win) {
+  constexpr int kCap = kStageBytes / (kThreads * 16);
+  __shared__ u32x4 stage[kCap][kThreads];
+  __shared__ u32x4* s_tab[kMaxReplicas];
+  if (threadIdx.x < static_cast<unsigned>(NR + 1)) s_tab[threadIdx.x] = static_cast<u32x4*>(tab.p[threadIdx.x]);
+  __syncthreads();
+  u32x4* p[NR + 1];
+#pragma unroll
+  for (int j = 0; j < NR + 1; ++j) p[j] = uniform_ptr(s_tab[j]);
+  const size_t n_tiles = n_vec / kThreads;  // the host passes whole tiles only
+  const size_t gx = gridDim.x;
+  unsigned pending = 0;
+  size_t first = 0;
+  for (size_t t = blockIdx.x; t < n_tiles; t += gx) {
+    const unsigned now = static_cast<unsigned>(wall_clock64());
+    u32x4 x[NR];
+#pragma unroll
+    for (int j = 0; j < NR; ++j) x[j] = ld<POL>(p[j] + t * kThreads + threadIdx.x);
+    u32x4 f = x[0];
+#pragma unroll
+    for (int j = 1; j < NR; ++j) f = f ^ x[j];
+    if (pending == 0) first = t;
+    stage[pending][threadIdx.x] = f;  // a lane only reads back its own slots
+    ++pending;
+    const bool window = (now & win.period_mask) < win.write_ticks && pending >= win.min_tiles;
+    if (pending == static_cast<unsigned>(kCap) || window) {
+      for (unsigned k = 0; k < pending; ++k)
+        st<POL>(p[NR] + (first + k * gx) * kThreads + threadIdx.x, stage[k][threadIdx.x]);
+      pending = 0;
+    }
+  }
+  for (unsigned k = 0; k < pending; ++k) st<POL>(p[NR] + (first + k * gx) * kThreads + threadIdx.x, stage[k][threadIdx.x]);
+}
+
+template <int NR>
+struct ProbeWin {
+  const PtrTable& tab; size_t n_vec; WriteWindow win; hipStream_t stream;
+  template <int POL> hipError_t operator()(unsigned) const {
+    const size_t tiles = n_vec / kThreads;
+    launch(k_probe_stream_win<NR, POL>, dim3(grid_x_for(tiles, static_cast<unsigned>(device_cu_count()))), dim3(kThreads),
+           stream, tab, n_vec, win);
+    return hipGetLastError();
+  }
+};
+
 constexpr int probe_unroll(int streams) { return streams <= 2 ? 8 : streams <= 4 ? 4 : streams <= 8 ? 2 : 1; }
 
 template <int NR, int NW>
@@ -73,6 +123,17 @@ hipError_t launch_probe_stream(const PtrTable& tab, int n_read, int n_written, s
   FTAR_PROBE(0, 1) FTAR_PROBE(0, 2) FTAR_PROBE(0, 4) FTAR_PROBE(0, 8)
   FTAR_PROBE(1, 1) FTAR_PROBE(2, 1) FTAR_PROBE(3, 1) FTAR_PROBE(4, 1) FTAR_PROBE(7, 1) FTAR_PROBE(8, 1) FTAR_PROBE(16, 1)
   FTAR_PROBE(4, 4) FTAR_PROBE(8, 8)
+#undef FTAR_PROBE
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_probe_stream_win(const PtrTable& tab, int n_read, size_t n_vec, unsigned period_ticks,
+                                   unsigned window_ticks, hipStream_t stream) {
+  const LaunchCfg cfg = launch_cfg(1, 3);
+  const WriteWindow win{period_ticks - 1u, window_ticks, 4u};
+#define FTAR_PROBE(r) \
+  if (n_read == r) return with_policy(cfg, ProbeWin<r>{tab, n_vec, win, stream});
+  FTAR_PROBE(1) FTAR_PROBE(2) FTAR_PROBE(4) FTAR_PROBE(7) FTAR_PROBE(8) FTAR_PROBE(16)
 #undef FTAR_PROBE
   return hipErrorInvalidValue;
 }

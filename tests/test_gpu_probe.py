@@ -65,3 +65,26 @@ def test_mixes_and_sizes_that_are_not_offered(B):
     with pytest.raises(B.FtarError) as e:
         B.ftar_probe_stream(odd[:1], odd[1:])           # not a multiple of 32 KiB
     assert e.value.status == B.FTAR_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("n_read", [1, 2, 4, 7, 8, 16])
+@pytest.mark.parametrize("period,window", [(4096, 512), (64, 32), (256, 256)])
+def test_windowed_probe_writes_the_xor_whatever_the_window(B, n_read, period, window):
+    words = 32 * 1024 // 4 * 4 * 300                    # 300 x 128 KiB: several tiles per workgroup, a full stage now and then
+    say("windowed probe", n_read, period, window)
+    read = _bufs(n_read, words, 200 + n_read)
+    keep = [r.clone() for r in read]
+    written = torch.zeros(words, dtype=torch.int32, device="cuda")
+    B.ftar_probe_stream_windows(read, written, period, window)
+    torch.cuda.synchronize()
+    want = keep[0].clone()
+    for r in keep[1:]:
+        want ^= r
+    assert torch.equal(written, want)
+    for r, k in zip(read, keep):
+        assert torch.equal(r, k)
+    with pytest.raises(B.FtarError):
+        B.ftar_probe_stream_windows(read, written, 1000, 10)      # the period is not a power of two
+    if n_read == 1:
+        with pytest.raises(B.FtarError):
+            B.ftar_probe_stream_windows(read + read + read, written, 4096, 512)   # 3 + 1 is not offered
