@@ -694,6 +694,8 @@ def cu_budget_report(path, B, W, torch):
             B.ftar_set_tuning(0, 0x400000)
             line.append("%.0f" % (gb / timed(None, k * per)))
             B.ftar_set_tuning(0, 0)
+        if mask_note:                                           # no reserved-unit columns to show
+            line = [line[i] for i in (0, 1, 2, 7, 8)]
         rows.append("| " + " | ".join(line) + " |")
         print(rows[-1], file=sys.stderr, flush=True)
         torch.cuda.synchronize()
@@ -747,14 +749,47 @@ def cu_budget_report(path, B, W, torch):
            "steps released at once; GB/s of algorithmic bytes (%.1f GB per all-reduce), wall time of one call. "
            "\"Reserved units\": the ring's stream is created with `hipExtStreamCreateWithCUMask` over that many "
            "compute units, spread evenly over the chip; its workgroups can only run there. " % (path, gb) + mask_note, "",
-           "| budget n | n workgroups anywhere, big tiles (default) | anywhere, small tiles | n reserved units x 1 workgroup, small tiles | x 2 | x 4 | n reserved units x 1, big tiles | 2n workgroups anywhere, small tiles | 4n anywhere, small tiles |",
-           "|---|---|---|---|---|---|---|---|---|"] + rows + [
+           ("| budget n | n workgroups anywhere, big tiles (default) | anywhere, small tiles | 2n workgroups anywhere, small tiles | 4n anywhere, small tiles |"
+            if mask_note else
+            "| budget n | n workgroups anywhere, big tiles (default) | anywhere, small tiles | n reserved units x 1 workgroup, small tiles | x 2 | x 4 | n reserved units x 1, big tiles | 2n workgroups anywhere, small tiles | 4n anywhere, small tiles |"),
+           ("|---|---|---|---|---|" if mask_note else "|---|---|---|---|---|---|---|---|---|")] + rows + [
            "", "## A GEMM next to it", "",
            "bf16 8192 x 8192 x 8192 (`torch.matmul`) 40 times on a second stream of the same priority; alone: %.3f ms." % (alone * 1e3), "",
            "| the ring | GEMM ms | change |", "|---|---|---|"] + share
-    # ---- the chunk pipeline at the paper's chunk size ---------------------------------------
+    # ---- what a few workgroups can move at all ------------------------------------------------
     del bufs, acc, a, b, o
     torch.cuda.empty_cache()
+    nbytes = 256 * W.M
+    pool = [torch.randint(-2**31, 2**31 - 1, (nbytes // 4,), dtype=torch.int32, device=dev) for _ in range(3)]
+    few = []
+    for n_read in (1, 2):
+        for threads, per_lane in ((256, 8), (256, 32), (1024, 8)):
+            if n_read == 2 and per_lane == 32:
+                continue                        # not offered: does not fit the registers
+            cells = []
+            for wg in (2, 8):
+                def probe():
+                    B.ftar_probe_stream_workgroups(pool[:n_read], pool[2], wg, threads, per_lane)
+                probe()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                probe()
+                e1.record()
+                torch.cuda.synchronize()
+                cells.append("%.1f" % ((n_read + 1) * nbytes / 1e9 / (e0.elapsed_time(e1) * 1e-3) / wg))
+            few.append("| %d + 1 | %d | %d | %s |" % (n_read, threads, per_lane, " | ".join(cells)))
+            print(few[-1], file=sys.stderr, flush=True)
+    del pool
+    torch.cuda.empty_cache()
+    out += ["", "## What one workgroup can move, whatever it keeps in flight", "",
+            "`ftar_probe_stream_workgroups`: the bare streaming kernel (16-byte lanes, ordinary loads and stores, streams of "
+            "256 MiB) on exactly 2 and 8 workgroups. GB/s of bytes read + written PER WORKGROUP, by workgroup size and by "
+            "16-byte vectors per lane and tile (loads in flight per lane). The persistent ring's worker workgroups (256 lanes, "
+            "32 vectors per lane at a small budget) are to be read against these.", "",
+            "| streams read + written | lanes per workgroup | vectors per lane and tile | GB/s per workgroup, 2 workgroups | 8 workgroups |",
+            "|---|---|---|---|---|"] + few
+    # ---- the chunk pipeline at the paper's chunk size ---------------------------------------
     S = 4 * W.M                      # 8 MB of bf16: the paper's chunk
     n, count = 16, 1024 * W.M
     bufs = [torch.empty(count, dtype=torch.bfloat16, device=dev).normal_(0, 1e-3) for _ in range(n)]

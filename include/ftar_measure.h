@@ -8,8 +8,8 @@
  *
  * Two libraries export them:
  *   libftar.so          ftar_set_tuning, ftar_time_next_launch  (hooks in the product's launch path)
- *   libftar_measure.so  ftar_probe_stream, ftar_probe_stream_windows   (bench-only; links against
- *                                                                libftar.so and honours both hooks)
+ *   libftar_measure.so  ftar_probe_stream, ftar_probe_stream_windows, ftar_probe_stream_workgroups
+ *                       (bench-only; links against libftar.so and honours both hooks)
  */
 #ifndef FTAR_MEASURE_H_
 #define FTAR_MEASURE_H_
@@ -64,6 +64,16 @@ ftar_status_t ftar_probe_stream(void* const* bufs, int n_read, int n_written, si
  * n_read in 1, 2, 4, 7, 8, 16; anything else FTAR_ERR_INVALID_ARG.  One workgroup per compute unit. */
 ftar_status_t ftar_probe_stream_windows(void* const* bufs, int n_read, size_t bytes, unsigned period_ticks,
                                         unsigned window_ticks, void* stream);
+
+/* Measurement only: n_read (1 or 2) buffers read and ONE written (the xor) by exactly n_workgroups
+ * workgroups of `threads` lanes, each lane moving vectors_per_lane 16-byte vectors per tile, with
+ * ordinary loads and stores: what a few compute units can move, next to the persistent ring at a
+ * small compute-unit budget (paper section 4.2 "Optimizations": two thread blocks).  (threads,
+ * vectors_per_lane) one of (256, 8), (1024, 8) and, with one read buffer, (256, 32); bytes a multiple of threads *
+ * vectors_per_lane * 16; n_workgroups 1..4096; anything else FTAR_ERR_INVALID_ARG.  Ignores
+ * ftar_set_tuning; honours ftar_time_next_launch. */
+ftar_status_t ftar_probe_stream_workgroups(void* const* bufs, int n_read, size_t bytes, unsigned n_workgroups,
+                                           unsigned threads, unsigned vectors_per_lane, void* stream);
 
 #ifdef __cplusplus
 }

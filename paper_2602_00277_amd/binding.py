@@ -56,7 +56,7 @@ EXPORTS = [
 # every symbol include/ftar_measure.h declares: measurement hooks in libftar.so, probe kernels in
 # the bench-only libftar_measure.so
 MEASURE_HOOKS = ["ftar_set_tuning", "ftar_time_next_launch"]
-MEASURE_EXPORTS = ["ftar_probe_stream", "ftar_probe_stream_windows"]
+MEASURE_EXPORTS = ["ftar_probe_stream", "ftar_probe_stream_windows", "ftar_probe_stream_workgroups"]
 MEASURE_LIB_PATH = os.path.join(_PKG, "libftar_measure.so")
 
 _lib = None
@@ -185,6 +185,9 @@ def measure_lib():
     M.ftar_probe_stream_windows.restype = ctypes.c_int
     M.ftar_probe_stream_windows.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_uint,
                                             ctypes.c_uint, ctypes.c_void_p]
+    M.ftar_probe_stream_workgroups.restype = ctypes.c_int
+    M.ftar_probe_stream_workgroups.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_uint,
+                                               ctypes.c_uint, ctypes.c_uint, ctypes.c_void_p]
     _measure_lib = M
     return M
 
@@ -450,6 +453,20 @@ def ftar_probe_stream_windows(read: Sequence[torch.Tensor], written: torch.Tenso
                                                  _stream_handle(stream))
     if st != FTAR_OK:
         raise FtarError(st, "ftar_probe_stream_windows")
+
+
+def ftar_probe_stream_workgroups(read: Sequence[torch.Tensor], written: torch.Tensor, n_workgroups: int,
+                                 threads: int = 256, vectors_per_lane: int = 8, stream=None) -> None:
+    """Measurement only: the bare streaming kernel on exactly n_workgroups workgroups."""
+    bufs = list(read) + [written]
+    nbytes = bufs[0].numel() * bufs[0].element_size()
+    for b in bufs:
+        if not b.is_cuda or not b.is_contiguous() or b.numel() * b.element_size() != nbytes:
+            raise ValueError("probe buffers must be contiguous GPU tensors of one size")
+    st = measure_lib().ftar_probe_stream_workgroups(_ptr_array(bufs), len(read), nbytes, n_workgroups, threads,
+                                                    vectors_per_lane, _stream_handle(stream))
+    if st != FTAR_OK:
+        raise FtarError(st, "ftar_probe_stream_workgroups")
 
 
 def ftar_set_tuning(blocks_per_cu: int = 0, flags: int = 0) -> None:

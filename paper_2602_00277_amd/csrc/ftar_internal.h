@@ -177,6 +177,11 @@ hipError_t launch_probe_stream(const PtrTable& tab, int n_read, int n_written, s
 hipError_t launch_probe_stream_win(const PtrTable& tab, int n_read, size_t n_vec, unsigned period_ticks,
                                    unsigned window_ticks, hipStream_t stream);
 
+// Measurement only: n_read (1 or 2) streams read and one written by n_workgroups workgroups of
+// `threads` lanes that move `per_lane` 16-byte vectors per lane and tile.
+hipError_t launch_probe_few(const PtrTable& tab, int n_read, size_t n_vec, unsigned n_workgroups, unsigned threads,
+                            unsigned per_lane, hipStream_t stream);
+
 }  // namespace ftar
 
 #endif  // FTAR_INTERNAL_H_

@@ -44,4 +44,21 @@ ftar_status_t ftar_probe_stream_windows(void* const* bufs, int n_read, size_t by
   return e == hipSuccess ? FTAR_OK : FTAR_ERR_DEVICE;
 }
 
+ftar_status_t ftar_probe_stream_workgroups(void* const* bufs, int n_read, size_t bytes, unsigned n_workgroups,
+                                           unsigned threads, unsigned vectors_per_lane, void* stream) {
+  if (!bufs || n_read < 1 || n_read > 2 || bytes == 0 || n_workgroups == 0 || n_workgroups > 4096 || threads == 0 ||
+      vectors_per_lane == 0 || bytes % (static_cast<size_t>(threads) * vectors_per_lane * 16) != 0)
+    return FTAR_ERR_INVALID_ARG;
+  PtrTable tab;
+  std::memset(&tab, 0, sizeof(tab));
+  for (int j = 0; j < n_read + 1; ++j) {
+    if (!bufs[j] || reinterpret_cast<uintptr_t>(bufs[j]) % 16 != 0) return FTAR_ERR_INVALID_ARG;
+    tab.p[j] = bufs[j];
+  }
+  hipError_t e = launch_probe_few(tab, n_read, bytes / 16, n_workgroups, threads, vectors_per_lane,
+                                  static_cast<hipStream_t>(stream));
+  if (e == hipErrorInvalidValue) return FTAR_ERR_INVALID_ARG;
+  return e == hipSuccess ? FTAR_OK : FTAR_ERR_DEVICE;
+}
+
 }  // extern "C"

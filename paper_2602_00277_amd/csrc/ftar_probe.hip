@@ -94,6 +94,35 @@ struct ProbeWin {
   }
 };
 
+// The same mix on a given number of workgroups of THREADS lanes, U vectors per lane and tile,
+// ordinary loads and stores: what a few compute units can move, whatever is in flight.
+template <int NR, int NW, int U, int THREADS>
+__global__ void __launch_bounds__(THREADS)
+k_probe_few(PtrTable tab, size_t n_vec) {
+  u32x4* p[NR + NW];
+#pragma unroll
+  for (int j = 0; j < NR + NW; ++j) p[j] = static_cast<u32x4*>(tab.p[j]);
+  constexpr size_t kTile = static_cast<size_t>(THREADS) * U;
+  const size_t n_tiles = n_vec / kTile;  // the host passes whole tiles only
+  for (size_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+    const size_t v = t * kTile + threadIdx.x;
+    u32x4 x[U][NR];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int j = 0; j < NR; ++j) x[u][j] = p[j][v + u * THREADS];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      u32x4 f = x[u][0];
+#pragma unroll
+      for (int j = 1; j < NR; ++j) f = f ^ x[u][j];
+#pragma unroll
+      for (int w = 0; w < NW; ++w) p[NR + w][v + u * THREADS] = f;
+    }
+  }
+}
+
 constexpr int probe_unroll(int streams) { return streams <= 2 ? 8 : streams <= 4 ? 4 : streams <= 8 ? 2 : 1; }
 
 template <int NR, int NW>
@@ -134,6 +163,21 @@ hipError_t launch_probe_stream_win(const PtrTable& tab, int n_read, size_t n_vec
 #define FTAR_PROBE(r) \
   if (n_read == r) return with_policy(cfg, ProbeWin<r>{tab, n_vec, win, stream});
   FTAR_PROBE(1) FTAR_PROBE(2) FTAR_PROBE(4) FTAR_PROBE(7) FTAR_PROBE(8) FTAR_PROBE(16)
+#undef FTAR_PROBE
+  return hipErrorInvalidValue;
+}
+
+// n_read 1 or 2, one written stream; (threads, vectors per lane) one of (256, 8), (1024, 8) and, for one
+// read stream, (256, 32).
+hipError_t launch_probe_few(const PtrTable& tab, int n_read, size_t n_vec, unsigned n_workgroups, unsigned threads,
+                            unsigned per_lane, hipStream_t stream) {
+#define FTAR_PROBE(r, t, u)                                                                              \
+  if (n_read == r && threads == t && per_lane == u) {                                                    \
+    launch(k_probe_few<r, 1, u, t>, dim3(n_workgroups), dim3(t), stream, tab, n_vec);                    \
+    return hipGetLastError();                                                                            \
+  }
+  FTAR_PROBE(1, 256, 8) FTAR_PROBE(1, 256, 32) FTAR_PROBE(1, 1024, 8)
+  FTAR_PROBE(2, 256, 8) FTAR_PROBE(2, 1024, 8)  // (2, 256, 32) would not fit the registers
 #undef FTAR_PROBE
   return hipErrorInvalidValue;
 }

@@ -88,3 +88,28 @@ def test_windowed_probe_writes_the_xor_whatever_the_window(B, n_read, period, wi
     if n_read == 1:
         with pytest.raises(B.FtarError):
             B.ftar_probe_stream_windows(read + read + read, written, 4096, 512)   # 3 + 1 is not offered
+
+
+@pytest.mark.parametrize("n_read", [1, 2])
+@pytest.mark.parametrize("threads,per_lane", [(256, 8), (256, 32), (1024, 8)])
+@pytest.mark.parametrize("n_workgroups", [1, 2, 7])
+def test_few_workgroup_probe_writes_the_xor(B, n_read, threads, per_lane, n_workgroups):
+    words = threads * per_lane * 4 * 19               # 19 tiles: uneven over 2 and 7 workgroups
+    say("few-workgroup probe", n_read, threads, per_lane, n_workgroups)
+    read = _bufs(n_read, words, 300 + n_read)
+    keep = [r.clone() for r in read]
+    written = torch.zeros(words, dtype=torch.int32, device="cuda")
+    if n_read == 2 and per_lane == 32:                # not offered: two streams of 32 vectors do not fit the registers
+        with pytest.raises(B.FtarError):
+            B.ftar_probe_stream_workgroups(read, written, n_workgroups, threads, per_lane)
+        return
+    B.ftar_probe_stream_workgroups(read, written, n_workgroups, threads, per_lane)
+    torch.cuda.synchronize()
+    want = keep[0].clone()
+    for r in keep[1:]:
+        want ^= r
+    assert torch.equal(written, want)
+    with pytest.raises(B.FtarError):
+        B.ftar_probe_stream_workgroups(read, written, n_workgroups, 512, 8)        # not an offered shape
+    with pytest.raises(B.FtarError):
+        B.ftar_probe_stream_workgroups([r[:-4] for r in read], written[:-4], n_workgroups, threads, per_lane)   # not whole tiles
