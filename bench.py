@@ -971,6 +971,13 @@ def main():
     n_buckets = (count + bucket_elems - 1) // bucket_elems
     bmasks = W.bucket_masks(n, n_buckets, 0.9, seed=w.seed)
 
+    # a plain copy of known size before anything else: under `rocprofv3 --pmc` the scale factors of
+    # FETCH_SIZE and WRITE_SIZE come from this first copy kernel of the run (128 MiB read and written)
+    marker = torch.empty(128 * W.M, dtype=torch.uint8, device=dev)
+    torch.empty_like(marker).copy_(marker)
+    torch.cuda.synchronize()
+    del marker
+
     t_setup = time.perf_counter()
     bufs = W.draw_replicas(w, dev)
     out = torch.empty(count, dtype=w.dtype, device=dev)

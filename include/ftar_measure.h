@@ -32,7 +32,8 @@ extern "C" {
  *   0x80          no write windows in the many-source reductions
  *   bits 8..11    vectors per lane and tile in the ring step kernels (2, 4 or 8)
  *   bits 12..15   log2 of the write-window period in 10 ns ticks; bits 16..19: log2(period / window)
- *   0x100000      write windows at any output size
+ *   0x100000      write windows whenever the kernel has them (also for outputs below 16 MiB and, with four
+ *                 or five sources, below 256 MiB)
  *   0x200000      bf16 ReduceScatter lanes take 8 elements (16-byte loads, two partial-sum vectors)
  *   0x400000      the persistent ring keeps its small tile also with few workgroups
  *   bits 24..27   log2 of the MiB of traffic per launch of a long ring step */

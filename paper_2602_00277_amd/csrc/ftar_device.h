@@ -279,8 +279,9 @@ __device__ __forceinline__ void sum_tile_values(T* const (&src)[NSRC], float sca
 // only inside windows of the 100 MHz wall clock, which is the same for all compute units: the
 // whole chip then reads for tens of microseconds and writes in one short burst, with no
 // communication between workgroups (8 + 1 streams of 1 GiB: 5.7 -> 6.5 TB/s; of 3 GiB: 5.6 ->
-// 6.4).  It pays from four sources on; with a third or more of the bytes written the LDS cannot
-// hold a long enough period and nothing is gained.  Nor when the result goes back into one of the
+// 6.4), always with non-temporal stores.  It pays from four sources on (from six on at any size,
+// see reduce_window); with a third or more of the bytes written the LDS cannot hold a long enough
+// period and nothing is gained.  Nor when the result goes back into one of the
 // buffers just read: the one-pass ReduceScatter loses with windows (8 x 1 Gi bf16: 5.6 TB/s plain,
 // 4.9 staged) and keeps its plain stores.  A full stage is written out at once, whatever the clock
 // says, so progress never depends on the clock.

@@ -365,16 +365,22 @@ struct ReduceFixedCvt {
 };
 
 // When the write windows are used and with which period (tuning flags for measurement: 0x80 never,
-// 0x100000 at any size; bits 12..15 = log2 of the period in ticks, bits 16..19 = log2 of period / window).
-// From four sources on, and only when the whole output is too large for the Infinity Cache: a smaller
-// output is absorbed there whenever it is written, and staging it only delays it (8 x 64 Mi bf16,
-// fp32 result: 6.1 TB/s plain, 5.5 with windows).  The period grows with the number of sources: the
-// stage must hold what one period produces.
+// 0x100000 whenever the kernel can; bits 12..15 = log2 of the period in ticks, bits 16..19 = log2 of
+// period / window).  From six sources on they pay at every size beyond a few tiles per workgroup,
+// together with non-temporal stores (8 x 64 Mi bf16, replica 3 dead: 6.16 -> 6.75 TB/s; 8 x 16 Mi:
+// 5.46 -> 5.84; with ordinary stores, which a small output would otherwise get, nothing is gained;
+// per-bucket masks, 8 x 64 Mi bf16: 5.8 -> 6.5).
+// With four or five sources only when the whole output is too large for the Infinity Cache (4 + 1
+// streams of 128 MiB: 6.3 TB/s plain, 5.7 staged; of 1 GiB: 5.5 and 5.7).  The period grows with
+// the number of sources: the stage must hold what one period produces.
 WriteWindow reduce_window(int n_src, size_t out_bytes) {
   const int flags = current_tuning().flags;
   WriteWindow w{0u, 0u, 0u};
   if (n_src < 4 || n_src > 16 || (flags & 0x80) != 0) return w;
-  if (out_bytes <= 256 * kMiB && (flags & 0x100000) == 0) return w;
+  if ((flags & 0x100000) == 0) {
+    if (n_src < 6 && out_bytes <= 256 * kMiB) return w;
+    if (out_bytes < 16 * kMiB) return w;
+  }
   int lg = n_src >= 6 ? 12 : 11;  // 41 us, 20 us
   int div = n_src >= 6 ? 3 : 2;   // window = period / 8, period / 4
   if ((flags >> 12) & 0xf) lg = (flags >> 12) & 0xf;
@@ -418,7 +424,8 @@ struct ReduceWin {
 template <typename TI, typename TO>
 hipError_t reduce_masked_cvt(const PtrTable& live, int N, size_t count, bool vec, void* out, float scale,
                              float zterm, size_t whole_out_bytes, const WriteWindow& win, hipStream_t stream) {
-  const LaunchCfg cfg = reduce_cfg(N, whole_out_bytes);
+  // staged results go out with non-temporal stores whatever the size (see reduce_window)
+  const LaunchCfg cfg = vec && win.period_mask != 0 ? launch_cfg(1, 3) : reduce_cfg(N, whole_out_bytes);
   TO* o = static_cast<TO*>(out);
   if (vec && win.period_mask != 0)
     return with_policy(cfg, ReduceWin<TI, 4, (__is_same(TI, float) ? 3 : 2)>{live, N, count, out, scale, zterm, win, stream});
@@ -432,7 +439,7 @@ hipError_t reduce_masked_typed(const PtrTable& live, int N, size_t count, bool v
                                float scale, float zterm, size_t whole_out_bytes, const WriteWindow& win,
                                hipStream_t stream) {
   T* o = static_cast<T*>(out);
-  const LaunchCfg cfg = reduce_cfg(N, whole_out_bytes);
+  const LaunchCfg cfg = vec && win.period_mask != 0 ? launch_cfg(1, 3) : reduce_cfg(N, whole_out_bytes);
   if (vec && win.period_mask != 0)
     return with_policy(cfg, ReduceWin<T, VECW, 0>{live, N, count, out, scale, zterm, win, stream});
   if (vec && N <= 16) return with_policy(cfg, ReduceFixed<T, VECW>{live, N, count, o, scale, zterm, stream});
@@ -472,8 +479,9 @@ hipError_t bucketed_typed(const PtrTable& all, int n_replicas, const BucketTable
                           int n_buckets, size_t first_elem, size_t bucket_elems, size_t count,
                           const ScaleTable& scales, bool vec, void* out, hipStream_t stream) {
   T* o = static_cast<T*>(out);
-  const LaunchCfg cfg = bucketed_cfg(n_replicas, count * sizeof(T));
   const WriteWindow win = reduce_window(n_replicas, count * sizeof(T));
+  // staged results: non-temporal stores whatever the size (8 x 64 Mi bf16, buckets of 25 Mi: 5.8 -> 6.5 TB/s)
+  const LaunchCfg cfg = vec && win.period_mask != 0 ? launch_cfg(1, 3) : bucketed_cfg(n_replicas, count * sizeof(T));
   if (vec)
     return with_policy(cfg, Bucketed<T, VECW>{all, n_replicas, masks, n_buckets, first_elem, bucket_elems, count,
                                               scales, o, win, stream});
