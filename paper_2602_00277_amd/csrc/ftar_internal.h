@@ -57,6 +57,7 @@ struct DevCtrl {  // device memory, zeroed on the stream before every launch
   unsigned int verdict;         // 0 run, 1 a wait timed out, 2 cancelled, 3 skipped: everybody leaves
   unsigned int exited;          // workers that have left the kernel
   unsigned int min_unit;        // gate units finished by EVERY worker, maintained by the relay
+  unsigned int align_count;     // arrivals at the soft barriers inside long steps (a performance hint only)
   unsigned int worker_unit[kMaxPersistentBlocks];  // gate units finished by worker b
 };
 

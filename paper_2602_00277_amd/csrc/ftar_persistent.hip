@@ -215,6 +215,24 @@ __device__ __forceinline__ bool wait_all_done(const WaitCtx& w, unsigned units, 
   return true;
 }
 
+// Soft barrier inside a long step, a performance hint only: the workers of one launch never wait
+// for each other, and over a gigabyte of traffic they drift apart, the window of addresses in use
+// widens and the DRAM sees less locality (the step kernels avoid that by going out as several
+// launches).  Every worker counts itself in at its n-th boundary and waits, bounded, until all
+// have; nobody depends on it, and a worker that has left only costs the others the bound.
+__device__ __forceinline__ void soft_align(DevCtrl* mirror, unsigned n_workers, unsigned nth) {
+  if (threadIdx.x == 0) {
+    __hip_atomic_fetch_add(&mirror->align_count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned target = nth * n_workers;
+    for (int spin = 0; spin < 2000; ++spin) {
+      if (static_cast<int>(dev_load(&mirror->align_count) - target) >= 0) break;
+      if (dev_load(&mirror->verdict) != 0) break;
+      __builtin_amdgcn_s_sleep(2);
+    }
+  }
+  __syncthreads();
+}
+
 // ---- rows of chunks ------------------------------------------------------------------
 // Tile order of one slot when the gate unit is a row of chunks: row after row, inside a row
 // portion after portion, inside a chunk tile after tile (a tile never crosses a chunk's end).
@@ -354,7 +372,9 @@ __global__ void __launch_bounds__(kThreads)
 k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable tile_last, int N, float* acc,
                   float scale, Ctrl* ctrl, CallRec* rec, unsigned long long epoch, DevCtrl* mirror,
                   unsigned long long timeout_ticks, unsigned long long max_spins, unsigned flags,
-                  unsigned long long zpos) {
+                  unsigned long long zpos, unsigned long long run_tiles) {
+  // run_tiles: 0, or the tiles (a multiple of the number of workers, so that a tile keeps its
+  // worker) between two soft barriers inside a step
   __shared__ T* s_tab[kMaxReplicas];
   __shared__ unsigned long long s_seg[2][kMaxReplicas + 1], s_tile[2][kMaxReplicas + 1];
   __shared__ unsigned long long s_word;  // what lane 0 saw in a wait
@@ -386,6 +406,7 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
   const unsigned rows_full = CH ? geom.rows_full : 1u, rows_last = CH ? geom.rows_last : 1u;
   const unsigned units_full = n_steps * rows_full;  // per full partition
   unsigned released = 0;  // units [0, released) are known to be released
+  unsigned n_aligned = 0;  // soft barriers inside steps passed so far (the same sequence in every worker)
   // acc handover before a shorter last partition (see above): every worker must have finished
   // the ReduceScatter phase of the partition before
   const bool handover = N >= 3 && geom.n_parts >= 2 && geom.seg_last.begin[N] != geom.part_elems;
@@ -427,23 +448,34 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
           if (unit >= released && !wait_released(wc, unit, &released)) return;
           ring_one_tile<T, VEC, U, POL>(s_tab, N, step, t.k, t.begin, t.rem, acc, scale, off, zpos);
         }
-      } else if (step < N - 1) {
-        if (N == 2)
-          ring_reduce_pass<T, VEC, kRsOnly, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off,
-                                                    zpos);
-        else if (step == 0)
-          ring_reduce_pass<T, VEC, kRsFirst, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off,
-                                                     zpos);
-        else if (step == N - 2)
-          ring_reduce_pass<T, VEC, kRsLast, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off,
-                                                    zpos);
-        else
-          ring_reduce_pass<T, VEC, kRsMid, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off,
-                                                   zpos);
       } else {
-        // same tiles, widest copy: kThreads*U*VEC == kThreads*(U*VEC/CV)*CV
-        constexpr int CV = VEC == 1 ? 1 : 16 / static_cast<int>(sizeof(T));
-        ring_allgather_pass<T, CV, U * VEC / CV, POL>(s_tab, seg, til, N, step - (N - 1), worker, n_workers, off);
+        const size_t slot_tiles = uniform_u64(til[N]);
+        const size_t run = static_cast<size_t>(run_tiles);
+        for (size_t g0 = 0;;) {
+          const size_t g1 = run_tiles == 0 || slot_tiles - g0 < run + run / 2 ? slot_tiles : g0 + run;  // no short last run
+          if (step < N - 1) {
+            if (N == 2)
+              ring_reduce_pass<T, VEC, kRsOnly, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off,
+                                                        zpos, g0, g1);
+            else if (step == 0)
+              ring_reduce_pass<T, VEC, kRsFirst, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers,
+                                                         off, zpos, g0, g1);
+            else if (step == N - 2)
+              ring_reduce_pass<T, VEC, kRsLast, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off,
+                                                        zpos, g0, g1);
+            else
+              ring_reduce_pass<T, VEC, kRsMid, U, POL>(s_tab, seg, til, N, step, acc, scale, worker, n_workers, off,
+                                                       zpos, g0, g1);
+          } else {
+            // same tiles, widest copy: kThreads*U*VEC == kThreads*(U*VEC/CV)*CV
+            constexpr int CV = VEC == 1 ? 1 : 16 / static_cast<int>(sizeof(T));
+            ring_allgather_pass<T, CV, U * VEC / CV, POL>(s_tab, seg, til, N, step - (N - 1), worker, n_workers, off,
+                                                          g0, g1);
+          }
+          if (g1 >= slot_tiles) break;
+          g0 = g1;
+          soft_align(mirror, n_workers, ++n_aligned);
+        }
       }
       // A block-wide barrier with workgroup release/acquire is needed (a) before the first
       // AllGather step, whose 16-byte lanes read what other lanes of the block wrote in the last
@@ -517,9 +549,20 @@ struct RingPersistent {
     const unsigned workers = n_blocks + 1 > capacity ? capacity - 1 : n_blocks;
     hipLaunchKernelGGL(k_clear_mirror, dim3(1), dim3(256), 0, stream, mirror);
     const dim3 grid(workers + 1), block(kThreads);  // the relay + the workers
+    // With FTAR_PERSIST_ALIGN a long step also gets soft barriers inside, one per 256 Mi elements, in
+    // whole rounds of the workers (8 x 2e9 bf16: 5.35 -> 5.65 TB/s; shorter runs cost more than they
+    // give: every barrier waits for the slowest worker).  Tuning bits 24..27: log2 of the Mi elements.
+    unsigned long long run_tiles = 0;
+    if (!CH && (flags & FTAR_PERSIST_ALIGN) != 0 && (current_tuning().flags & 0x40) == 0) {
+      const int lg = (current_tuning().flags >> 24) & 0xf;
+      const size_t run_elems = static_cast<size_t>(1) << (lg ? 20 + lg : 28);
+      const size_t tile_elems = static_cast<size_t>(kThreads) * U * VEC;
+      run_tiles = (run_elems / tile_elems + workers - 1) / workers * workers;
+      if (run_tiles < 4ull * workers) run_tiles = 4ull * workers;
+    }
     // one spin of a wait is a sleep plus two loads from device memory: well over 0.1 us
     launch(k_ring_persistent<T, VEC, POL, U, CH>, grid, block, stream, ring, geom, tile_full, tile_last, N, acc,
-           scale, ctrl, rec, epoch, mirror, timeout_ticks, timeout_ticks / 10 + 100000, flags, zpos);
+           scale, ctrl, rec, epoch, mirror, timeout_ticks, timeout_ticks / 10 + 100000, flags, zpos, run_tiles);
     return hipGetLastError();
   }
 };

@@ -287,3 +287,47 @@ def test_shorter_last_partition_reuses_acc_only_after_everybody_is_done_with_it(
         assert ctrl.result() == (B.FTAR_OK, plan.n_slots)
         for r in range(n):
             assert_same(host(bufs[r]), want if (mask >> r) & 1 else orig[r], "rep %d buf %d" % (rep, r))
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("n_blocks,flags", [(3, 2), (16, 2), (16, 3), (300, 2)])
+def test_soft_barriers_inside_long_steps_change_nothing(B, oracle, dtype, n_blocks, flags):
+    # FTAR_PERSIST_ALIGN cuts a long step into runs of tiles with a bounded soft barrier between them; the tuning
+    # makes the runs short (2 Mi elements) so that a step of this size has several, with a merged last one
+    n, mask, chunk = 8, 0b11110111, 1024
+    count = 7 * chunk * 800 + 333
+    say("persistent ring, soft barriers inside steps", dtype, n_blocks, flags)
+    bufs = rand_bufs(n, count, dtype, seed=61, dist="student_t3", mask=mask)
+    orig = [host(b) for b in bufs]
+    plan = B.ftar_plan(n, mask, count, chunk, dtype)
+    acc = torch.empty(count, dtype=torch.float32, device="cuda")
+    ctrl = B.ftar_ctrl_create()
+    try:
+        B.ftar_set_tuning(0, 1 << 24)
+        B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=n_blocks, timeout_us=5_000_000, flags=flags)
+        B.ftar_set_tuning(0, 0)
+        ctrl.release(5)                                   # some steps first, the rest later
+        assert _wait_progress(ctrl, 5)
+        ctrl.release(12)
+        torch.cuda.synchronize()
+        assert ctrl.result() == (B.FTAR_OK, 12)
+        want = oracle.ring_closed_form(orig, mask, count, chunk, code(dtype))
+        for r in range(n):
+            assert_same(host(bufs[r]), want if (mask >> r) & 1 else orig[r], "buf %d" % r)
+        # a cancel while the workers wait at the gate still ends the call at once
+        bufs2 = rand_bufs(n, count, dtype, seed=62, mask=mask)
+        keep = [host(b) for b in bufs2]
+        B.ftar_set_tuning(0, 1 << 24)
+        B.ftar_ring_persistent(plan, bufs2, acc, ctrl, n_blocks=n_blocks, timeout_us=5_000_000, flags=flags)
+        B.ftar_set_tuning(0, 0)
+        ctrl.release(3)
+        assert _wait_progress(ctrl, 3)
+        ctrl.cancel()
+        torch.cuda.synchronize()
+        st, done = ctrl.result()
+        assert st == B.FTAR_ERR_STALE_PLAN and done == 3
+        for r in range(n):
+            assert_same(host(bufs2[r]), keep[r], "buf %d untouched before the last ReduceScatter step" % r)
+    finally:
+        B.ftar_set_tuning(0, 0)
+        ctrl.destroy()
