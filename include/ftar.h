@@ -337,7 +337,8 @@ ftar_status_t ftar_allreduce_onepass(const ftar_plan_t* plan, void* const* bufs,
  *               the CPU's signal would need; without it progress means "computed", and the data
  *               is guaranteed visible off the GPU once the stream has been synchronised.
  *               FTAR_PERSIST_ALIGN: workgroups that ran ahead wait (bounded) for the others after
- *               every step; a performance hint for long steps, never needed for correctness.
+ *               every step and, inside a step, after every 256 Mi elements (not with
+ *               FTAR_PERSIST_CHUNKS); a performance hint for long steps, never needed for correctness.
  *               The library sets it by itself when the partial sums of one partition exceed
  *               256 MiB (steps of hundreds of microseconds: +5..9 %; below that it costs).
  *               FTAR_PERSIST_CHUNKS: the gate unit is a row of chunks (above).
