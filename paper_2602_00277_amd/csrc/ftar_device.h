@@ -335,19 +335,20 @@ __host__ __device__ constexpr int unroll_narrow(int n_src) {
 }
 
 // ---- any number of sources (runtime N): loads in groups of 8 ---------------
-template <typename T, int VEC, int POL, typename TO = T>
-__device__ __forceinline__ void sum_any_one(T* const* s_tab, size_t base, int N, TO* out, float scale,
-                                            size_t v, float zterm) {
+// G: loads a lane has in flight; the N sources are taken G at a time, always in ascending order.
+template <typename T, int VEC, int POL, typename TO = T, int G = 8>
+__device__ __forceinline__ typename Raw<TO, VEC>::type sum_any_value(T* const* s_tab, size_t base, int N, float scale,
+                                                                     size_t v, float zterm) {
   typedef typename Raw<T, VEC>::type R;
   typedef typename Raw<TO, VEC>::type RO;
   float a[VEC];
-  for (int j0 = 0; j0 < N; j0 += 8) {
-    R raw[8];
+  for (int j0 = 0; j0 < N; j0 += G) {
+    R raw[G];
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj)
+    for (int jj = 0; jj < G; ++jj)
       if (j0 + jj < N) raw[jj] = ld<POL>(reinterpret_cast<const R*>(uniform_ptr(s_tab[j0 + jj]) + base) + v);
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj) {
+    for (int jj = 0; jj < G; ++jj) {
       if (j0 + jj < N) {
         float x[VEC];
         widen(raw[jj], x);
@@ -363,7 +364,14 @@ __device__ __forceinline__ void sum_any_one(T* const* s_tab, size_t base, int N,
   }
 #pragma unroll
   for (int e = 0; e < VEC; ++e) a[e] = (a[e] + zterm) * scale;
-  st<POL>(reinterpret_cast<RO*>(out) + v, narrow<RO, VEC>(a));
+  return narrow<RO, VEC>(a);
+}
+
+template <typename T, int VEC, int POL, typename TO = T>
+__device__ __forceinline__ void sum_any_one(T* const* s_tab, size_t base, int N, TO* out, float scale,
+                                            size_t v, float zterm) {
+  typedef typename Raw<TO, VEC>::type RO;
+  st<POL>(reinterpret_cast<RO*>(out) + v, sum_any_value<T, VEC, POL, TO>(s_tab, base, N, scale, v, zterm));
 }
 
 template <typename T, int VEC, int POL, typename TO = T>

@@ -83,6 +83,50 @@ k_reduce_masked_win(PtrTable live, void* out_, float scale, size_t count, float 
   }
 }
 
+// The same for any N up to 64: what the specialised kernel above does for up to 16 sources, for the
+// 17 to 64 that the paper's 10 to 20 replicas can reach.  One vector per lane and tile, up to 32
+// loads per lane in flight (N = 20: 5.1 TB/s with the plain kernel's groups of 8, 5.6 with windows,
+// more with all 20 loads in flight).
+template <typename T, int VEC, int POL, typename TO>
+__global__ void __launch_bounds__(kThreads)
+k_reduce_masked_any_win(PtrTable live, int N, TO* out, float scale, size_t count, float zterm, WriteWindow win) {
+  typedef typename Raw<TO, VEC>::type RO;
+  constexpr int kCap = kStageBytes / (kThreads * static_cast<int>(sizeof(RO)));
+  __shared__ RO stage[kCap][kThreads];
+  __shared__ T* s_tab[kMaxReplicas];
+  const unsigned tid = threadIdx.x;
+  if (tid < static_cast<unsigned>(N)) s_tab[tid] = static_cast<T*>(live.p[tid]);
+  __syncthreads();
+  const size_t n_vec = count / VEC;
+  const size_t n_tiles = n_vec / kThreads;
+  const size_t gx = gridDim.x;
+  RO* o = reinterpret_cast<RO*>(out);
+  unsigned pending = 0;
+  size_t first = 0;
+  for (size_t t = blockIdx.x; t < n_tiles; t += gx) {
+    const unsigned now = static_cast<unsigned>(wall_clock64());
+    const RO r = sum_any_value<T, VEC, POL, TO, 32>(s_tab, 0, N, scale, t * kThreads + tid, zterm);
+    if (pending == 0) first = t;
+    stage[pending][tid] = r;
+    ++pending;
+    const bool window = (now & win.period_mask) < win.write_ticks && pending >= win.min_tiles;
+    if (pending == static_cast<unsigned>(kCap) || window) {
+      for (unsigned k = 0; k < pending; ++k) st<POL>(o + (first + k * gx) * kThreads + tid, stage[k][tid]);
+      pending = 0;
+    }
+  }
+  for (unsigned k = 0; k < pending; ++k) st<POL>(o + (first + k * gx) * kThreads + tid, stage[k][tid]);
+  // whole vectors past the last full tile and the last count % VEC elements: one workgroup, directly
+  if (blockIdx.x == n_tiles % gx) {
+    const size_t v = n_tiles * kThreads + tid;
+    if (v < n_vec) sum_any_one<T, VEC, POL, TO>(s_tab, 0, N, out, scale, v, zterm);
+    if constexpr (VEC > 1) {
+      const size_t e = n_vec * VEC + tid;
+      if (e < count) sum_any_one<T, 1, POL, TO>(s_tab, 0, N, out, scale, e, zterm);
+    }
+  }
+}
+
 // The same with a result of the other element type, 4 elements per lane and vector: an fp32 result
 // from bf16 inputs (8-byte loads, 16-byte stores) or a bf16 result from fp32 inputs (16-byte loads,
 // 8-byte stores).  TI = input type; out is float* for bf16 inputs and bf16* for fp32 inputs.
@@ -212,10 +256,9 @@ __device__ __forceinline__ void bucket_tile_n_staged(T* const* s_tab, float scal
   }
 }
 
-// k_reduce_bucketed with write windows (see WriteWindow): whole tiles of buckets with up to 16 live
-// replicas leave their results in the LDS stage; they are written out inside the clock windows or
-// when the stage is full.  Short tiles (the end of a bucket) and buckets with more live replicas are
-// written directly, as in the plain kernel.  One workgroup per compute unit.
+// k_reduce_bucketed with write windows (see WriteWindow): whole tiles leave their results in the LDS
+// stage; they are written out inside the clock windows or when the stage is full.  Short tiles (the
+// end of a bucket) are written directly, as in the plain kernel.  One workgroup per compute unit.
 template <typename T, int VEC, int POL>
 __global__ void __launch_bounds__(kThreads)
 k_reduce_bucketed_win(PtrTable all, int n_replicas, BucketTable masks, ScaleTable scales,
@@ -266,7 +309,12 @@ k_reduce_bucketed_win(PtrTable all, int n_replicas, BucketTable masks, ScaleTabl
         FTAR_CASE(8) FTAR_CASE(9) FTAR_CASE(10) FTAR_CASE(11) FTAR_CASE(12) FTAR_CASE(13)
         FTAR_CASE(14) FTAR_CASE(15) FTAR_CASE(16)
 #undef FTAR_CASE
-        default: staged = false; break;
+        default:  // 17 to 64 live replicas: the generic sum, all of a vector's loads in flight (up to 32)
+#pragma unroll
+          for (int u = 0; u < kBucketUnroll; ++u)
+            lane_stage[u * kThreads] =
+                sum_any_value<T, VEC, POL, T, 32>(s_tab, begin, N, scale, tid + static_cast<size_t>(u) * kThreads, -0.0f);
+          break;
       }
     }
     if (staged) {
@@ -376,13 +424,13 @@ struct ReduceFixedCvt {
 WriteWindow reduce_window(int n_src, size_t out_bytes) {
   const int flags = current_tuning().flags;
   WriteWindow w{0u, 0u, 0u};
-  if (n_src < 4 || n_src > 16 || (flags & 0x80) != 0) return w;
+  if (n_src < 4 || n_src > kMaxReplicas || (flags & 0x80) != 0) return w;
   if ((flags & 0x100000) == 0) {
     if (n_src < 6 && out_bytes <= 256 * kMiB) return w;
     if (out_bytes < 16 * kMiB) return w;
   }
-  int lg = n_src >= 6 ? 12 : 11;  // 41 us, 20 us
-  int div = n_src >= 6 ? 3 : 2;   // window = period / 8, period / 4
+  int lg = n_src > 16 ? 13 : n_src >= 6 ? 12 : 11;  // 82 us, 41 us, 20 us
+  int div = n_src >= 6 ? 3 : 2;                     // window = period / 8, period / 4
   if ((flags >> 12) & 0xf) lg = (flags >> 12) & 0xf;
   if ((flags >> 16) & 0xf) div = (flags >> 16) & 0xf;
   w.period_mask = (1u << lg) - 1u;
@@ -420,6 +468,17 @@ struct ReduceWin {
   }
 };
 
+template <typename T, int VEC, typename TO>
+struct ReduceAnyWin {
+  const PtrTable& live; int N; size_t count; TO* out; float scale; float zterm; WriteWindow win; hipStream_t stream;
+  template <int POL> hipError_t operator()(unsigned) const {
+    const size_t tiles = count / VEC / kThreads;
+    const dim3 grid(grid_x_for(tiles, static_cast<unsigned>(device_cu_count()))), block(kThreads);
+    launch(k_reduce_masked_any_win<T, VEC, POL, TO>, grid, block, stream, live, N, out, scale, count, zterm, win);
+    return hipGetLastError();
+  }
+};
+
 // whole_out_bytes: output size of the whole call (a long call goes out as several launches)
 template <typename TI, typename TO>
 hipError_t reduce_masked_cvt(const PtrTable& live, int N, size_t count, bool vec, void* out, float scale,
@@ -427,6 +486,8 @@ hipError_t reduce_masked_cvt(const PtrTable& live, int N, size_t count, bool vec
   // staged results go out with non-temporal stores whatever the size (see reduce_window)
   const LaunchCfg cfg = vec && win.period_mask != 0 ? launch_cfg(1, 3) : reduce_cfg(N, whole_out_bytes);
   TO* o = static_cast<TO*>(out);
+  if (vec && win.period_mask != 0 && N > 16)
+    return with_policy(cfg, ReduceAnyWin<TI, 4, TO>{live, N, count, o, scale, zterm, win, stream});
   if (vec && win.period_mask != 0)
     return with_policy(cfg, ReduceWin<TI, 4, (__is_same(TI, float) ? 3 : 2)>{live, N, count, out, scale, zterm, win, stream});
   if (vec && N <= 16) return with_policy(cfg, ReduceFixedCvt<TI>{live, N, count, out, scale, zterm, stream});
@@ -440,6 +501,8 @@ hipError_t reduce_masked_typed(const PtrTable& live, int N, size_t count, bool v
                                hipStream_t stream) {
   T* o = static_cast<T*>(out);
   const LaunchCfg cfg = vec && win.period_mask != 0 ? launch_cfg(1, 3) : reduce_cfg(N, whole_out_bytes);
+  if (vec && win.period_mask != 0 && N > 16)
+    return with_policy(cfg, ReduceAnyWin<T, VECW, T>{live, N, count, o, scale, zterm, win, stream});
   if (vec && win.period_mask != 0)
     return with_policy(cfg, ReduceWin<T, VECW, 0>{live, N, count, out, scale, zterm, win, stream});
   if (vec && N <= 16) return with_policy(cfg, ReduceFixed<T, VECW>{live, N, count, o, scale, zterm, stream});

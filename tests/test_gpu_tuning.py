@@ -133,7 +133,8 @@ def test_long_reduce_goes_out_in_several_launches_with_the_same_bits_and_one_bra
     hip.hipEventDestroy(b)
 
 
-@pytest.mark.parametrize("n,mask", [(4, 0xF), (6, 0b110111), (8, 0xFF), (16, 0xFFFF), (16, 0xBFFD)])
+@pytest.mark.parametrize("n,mask", [(4, 0xF), (6, 0b110111), (8, 0xFF), (16, 0xFFFF), (16, 0xBFFD), (17, 0x1FFFF),
+                                    (20, 0xFFFFF), (33, 0x1FFFFF7FD), (64, (1 << 64) - 1)])
 def test_write_windows_give_the_same_bits(B, oracle, n, mask):
     # the staged kernel (results held in LDS, written out in windows of the wall clock) against the plain
     # one and the oracle: several tiles per workgroup, a ragged tail, every pair of element types
