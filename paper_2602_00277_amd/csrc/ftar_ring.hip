@@ -71,23 +71,24 @@ __device__ __forceinline__ void onepass_tile(T* const (&buf)[N], float scale, si
   }
 }
 
-// Any N (runtime): loads in groups of 8 in ring order starting at position k, then N stores.
-template <typename T, int VEC, int POL, bool OWNER>
+// Any N (runtime): loads in groups of G in ring order starting at position k, then N stores.
+template <typename T, int VEC, int POL, bool OWNER, int G = 8>
 __device__ __forceinline__ void onepass_any_one(T* const* s_tab, int N, int k, size_t base, float scale,
                                                 size_t v, unsigned long long zpos) {
   typedef typename Raw<T, VEC>::type R;
   float a[VEC];
-  for (int j0 = 0; j0 < N; j0 += 8) {
-    R raw[8];
+  for (int j0 = 0; j0 < N; j0 += G) {
+    R raw[G];
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj)
+    for (int jj = 0; jj < G; ++jj)
       if (j0 + jj < N) {
-        const int p = (k + j0 + jj) % N;
+        int p = k + j0 + jj;  // < 2N: one conditional subtraction instead of a division per load
+        if (p >= N) p -= N;
         if ((zpos >> p) & 1ull) raw[jj] = R{};
         else raw[jj] = ld<POL>(reinterpret_cast<const R*>(uniform_ptr(s_tab[p]) + base) + v);
       }
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj) {
+    for (int jj = 0; jj < G; ++jj) {
       if (j0 + jj < N) {
         float x[VEC];
         widen(raw[jj], x);
@@ -111,12 +112,12 @@ __device__ __forceinline__ void onepass_any_one(T* const* s_tab, int N, int k, s
   }
 }
 
-template <typename T, int VEC, int POL, bool OWNER>
+template <typename T, int VEC, int POL, bool OWNER, int G = 8>
 __device__ __forceinline__ void onepass_any_range(T* const* s_tab, int N, int k, size_t base, float scale,
                                                   size_t len, unsigned long long zpos) {
   const size_t n_vec = len / VEC;
   for (size_t v = threadIdx.x; v < n_vec; v += kThreads)
-    onepass_any_one<T, VEC, POL, OWNER>(s_tab, N, k, base, scale, v, zpos);
+    onepass_any_one<T, VEC, POL, OWNER, G>(s_tab, N, k, base, scale, v, zpos);
   if constexpr (VEC > 1) {
     const size_t e = n_vec * VEC + threadIdx.x;
     if (e < len) onepass_any_one<T, 1, POL, OWNER>(s_tab, N, k, base, scale, e, zpos);
@@ -152,7 +153,8 @@ k_ring_onepass(PtrTable ring, SegTable seg, SegTable tile0, int N, float scale, 
         continue;
       }
     }
-    if (t.rem >= kTileElems) onepass_any_range<T, VEC, POL, OWNER>(s_tab, N, t.k, t.begin, scale, kTileElems, zpos);
+    // whole tiles of a ring of more than 16: all of a vector's loads in flight, up to 32
+    if (t.rem >= kTileElems) onepass_any_range<T, VEC, POL, OWNER, (NT == 0 && VEC > 1 ? 32 : 8)>(s_tab, N, t.k, t.begin, scale, kTileElems, zpos);
     else onepass_any_range<T, VEC, POL, OWNER>(s_tab, N, t.k, t.begin, scale, t.rem, zpos);
   }
 }
