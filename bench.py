@@ -802,18 +802,23 @@ def cu_budget_report(path, B, W, torch):
         plan.set_partition(part)
         acc = torch.empty(plan.acc_bytes // 4, dtype=torch.float32, device=dev)
         cells = []
-        for flags, stepwise in ((0, False), (B.FTAR_PERSIST_CHUNKS, False), (B.FTAR_PERSIST_CHUNKS | B.FTAR_PERSIST_PUBLISH, True)):
+        # ahead: how many rows the CPU keeps released beyond the progress it has seen (0: all at once)
+        for flags, ahead in ((0, 0), (B.FTAR_PERSIST_CHUNKS, 0), (B.FTAR_PERSIST_CHUNKS | B.FTAR_PERSIST_PUBLISH, 1),
+                             (B.FTAR_PERSIST_CHUNKS | B.FTAR_PERSIST_PUBLISH, 2), (B.FTAR_PERSIST_CHUNKS, 2)):
             units = plan.n_gate_units(flags)
 
             def run():
                 B.ftar_ring_persistent(plan, bufs, acc, ctrl, timeout_us=60_000_000, flags=flags)
-                if not stepwise:
+                if ahead == 0:
                     ctrl.release(units)
                 else:
-                    for u in range(units):
-                        ctrl.release(u + 1)
-                        while ctrl.progress() < u + 1:
-                            pass
+                    done = 0
+                    ctrl.release(min(units, ahead))
+                    while done < units:
+                        p = ctrl.progress()
+                        if p > done:
+                            done = p
+                            ctrl.release(min(units, done + ahead))
             run()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
@@ -830,10 +835,13 @@ def cu_budget_report(path, B, W, torch):
     out += ["", "## The chunk pipeline at the paper's chunk size", "",
             "16 x 1 Gi bf16 (%.0f GB per all-reduce), chunk S = 8 MB (4 Mi bf16 elements), partitions of S x C x N bytes "
             "(paper section 4.2), one persistent kernel, one workgroup per compute unit (two with partitions). Gate units: "
-            "slots (a whole step of a partition), or rows of chunks (FTAR_PERSIST_CHUNKS: C rows per step). Last column: a "
-            "CPU thread releases row u + 1 only after every workgroup has reported row u written back (PUBLISH)." % gb2, "",
-            "| C | partition | gated by slots, all released | gated by rows of chunks, all released | rows released one by one by the CPU |",
-            "|---|---|---|---|---|"] + pipe
+            "slots (a whole step of a partition), or rows of chunks (FTAR_PERSIST_CHUNKS: C rows per step). Last two columns: "
+            "a CPU thread releases row u + 1 only after every workgroup has reported row u written back (PUBLISH) - the "
+            "handshake fully exposed -, the same thread keeping two rows released beyond the progress it has seen, as a "
+            "pipeline with chunks in flight does, and that without PUBLISH (progress then means computed, not yet written "
+            "back from the L2)." % gb2, "",
+            "| C | partition | gated by slots, all released | gated by rows of chunks, all released | rows released one by one by the CPU (PUBLISH) | rows released two ahead of the progress (PUBLISH) | two ahead, without PUBLISH |",
+            "|---|---|---|---|---|---|---|"] + pipe
     with open(path, "w") as f:
         f.write("\n".join(out) + "\n")
 
