@@ -136,9 +136,10 @@ def all_configs_report(path, B, W, torch, np):
     def add_row(name, what, gbytes, med, mn, ok, cpu_gbs, cpu_note):
         verdict = "bit-exact" if ok else "MISMATCH"   # every row is a real comparison with the oracle on slabs
         cpu = "-" if cpu_note in ("-", "slabs") else "%.2f (%s)" % (cpu_gbs, cpu_note)
-        rows.append("| %s | %s | %.3f | %.1f | %.0f | %.1f | %.0f | %s | %s |" % (
-            name, what, gbytes, med * 1e6, gbytes / med, 100 * gbytes / med / HBM_PEAK_GBS,
-            gbytes / mn, verdict, cpu))
+        # bytes that are served by the caches are not a fraction of the HBM peak: no percentage for those rows
+        pct = "-" if "NOT an HBM fraction" in what else "%.1f" % (100 * gbytes / med / HBM_PEAK_GBS)
+        rows.append("| %s | %s | %.3f | %.1f | %.0f | %s | %.0f | %s | %s |" % (
+            name, what, gbytes, med * 1e6, gbytes / med, pct, gbytes / mn, verdict, cpu))
         print(rows[-1], file=sys.stderr, flush=True)
 
     cfgs = W.configs()
