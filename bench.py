@@ -235,6 +235,26 @@ def all_configs_report(path, B, W, torch, np):
             del out32
         del bufs, out
         torch.cuda.empty_cache()
+    # ---- beyond the five workloads: the paper's upper replica count (10 to 20) in the one-shot reduce ----
+    n20, mask20, count20 = 20, (1 << 20) - 1 - (1 << 7) - (1 << 13), 128 * W.M
+    bufs = [torch.empty(count20, dtype=torch.bfloat16, device=dev).normal_(0, 1e-3) for _ in range(n20)]
+    out = torch.empty(count20, dtype=torch.bfloat16, device=dev)
+    B.ftar_reduce_masked(bufs, mask20, out)
+    torch.cuda.synchronize()
+    ok, cpu_s, cpu_elems = True, 0.0, 0
+    for st in starts_for(count20, [], 20):
+        hb = [None if not (mask20 >> r) & 1 else W.to_numpy_bits(b[st:st + SLAB]) for r, b in enumerate(bufs)]
+        t0 = time.perf_counter()
+        want = oracle.reduce_masked(hb, mask20, code(torch.bfloat16))
+        cpu_s += time.perf_counter() - t0
+        cpu_elems += want.size
+        ok = ok and same(W.to_numpy_bits(out[st:st + SLAB]), want)
+    gb = (18 + 1) * 2 * count20 / 1e9
+    med, mn = time_schedule(lambda: B.ftar_reduce_masked(bufs, mask20, out), 20)
+    add_row("extra_20x128M_bf16_drop2", "ftar_reduce_masked, N=18 of 20 replicas (N(0, 1e-3); more than 16 sources: the generic kernel)",
+            gb, med, mn, ok, 19 * 2 * cpu_elems / cpu_s / 1e9, "%d elems" % cpu_elems)
+    del bufs, out
+    torch.cuda.empty_cache()
     # ---- ring: cfg 3a (clean 16-ring) and 3b (5 steps, replica 9 leaves, re-plan) ------
     w = cfgs[2]
     E = w.elem_bytes
