@@ -49,6 +49,7 @@ struct ScaleTable {
 // workgroup whose wait times out stores it into gpu_dead_epoch; the relay of every later kernel of
 // a dead epoch sees that before it passes on anything and tells its workers to leave.
 constexpr int kMaxPersistentBlocks = 1024;
+constexpr int kMaxXcds = 16;  // the hardware's XCC id has four bits
 constexpr int kCtrlCalls = 64;  // records in a control block: calls that may be in flight at once
 constexpr unsigned long long kGateCancel = 1ull << 63;  // in the mirror's gate word only
 
@@ -58,6 +59,11 @@ struct DevCtrl {  // device memory, zeroed on the stream before every launch
   unsigned int exited;          // workers that have left the kernel
   unsigned int min_unit;        // gate units finished by EVERY worker, maintained by the relay
   unsigned int align_count;     // arrivals at the soft barriers inside long steps (a performance hint only)
+  // Rows of chunks with FTAR_PERSIST_PUBLISH: one worker per XCD (its "leader") writes the XCD's L2 back
+  unsigned int xcd_workers[kMaxXcds];  // workers that run on XCD x (each registers before its first wait)
+  unsigned int xcd_min[kMaxXcds];      // gate units finished by every worker of XCD x, maintained by the relay
+  unsigned int xcd_done[kMaxXcds];     // ... and written back from that XCD's L2 by its leader
+  unsigned char worker_xcd[kMaxPersistentBlocks];  // the XCD worker b runs on
   unsigned int worker_unit[kMaxPersistentBlocks];  // gate units finished by worker b
 };
 

@@ -88,13 +88,20 @@ __global__ void k_clear_mirror(DevCtrl* m) {
 }
 
 // The relay block (all its lanes take part in the scan of the workers' progress words).
+// leaders: rows of chunks with FTAR_PERSIST_PUBLISH - the workers report a row without writing the L2
+// back themselves; the relay keeps one minimum per XCD, the XCD's leader writes its L2 back once for
+// everybody (xcd_done), and the progress the CPU sees is the minimum of what has been written back.
 __device__ __forceinline__ void relay_loop(Ctrl* ctrl, CallRec* rec, unsigned long long epoch, DevCtrl* mirror,
-                                           unsigned n_workers, unsigned long long max_spins, unsigned flags) {
+                                           unsigned n_workers, unsigned long long max_spins, unsigned flags,
+                                           bool leaders) {
   __shared__ unsigned s_min;
+  __shared__ unsigned s_min_x[kMaxXcds];
   __shared__ int s_last_round;
+  __shared__ int s_registered;
   unsigned long long last_gate = 0;
-  unsigned last_min = 0;
+  unsigned last_min = 0, last_pub = 0;
   bool first = true;
+  bool registered = !leaders;  // every worker has said which XCD it runs on (it does so before its first wait)
   // max_spins bounds one wait of one worker; every worker leaves after at most n_units such waits
   // plus its work, so the factor below is never reached: it only guarantees termination.
   for (unsigned long long spin = 0; spin < max_spins * 65536ull; ++spin) {
@@ -103,11 +110,17 @@ __device__ __forceinline__ void relay_loop(Ctrl* ctrl, CallRec* rec, unsigned lo
       // before it counts itself out, so the scan of the last round sees every final value
       s_last_round = __hip_atomic_load(&mirror->exited, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= n_workers;
       s_min = 0xffffffffu;
+      if (!registered) {
+        unsigned sum = 0;
+        for (int x = 0; x < kMaxXcds; ++x) sum += dev_load(&mirror->xcd_workers[x]);
+        registered = sum >= n_workers;
+      }
+      s_registered = registered;
       const unsigned long long d0 = sys_load(&ctrl->dead_epoch), d1 = sys_load(&ctrl->gpu_dead_epoch);
       const bool dead = (d0 > d1 ? d0 : d1) >= epoch;
       if (dead && first) {
         dev_store(&mirror->verdict, kVerdictSkipped);  // before any unit is passed on: nothing will run
-      } else {
+      } else if (registered || dead) {  // no unit is passed on before the per-XCD bookkeeping is complete
         unsigned long long g = sys_load(&rec->gate) & 0xffffffffull;
         if (dead) g |= kGateCancel;
         if (g != last_gate) {
@@ -117,28 +130,70 @@ __device__ __forceinline__ void relay_loop(Ctrl* ctrl, CallRec* rec, unsigned lo
       }
       first = false;
     }
+    if (threadIdx.x < static_cast<unsigned>(kMaxXcds)) s_min_x[threadIdx.x] = 0xffffffffu;
     __syncthreads();
+    const bool per_xcd = leaders && s_registered != 0;
     unsigned lo = 0xffffffffu;
     for (unsigned b = threadIdx.x; b < n_workers; b += kThreads) {
       const unsigned v = dev_load(&mirror->worker_unit[b]);
       lo = v < lo ? v : lo;
+      if (per_xcd) atomicMin(&s_min_x[dev_load(&mirror->worker_xcd[b]) % kMaxXcds], v);  // written once, before the worker's first wait
     }
     atomicMin(&s_min, lo);
     __syncthreads();
     const int last_round = s_last_round;
     if (threadIdx.x == 0) {
       const unsigned m = s_min;
+      unsigned pub = m;  // what the CPU may see
+      if (leaders) {
+        pub = per_xcd ? 0xffffffffu : 0u;
+        if (per_xcd) {
+          for (int x = 0; x < kMaxXcds; ++x) {
+            if (s_min_x[x] == 0xffffffffu) continue;  // nobody runs there
+            dev_store(&mirror->xcd_min[x], s_min_x[x]);
+            const unsigned d = dev_load(&mirror->xcd_done[x]);
+            pub = d < pub ? d : pub;
+          }
+          if (pub == 0xffffffffu) pub = 0u;
+        }
+      }
       if (m != last_min) {
-        if (flags & FTAR_PERSIST_PUBLISH) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        if (!leaders && (flags & FTAR_PERSIST_PUBLISH)) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         dev_store(&mirror->min_unit, m);
-        sys_store(&rec->progress, static_cast<unsigned long long>(m));
         last_min = m;
+      }
+      if (pub != last_pub) {
+        sys_store(&rec->progress, static_cast<unsigned long long>(pub));
+        last_pub = pub;
       }
       if (last_round) sys_store(&rec->ended, 1ull);  // after the final progress: the call is over
     }
     if (last_round) return;  // the same for every lane
     __builtin_amdgcn_s_sleep(8);
     __syncthreads();  // everybody has read s_last_round before lane 0 writes it again
+  }
+}
+
+// s_waitcnt vmcnt(0) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left
+// at their maxima): all of the wave's loads have returned and its stores have been taken by the L2.
+// A workgroup-scope release does not include it when the workgroup's waves share one compute unit.
+constexpr int kWaitVmcnt0 = 0x0F70;
+
+// The XCD this wave runs on (XCC_ID, bits 3:0 of hardware register 20 on gfx942 / gfx950).
+__device__ __forceinline__ unsigned xcd_of_this_wave() {
+  return __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20) & 0xfu;
+}
+
+// One lane of an XCD's leader: when every worker of the XCD has finished more units than have been
+// written back, write the XCD's L2 back (a release at agent scope does) and say so.  A write-back
+// serves the whole L2, whoever wrote the lines; 32 workers per XCD each doing their own cost 11 us
+// per row against nothing for one (a bare kernel with the same mix of streams).
+__device__ __forceinline__ void leader_duty(DevCtrl* mirror, unsigned xcd, unsigned* done) {
+  const unsigned v = dev_load(&mirror->xcd_min[xcd]);
+  if (v > *done) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    dev_store(&mirror->xcd_done[xcd], v);
+    *done = v;
   }
 }
 
@@ -149,6 +204,9 @@ struct WaitCtx {
   DevCtrl* mirror;
   unsigned long long epoch, timeout_ticks, max_spins;
   unsigned long long* s_word;  // LDS: what lane 0 saw
+  bool leader;                 // this worker writes its XCD's L2 back for everybody (see leader_duty), also while it waits
+  unsigned xcd;
+  unsigned* xcd_done;
 };
 
 // Records the verdict and counts the worker out (lane 0 only).
@@ -173,6 +231,7 @@ __device__ __forceinline__ bool wait_released(const WaitCtx& w, unsigned unit, u
       if ((g & kGateCancel) != 0) { seen = static_cast<unsigned long long>(kVerdictCancel) << 32; break; }
       if ((g & 0xffffffffull) > unit) { seen = g & 0xffffffffull; break; }
       if (static_cast<unsigned long long>(wall_clock64() - t0) > w.timeout_ticks) break;
+      if (w.leader) leader_duty(w.mirror, w.xcd, w.xcd_done);  // the CPU may be waiting for exactly this report
       __builtin_amdgcn_s_sleep(4);
     }
     *w.s_word = seen;
@@ -200,6 +259,7 @@ __device__ __forceinline__ bool wait_all_done(const WaitCtx& w, unsigned units, 
       const unsigned v = dev_load(&w.mirror->verdict);
       if (v != 0) { verdict = v; break; }
       if (static_cast<unsigned long long>(wall_clock64() - t0) > w.timeout_ticks) break;
+      if (w.leader) leader_duty(w.mirror, w.xcd, w.xcd_done);
       __builtin_amdgcn_s_sleep(4);
     }
     *w.s_word = verdict;
@@ -381,7 +441,7 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
   __shared__ ChunkTab s_chunk[CH ? 2 : 1];
   const unsigned n_workers = gridDim.x - 1;
   if (blockIdx.x == 0) {  // the first block (dispatched first, so always resident) is the relay
-    relay_loop(ctrl, rec, epoch, mirror, n_workers, max_spins, flags);
+    relay_loop(ctrl, rec, epoch, mirror, n_workers, max_spins, flags, CH && (flags & FTAR_PERSIST_PUBLISH) != 0);
     return;
   }
   const unsigned worker = blockIdx.x - 1;
@@ -400,7 +460,26 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
     if (tid == 64) build_chunk_tab(&s_chunk[1], s_seg[1], N, geom.chunk_elems, kTileElems);
     __syncthreads();
   }
-  const WaitCtx wc{ctrl, rec, mirror, epoch, timeout_ticks, max_spins, &s_word};
+  // Rows of chunks reported with FTAR_PERSIST_PUBLISH: say which XCD this worker runs on; the first
+  // one to register on an XCD is its leader (see leader_duty).  Before the first wait, so the relay
+  // has every worker's XCD before it passes on a single unit.
+  const bool leaders = CH && (flags & FTAR_PERSIST_PUBLISH) != 0;
+  unsigned xcd = 0, xcd_done = 0;
+  bool leader = false;
+  if (leaders) {
+    if (tid == 0) {
+      const unsigned x = xcd_of_this_wave();
+      dev_store(&mirror->worker_xcd[worker], static_cast<unsigned char>(x));
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // the relay reads it after it has seen the count
+      const unsigned before = __hip_atomic_fetch_add(&mirror->xcd_workers[x], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_word = static_cast<unsigned long long>(x) | (before == 0 ? 0x100ull : 0ull);
+    }
+    __syncthreads();
+    xcd = static_cast<unsigned>(s_word & 0xffull);
+    leader = (s_word & 0x100ull) != 0;
+    __syncthreads();  // everybody has read the word before a wait can write it again
+  }
+  const WaitCtx wc{ctrl, rec, mirror, epoch, timeout_ticks, max_spins, &s_word, leader, xcd, &xcd_done};
   const unsigned n_steps = static_cast<unsigned>(2 * N - 2);
   // gate units per step of a full partition and of the last one; a slot is one unit unless CH
   const unsigned rows_full = CH ? geom.rows_full : 1u, rows_last = CH ? geom.rows_last : 1u;
@@ -436,15 +515,17 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
           const unsigned unit = unit0 + t.row;
           if (unit != cur) {  // moving on to a later row: the rows before it are done
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            if (leaders) __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);  // every wave's stores have reached the L2
             __syncthreads();
             if (tid == 0) {
-              if (flags & FTAR_PERSIST_PUBLISH)
+              if ((flags & FTAR_PERSIST_PUBLISH) && !leaders)
                 __hip_atomic_store(&mirror->worker_unit[worker], unit, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-              else
+              else  // (with leaders: the stores are in the L2, the barrier's release saw to that)
                 dev_store(&mirror->worker_unit[worker], unit);
             }
             cur = unit;
           }
+          if (leader && tid == 0) leader_duty(mirror, xcd, &xcd_done);
           if (unit >= released && !wait_released(wc, unit, &released)) return;
           ring_one_tile<T, VEC, U, POL>(s_tab, N, step, t.k, t.begin, t.rem, acc, scale, off, zpos);
         }
@@ -490,13 +571,14 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
       const bool report = CH || done >= released || last_slot || (flags & FTAR_PERSIST_ALIGN) != 0 || hand_pub;
       if (report || step == N - 2) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        if (leaders) __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
         __syncthreads();
       }
       // With FTAR_PERSIST_PUBLISH the progress store is a release at agent scope: the data of the
       // units reported is written back from this XCD's L2 before the progress can be seen, which
       // is what a NIC reading the buffers on the CPU's signal would need.
       if (report && tid == 0) {
-        if ((flags & FTAR_PERSIST_PUBLISH) || hand_pub)  // the handover orders this block's reads of acc first
+        if (((flags & FTAR_PERSIST_PUBLISH) && !leaders) || hand_pub)  // the handover orders this block's reads of acc first
           __hip_atomic_store(&mirror->worker_unit[worker], done, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         else
           dev_store(&mirror->worker_unit[worker], done);
@@ -511,6 +593,18 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
         }
       }
       if (flags & FTAR_PERSIST_ALIGN) __syncthreads();
+    }
+  }
+  if (leader && tid == 0) {
+    // the leader stays until everything its XCD has written is out of the L2 (bounded like every wait)
+    const unsigned total_units = (geom.n_parts - 1) * units_full + n_steps * rows_last;
+    const long long t0 = wall_clock64();
+    for (unsigned long long spin = 0; spin < max_spins; ++spin) {
+      leader_duty(mirror, xcd, &xcd_done);
+      if (xcd_done >= total_units) break;
+      if (dev_load(&mirror->verdict) != 0 || (dev_load(&mirror->gate) & kGateCancel) != 0) break;
+      if (static_cast<unsigned long long>(wall_clock64() - t0) > timeout_ticks) break;
+      __builtin_amdgcn_s_sleep(4);
     }
   }
   if (tid == 0) __hip_atomic_fetch_add(&mirror->exited, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);

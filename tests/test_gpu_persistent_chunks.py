@@ -147,3 +147,51 @@ def test_cancel_inside_a_step_leaves_the_inputs_intact(B, oracle):
         assert_same(got[lo:lo + 3 * chunk], two[lo:lo + 3 * chunk], "portion %d, rows that ran step 1" % k)
         assert_same(got[lo + 3 * chunk:sb[k + 1]], one[lo + 3 * chunk:sb[k + 1]], "portion %d, rows that did not" % k)
     ctrl.destroy()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_rows_reported_with_publish_can_be_read_off_the_gpu_while_the_kernel_waits(B, oracle, dtype):
+    # FTAR_PERSIST_PUBLISH: a reported row has left the GPU's caches.  The kernel is held at the gate after the
+    # ReduceScatter phase; a copy engine on another stream then reads the owners' portions from memory (it does
+    # not look into any L2) and finds the phase's results; afterwards the AllGather phase is released.
+    n, mask, chunk = 8, 0xFF, 8192
+    rows = 12                                             # chunks per portion
+    count = n * chunk * rows
+    say("chunk rows with PUBLISH read by a copy while the kernel waits", dtype)
+    bufs = rand_bufs(n, count, dtype, seed=140, dist="student_t3", mask=mask)
+    orig = [host(b) for b in bufs]
+    want_rs = [o.copy() for o in orig]
+    oracle.ring_per_rank(want_rs, mask, chunk, code(dtype), rs_steps=n - 1, ag_steps=0)
+    plan = B.ftar_plan(n, mask, count, chunk, dtype)
+    flags = B.FTAR_PERSIST_CHUNKS | B.FTAR_PERSIST_PUBLISH
+    units = plan.n_gate_units(flags)
+    assert units == (2 * n - 2) * rows
+    acc = torch.empty(plan.acc_bytes // 4, dtype=torch.float32, device="cuda")
+    ctrl = B.ftar_ctrl_create()
+    side = torch.cuda.Stream()
+    pinned = [torch.empty(count, dtype=dtype).pin_memory() for _ in range(n)]
+    B.ftar_ring_persistent(plan, bufs, acc, ctrl, timeout_us=20_000_000, flags=flags)
+    try:
+        rs_units = (n - 1) * rows
+        ctrl.release(rs_units)
+        t0 = time.time()
+        while ctrl.progress() < rs_units:
+            assert time.time() - t0 < 10.0, "ReduceScatter phase not reported"
+            time.sleep(0.0002)
+        assert ctrl.progress() == rs_units                 # the kernel now waits for the AllGather phase
+        with torch.cuda.stream(side):
+            for r in range(n):
+                pinned[r].copy_(bufs[r], non_blocking=True)
+        side.synchronize()
+        for k in range(plan.n_live):
+            b, e, owner = plan.segment(k)
+            got = host(pinned[owner])
+            assert_same(got[b:e], want_rs[owner][b:e], "portion %d in its owner %d, read while the kernel waits" % (k, owner))
+    finally:
+        ctrl.release(units)
+        torch.cuda.synchronize()
+    assert ctrl.result() == (B.FTAR_OK, units)
+    want = oracle.ring_closed_form(orig, mask, count, chunk, code(dtype))
+    for r in range(n):
+        assert_same(host(bufs[r]), want, "buf %d" % r)
+    ctrl.destroy()
