@@ -335,8 +335,8 @@ ftar_status_t ftar_allreduce_onepass(const ftar_plan_t* plan, void* const* bufs,
  *   flags       FTAR_PERSIST_PUBLISH: a unit counts as done (ftar_ctrl_progress) only after its
  *               data has been written back from the GPU's L2, as a NIC reading the buffers on
  *               the CPU's signal would need; without it progress means "computed", and the data
- *               is guaranteed visible off the GPU once the stream has been synchronised.  (With
- *               FTAR_PERSIST_CHUNKS one workgroup per XCD writes that XCD's L2 back for all of them.)
+ *               is guaranteed visible off the GPU once the stream has been synchronised.  (One
+ *               workgroup per XCD writes that XCD's L2 back for all the workgroups that run there.)
  *               FTAR_PERSIST_ALIGN: workgroups that ran ahead wait (bounded) for the others after
  *               every step and, inside a step, after every 256 Mi elements (not with
  *               FTAR_PERSIST_CHUNKS); a performance hint for long steps, never needed for correctness.

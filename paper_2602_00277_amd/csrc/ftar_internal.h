@@ -59,7 +59,7 @@ struct DevCtrl {  // device memory, zeroed on the stream before every launch
   unsigned int exited;          // workers that have left the kernel
   unsigned int min_unit;        // gate units finished by EVERY worker, maintained by the relay
   unsigned int align_count;     // arrivals at the soft barriers inside long steps (a performance hint only)
-  // Rows of chunks with FTAR_PERSIST_PUBLISH: one worker per XCD (its "leader") writes the XCD's L2 back
+  // FTAR_PERSIST_PUBLISH: one worker per XCD (its "leader") writes the XCD's L2 back
   unsigned int xcd_workers[kMaxXcds];  // workers that run on XCD x (each registers before its first wait)
   unsigned int xcd_min[kMaxXcds];      // gate units finished by every worker of XCD x, maintained by the relay
   unsigned int xcd_done[kMaxXcds];     // ... and written back from that XCD's L2 by its leader

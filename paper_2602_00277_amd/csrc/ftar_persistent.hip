@@ -88,7 +88,7 @@ __global__ void k_clear_mirror(DevCtrl* m) {
 }
 
 // The relay block (all its lanes take part in the scan of the workers' progress words).
-// leaders: rows of chunks with FTAR_PERSIST_PUBLISH - the workers report a row without writing the L2
+// leaders: FTAR_PERSIST_PUBLISH - the workers report a unit without writing the L2
 // back themselves; the relay keeps one minimum per XCD, the XCD's leader writes its L2 back once for
 // everybody (xcd_done), and the progress the CPU sees is the minimum of what has been written back.
 __device__ __forceinline__ void relay_loop(Ctrl* ctrl, CallRec* rec, unsigned long long epoch, DevCtrl* mirror,
@@ -441,7 +441,7 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
   __shared__ ChunkTab s_chunk[CH ? 2 : 1];
   const unsigned n_workers = gridDim.x - 1;
   if (blockIdx.x == 0) {  // the first block (dispatched first, so always resident) is the relay
-    relay_loop(ctrl, rec, epoch, mirror, n_workers, max_spins, flags, CH && (flags & FTAR_PERSIST_PUBLISH) != 0);
+    relay_loop(ctrl, rec, epoch, mirror, n_workers, max_spins, flags, (flags & FTAR_PERSIST_PUBLISH) != 0);
     return;
   }
   const unsigned worker = blockIdx.x - 1;
@@ -460,10 +460,10 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
     if (tid == 64) build_chunk_tab(&s_chunk[1], s_seg[1], N, geom.chunk_elems, kTileElems);
     __syncthreads();
   }
-  // Rows of chunks reported with FTAR_PERSIST_PUBLISH: say which XCD this worker runs on; the first
+  // FTAR_PERSIST_PUBLISH: say which XCD this worker runs on; the first
   // one to register on an XCD is its leader (see leader_duty).  Before the first wait, so the relay
   // has every worker's XCD before it passes on a single unit.
-  const bool leaders = CH && (flags & FTAR_PERSIST_PUBLISH) != 0;
+  const bool leaders = (flags & FTAR_PERSIST_PUBLISH) != 0;
   unsigned xcd = 0, xcd_done = 0;
   bool leader = false;
   if (leaders) {
@@ -574,9 +574,10 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
         if (leaders) __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
         __syncthreads();
       }
-      // With FTAR_PERSIST_PUBLISH the progress store is a release at agent scope: the data of the
-      // units reported is written back from this XCD's L2 before the progress can be seen, which
-      // is what a NIC reading the buffers on the CPU's signal would need.
+      // With FTAR_PERSIST_PUBLISH the data of the units reported is written back from the XCD's L2
+      // before the CPU can see the progress, which is what a NIC reading the buffers on the CPU's
+      // signal would need: the workers' stores have reached the L2 (vmcnt(0) above), the XCD's
+      // leader writes the L2 back for all of them (leader_duty).
       if (report && tid == 0) {
         if (((flags & FTAR_PERSIST_PUBLISH) && !leaders) || hand_pub)  // the handover orders this block's reads of acc first
           __hip_atomic_store(&mirror->worker_unit[worker], done, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
@@ -592,6 +593,7 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
           }
         }
       }
+      if (leader && tid == 0) leader_duty(mirror, xcd, &xcd_done);
       if (flags & FTAR_PERSIST_ALIGN) __syncthreads();
     }
   }
