@@ -28,7 +28,8 @@ extern "C" {
  * flags: 0 = each kernel's defaults.
  *   0x10 | p      explicit cache policy p: bit 0 non-temporal loads, bit 1 non-temporal stores
  *   0x20          wide tiles in the one-shot reduce
- *   0x40          one launch, however long the call (one-shot reduce, big buckets, ring steps)
+ *   0x40          one launch, however long the call (one-shot reduce, big buckets, ring steps); no soft
+ *                 barriers inside the long steps of the persistent ring
  *   0x80          no write windows in the many-source reductions
  *   bits 8..11    vectors per lane and tile in the ring step kernels (2, 4 or 8)
  *   bits 12..15   log2 of the write-window period in 10 ns ticks; bits 16..19: log2(period / window)
@@ -36,7 +37,8 @@ extern "C" {
  *                 or five sources, below 256 MiB)
  *   0x200000      bf16 ReduceScatter lanes take 8 elements (16-byte loads, two partial-sum vectors)
  *   0x400000      the persistent ring keeps its small tile also with few workgroups
- *   bits 24..27   log2 of the MiB of traffic per launch of a long ring step */
+ *   bits 24..27   log2 of the MiB of traffic per launch of a long ring step; in the persistent ring, log2 of
+ *                 the Mi elements between two soft barriers inside a long step */
 void ftar_set_tuning(int blocks_per_cu, int flags);
 
 /* Measurement only: arms two hipEvent_t (passed as void*, either may be NULL) for the NEXT kernel
