@@ -197,6 +197,15 @@ __device__ __forceinline__ void leader_duty(DevCtrl* mirror, unsigned xcd, unsig
   }
 }
 
+// A worker counts itself out (one lane).  Its last progress word and verdict must be there before the
+// count: waiting for this wave's own stores does that.  A release at agent scope would also write the
+// XCD's L2 back, once per worker - 32 write-backs per XCD that the L2 serves one after the other
+// (about 11 us in all) for data that the end of the kernel writes back anyway.
+__device__ __forceinline__ void count_out(DevCtrl* mirror) {
+  __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+  __hip_atomic_fetch_add(&mirror->exited, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // What a worker needs to wait and to leave.
 struct WaitCtx {
   Ctrl* ctrl;
@@ -215,7 +224,7 @@ __device__ __forceinline__ void leave(const WaitCtx& w, unsigned verdict, unsign
   if (verdict == kVerdictTimeout) sys_store(&w.ctrl->gpu_dead_epoch, w.epoch);  // calls queued behind this one are skipped
   sys_store(&w.rec->blocked_unit, static_cast<unsigned long long>(unit));
   sys_store(&w.rec->status, static_cast<unsigned long long>(verdict));
-  __hip_atomic_fetch_add(&w.mirror->exited, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+  count_out(w.mirror);
 }
 
 // Block-wide, bounded wait until gate unit `unit` is released.  Returns true to go on (*released is
@@ -609,7 +618,7 @@ k_ring_persistent(PtrTable ring, PartGeom geom, SegTable tile_full, SegTable til
       __builtin_amdgcn_s_sleep(4);
     }
   }
-  if (tid == 0) __hip_atomic_fetch_add(&mirror->exited, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+  if (tid == 0) count_out(mirror);
 }
 
 template <typename T, int VEC>
