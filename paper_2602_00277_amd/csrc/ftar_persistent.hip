@@ -169,7 +169,7 @@ __device__ __forceinline__ void relay_loop(Ctrl* ctrl, CallRec* rec, unsigned lo
       if (last_round) sys_store(&rec->ended, 1ull);  // after the final progress: the call is over
     }
     if (last_round) return;  // the same for every lane
-    __builtin_amdgcn_s_sleep(8);
+    __builtin_amdgcn_s_sleep(1);
     __syncthreads();  // everybody has read s_last_round before lane 0 writes it again
   }
 }
