@@ -192,3 +192,18 @@ def test_bucketed_more_than_one_launch_and_many_replicas(B, oracle):
     with pytest.raises(B.FtarError) as e:
         B.ftar_reduce_masked_bucketed(bufs, [0] + masks[1:], bucket_elems, out)
     assert e.value.status == B.FTAR_ERR_NO_LIVE
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+@pytest.mark.parametrize("n,mask", [(7, 0b1110111), (8, 0xFF), (20, (1 << 20) - 1 - (1 << 7) - (1 << 13)), (40, (1 << 40) - 1 - (1 << 33))])
+def test_outputs_large_enough_for_the_default_write_windows(B, oracle, dtype, n, mask):
+    # with no tuning at all an output of 16 MiB or more from six or more sources goes through the kernels that
+    # stage their results (up to 16 sources specialised, beyond that the generic one): several stage-fulls per
+    # workgroup, leftover vectors and a ragged tail
+    count = (16 << 20) // (4 if dtype == torch.float32 else 2) + 256 * 8 * 3 + 21
+    say("reduce_masked, default write windows", dtype, n, hex(mask), count)
+    bufs = rand_bufs(n, count, dtype, seed=70 + n, dist="student_t3", mask=mask)
+    out = torch.empty(count, dtype=dtype, device="cuda")
+    B.ftar_reduce_masked(bufs, mask, out)
+    torch.cuda.synchronize()
+    assert_same(host(out), oracle.reduce_masked([host(b) for b in bufs], mask, code(dtype)), "n=%d" % n)
