@@ -207,3 +207,28 @@ def test_outputs_large_enough_for_the_default_write_windows(B, oracle, dtype, n,
     B.ftar_reduce_masked(bufs, mask, out)
     torch.cuda.synchronize()
     assert_same(host(out), oracle.reduce_masked([host(b) for b in bufs], mask, code(dtype)), "n=%d" % n)
+
+
+@pytest.mark.parametrize("dtype", DTYPES, ids=["f32", "bf16"])
+@pytest.mark.parametrize("n,p_live", [(8, 0.9), (20, 0.9), (20, 0.5)])
+def test_bucketed_outputs_large_enough_for_the_default_write_windows(B, oracle, dtype, n, p_live):
+    # the bucketed kernel that stages its results, as the library picks it by itself: buckets that end inside a
+    # tile, buckets with more than 16 live replicas (the generic sum) next to buckets with fewer
+    from paper_2602_00277_amd import workloads as W
+    count = (16 << 20) // (4 if dtype == torch.float32 else 2) + 12345
+    bucket_elems = 1_000_000 + 8 * 37
+    n_buckets = (count + bucket_elems - 1) // bucket_elems
+    masks = W.bucket_masks(n, n_buckets, p_live, seed=n)
+    masks[1] = (1 << n) - 1                               # everybody live
+    masks[2] = 1 << (n - 1)                               # one live replica
+    say("bucketed, default write windows", dtype, n, p_live, count, n_buckets)
+    bufs = rand_bufs(n, count, dtype, seed=80 + n, dist="student_t3")
+    hb = [host(b) for b in bufs]
+    out = torch.empty(count, dtype=dtype, device="cuda")
+    B.ftar_reduce_masked_bucketed(bufs, masks, bucket_elems, out)
+    torch.cuda.synchronize()
+    got = host(out)
+    for b in range(n_buckets):
+        lo, hi = b * bucket_elems, min(count, (b + 1) * bucket_elems)
+        want = oracle.reduce_masked([h[lo:hi].copy() for h in hb], masks[b], code(dtype))
+        assert_same(got[lo:hi], want, "bucket %d mask %s" % (b, bin(masks[b])))
