@@ -37,7 +37,7 @@ extern "C" {
  *                 or five sources, below 256 MiB)
  *   0x200000      bf16 ReduceScatter lanes take 8 elements (16-byte loads, two partial-sum vectors)
  *   0x400000      the persistent ring keeps its small tile also with few workgroups
- *   bits 24..27   log2 of the MiB of traffic per launch of a long ring step; in the persistent ring, log2 of
+ *   bits 24..27   traffic per launch of a long ring step in units of 256 MiB; in the persistent ring, log2 of
  *                 the Mi elements between two soft barriers inside a long step */
 void ftar_set_tuning(int blocks_per_cu, int flags);
 

@@ -221,18 +221,21 @@ struct RingAllgatherAll {
   }
 };
 
-// A long step goes out as several launches, each over a run of the flat tile sequence of about
-// 1 GiB of traffic (half of that for the AllGather copy; 8 x 2e9 bf16: middle step 5.7 -> 6.4 TB/s,
-// AllGather 5.1 -> 5.9): the workgroups of a launch never wait for each other and drift apart
-// over gigabytes (as in the one-shot reduce); the end of a launch brings them together again.
-// Tuning flag 0x40 forces one launch; bits 24..27 = log2 of the MiB per launch, for measurement.
-// A timed call brackets the whole series.
-constexpr size_t kRingLaunchBytes = static_cast<size_t>(1) << 30;
+// A long step goes out as several launches, each over a run of the flat tile sequence of 1.25 GiB
+// of traffic (512 MiB for the AllGather copy; 8 x 2e9 bf16: middle step 5.7 -> 6.45 TB/s, AllGather
+// 5.1 -> 5.95; 0.5 / 0.75 / 1 / 1.25 / 1.5 / 2 GiB per launch give the middle step 6.36 / 6.41 /
+// 6.42 / 6.46 / 6.37 / 6.32 TB/s and the copy 5.95 / 5.82 / 5.60 / 5.6 / 5.5 / 5.2): the workgroups
+// of a launch never wait for each other and drift apart over gigabytes (as in the one-shot
+// reduce); the end of a launch brings them together again.  Tuning flag 0x40 forces one launch;
+// bits 24..27 = traffic per launch in units of 256 MiB, for measurement.  A timed call brackets
+// the whole series.
+constexpr size_t kRingLaunchBytes = static_cast<size_t>(1280) << 20;
+constexpr size_t kCopyLaunchBytes = static_cast<size_t>(512) << 20;
 
 template <typename F>
 void for_tile_runs(size_t n_tiles, size_t tile_bytes, size_t launch_bytes, F f) {
   const int lg = (current_tuning().flags >> 24) & 0xf;
-  size_t per = (lg ? (static_cast<size_t>(1) << (20 + lg)) : launch_bytes) / tile_bytes;
+  size_t per = (lg ? (static_cast<size_t>(lg) << 28) : launch_bytes) / tile_bytes;
   if (per < 1) per = 1;
   if ((current_tuning().flags & 0x40) != 0 || n_tiles <= per + per / 2) per = n_tiles;
   hipEvent_t t_start = nullptr, t_stop = nullptr;
@@ -283,7 +286,7 @@ struct RingAllgather {
   template <int U, int POL> void go(unsigned blocks) const {
     const SegTable tiles = ring_tiles(seg, N, VEC, U);
     const size_t elems = static_cast<size_t>(kThreads) * U * VEC;
-    for_tile_runs(tiles.begin[N], elems * 2 * sizeof(T), kRingLaunchBytes / 2, [&](size_t g0, size_t g1) {
+    for_tile_runs(tiles.begin[N], elems * 2 * sizeof(T), kCopyLaunchBytes, [&](size_t g0, size_t g1) {
       const dim3 grid(grid_x_for(g1 - g0, blocks)), block(kThreads);
       launch(k_ring_allgather<T, VEC, U, POL>, grid, block, stream, ring, seg, tiles, N, step, g0, g1);
     });
