@@ -1,6 +1,7 @@
 """GPU: seeded random draws over the whole option space - element type, group size and mask,
 zero-gradient participants, divisor policy, sum or mean, chunk size, ragged count, pointer
-alignment, partition size, worker budget - every ring path and the one-shot reduce against the
+alignment, partition size, worker budget, gate unit (slots or rows of chunks), reporting and
+alignment flags, release pattern - every ring path and the one-shot reduce against the
 oracle, bit-exact."""
 import os
 
@@ -49,7 +50,7 @@ def _draw(rng):
         if rng.random() < 0.5:
             part = max(8, part // 8 * 8)
     workers = int(rng.choice([1, 3, 16, 200]))
-    flags = int(rng.choice([0, 0, 1, 2, 3]))
+    flags = int(rng.choice([0, 0, 1, 2, 3, 4, 5, 6, 7]))             # PUBLISH 1, ALIGN 2, CHUNKS 4
     release = str(rng.choice(["all", "all", "batches", "each"]))
     return dict(flags=flags, release=release, n=n, live=live, zmask=zmask, contributors_only=contributors_only, sum_only=sum_only,
                 chunk=chunk, count=count, dtype=dtype, offset=offset, part=part, workers=workers)
@@ -144,11 +145,15 @@ def test_random_option_draw(B, oracle, seed):
                 plan.set_partition(c["part"])
                 ref = np.concatenate([_ring_reference(oracle, orig, c, lo, min(count, lo + c["part"]))
                                       for lo in range(0, count, c["part"])])
-            B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=c["workers"], timeout_us=10_000_000,
-                                   flags=c["flags"])
-            _release(ctrl, plan.n_slots, c["release"], rng)
+            flags = c["flags"]
+            if flags & B.FTAR_PERSIST_CHUNKS and count // c["chunk"] > 3000:
+                flags &= 3                                  # rows of one or three elements by the ten thousand: slots then
+            units = plan.n_gate_units(flags)
+            assert units > 0 or plan.n_live < 2                 # a ring of one has no steps
+            B.ftar_ring_persistent(plan, bufs, acc, ctrl, n_blocks=c["workers"], timeout_us=10_000_000, flags=flags)
+            _release(ctrl, units, c["release"], rng)
             torch.cuda.synchronize()
-            assert ctrl.result() == (B.FTAR_OK, plan.n_slots), name
+            assert ctrl.result() == (B.FTAR_OK, units), name
         torch.cuda.synchronize()
         for r in range(n):
             assert_same(host(bufs[r]), ref if (live >> r) & 1 else orig[r], "%s buf %d" % (name, r))
