@@ -3,6 +3,8 @@ bench.py times.  Outputs are compared bit for bit with the CPU oracle on sampled
 (always including the first and last elements, portion / bucket boundaries and the places
 where 32-bit offsets would overflow); workloads the oracle finishes in about a second are
 compared on every element."""
+import time
+
 import numpy as np
 import pytest
 import torch
@@ -248,6 +250,34 @@ def test_cfg3a_every_other_ring_path_at_full_size(B, oracle):
     B.ftar_allgather_all(plan, bufs)
     torch.cuda.synchronize()
     _cfg3a_check(oracle, w, bufs, orig, starts, 0, "RS steps + allgather-all")
+    plan.destroy()
+    # (e) the persistent ring gated by rows of 8 MB chunks (the paper's chunk size: four rows per step, the
+    # same portions), reported written back (PUBLISH: one workgroup per XCD writes its L2 back for all), the
+    # CPU keeping two rows released beyond the progress it has seen
+    say(w.name, "persistent ring, rows of 8 MB chunks, PUBLISH, released two rows ahead")
+    fresh()
+    big_chunk = 4 * W.M
+    assert oracle.geometry(n, mask, count, big_chunk) == sb
+    plan = B.ftar_plan(n, mask, count, big_chunk, w.dtype)
+    flags = B.FTAR_PERSIST_CHUNKS | B.FTAR_PERSIST_PUBLISH
+    units = plan.n_gate_units(flags)
+    assert units == 30 * 4
+    ctrl = B.ftar_ctrl_create()
+    B.ftar_ring_persistent(plan, bufs, acc, ctrl, timeout_us=20_000_000, flags=flags)
+    done, t0 = 0, time.time()
+    ctrl.release(2)
+    while done < units:
+        p = ctrl.progress()
+        if p > done:
+            done = p
+            ctrl.release(min(units, done + 2))
+        assert time.time() - t0 < 30.0, "progress stuck at %d of %d" % (done, units)
+    torch.cuda.synchronize()
+    assert ctrl.result() == (B.FTAR_OK, units)
+    _cfg3a_check(oracle, w, bufs, orig, starts, 0, "persistent ring by rows of chunks")
+    for r in range(1, n):
+        assert torch.equal(bufs[r].view(torch.int16), live0.view(torch.int16)), r
+    ctrl.destroy()
     plan.destroy()
 
 
