@@ -75,3 +75,51 @@ def test_graph_replays_equal_eager(B, oracle, dtype):
         got = snapshot()
         for i, (g, e) in enumerate(zip(got, eager)):
             assert_same(g, e, "replay %d output %d" % (replay, i))
+
+
+def test_graph_replays_of_the_kernels_with_write_windows(B, oracle):
+    # outputs of 16 MiB and more from six or more sources go through the kernels that stage their results and
+    # write them out by the wall clock: when the stores happen differs from replay to replay, the bits must not
+    n, live = 8, 0b11110111
+    count = (16 << 20) // 2 + 256 * 8 * 5 + 11
+    say("graph capture, write windows")
+    bufs = rand_bufs(n, count, torch.bfloat16, seed=78, dist="student_t3", mask=live)
+    orig = [host(b) for b in bufs]
+    bucket = 1_000_000 + 24
+    n_buckets = (count + bucket - 1) // bucket
+    masks = [live if b % 3 else 0b01010111 for b in range(n_buckets)]
+    one_shot = torch.empty(count, dtype=torch.bfloat16, device="cuda")
+    bucketed = torch.empty(count, dtype=torch.bfloat16, device="cuda")
+    wide = torch.empty(count, dtype=torch.float32, device="cuda")
+
+    def enqueue():
+        B.ftar_reduce_masked(bufs, live, one_shot)
+        B.ftar_reduce_masked_bucketed(bufs, masks, bucket, bucketed)
+        B.ftar_reduce_masked_ex(bufs, live, wide)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [host(t).copy() for t in (one_shot, bucketed, wide)]
+
+    enqueue()
+    eager = snapshot()
+    assert_same(eager[0], oracle.reduce_masked(orig, live, code(torch.bfloat16)), "one-shot")
+    for b, m in enumerate(masks):
+        lo, hi = b * bucket, min(count, (b + 1) * bucket)
+        assert_same(eager[1][lo:hi], oracle.reduce_masked([o[lo:hi].copy() if o is not None else None for o in orig], m,
+                                                          code(torch.bfloat16)), "bucket %d" % b)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            enqueue()
+    torch.cuda.current_stream().wait_stream(side)
+    for replay in range(3):
+        for t in (one_shot, bucketed, wide):
+            t.fill_(float(replay + 1))
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for i, (g, e) in enumerate(zip(got, eager)):
+            assert_same(g, e, "replay %d output %d" % (replay, i))
